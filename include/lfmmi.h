@@ -1,0 +1,165 @@
+/*
+ * lfmmi.h - C ABI of the MI355X (gfx950) LF-MMI forward-backward library.
+ *
+ * The library computes, for a batch of unequal-length sequences, the HMM
+ * forward-backward over a graph shared by the batch (denominator) or over one
+ * graph per sequence (numerators): the per-sequence log-likelihood
+ * log P(X | G) of Eq. 2 and the pdf occupancies gamma of Eq. 3, which are the
+ * derivative of that log-likelihood with respect to the network output.
+ *
+ * Model (Section 3.3, Section 3.4 / Algorithm 1):
+ *   an arc goes from state src to state dst, emits pdf-id pdf and has
+ *   probability w = exp(logw); frame t of a sequence multiplies an arc by
+ *   exp(logits[b, t, pdf]); a graph has initial probabilities init_prob[s]
+ *   (a unique initial state is the one-hot case) and final probabilities
+ *   final_prob[s], applied at the sequence's own last frame. The leaky HMM the
+ *   paper refers to is taken as: at t = 0 and after every frame each state s
+ *   additionally receives leak * (total mass) * init_prob[s].
+ *
+ * Conventions: every function returns an lfmmi_status (never throws, never
+ * aborts); on failure lfmmi_last_error() describes the reason (thread-local).
+ * Inputs are never modified. "HOST" / "DEVICE" says where a pointer lives.
+ */
+#ifndef LFMMI_H
+#define LFMMI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lfmmi_graph lfmmi_graph; /* opaque; owns host and device copies */
+
+typedef enum {
+    LFMMI_OK = 0,
+    LFMMI_ERR_INVALID_ARG = 1, /* null pointer, negative size, shape mismatch   */
+    LFMMI_ERR_BAD_GRAPH = 2,   /* state / pdf id out of range, non-finite weight */
+    LFMMI_ERR_OOM = 3,         /* host or device allocation failed               */
+    LFMMI_ERR_HIP = 4,         /* a HIP runtime call failed (no GPU, launch...)  */
+    LFMMI_ERR_UNSUPPORTED = 5  /* size beyond what the kernels hold in LDS       */
+} lfmmi_status;
+
+/*
+ * Graph packing (Section 3.3: the transition list sorted by from-state and by
+ * to-state with per-state index ranges; here three sliced-ELL orderings -
+ * by to-state, by from-state, by pdf-id - built once on the host).
+ *
+ * All pointers HOST, copied. Arcs in any order, duplicates allowed.
+ *   src, dst [num_arcs] in [0, num_states); pdf [num_arcs] in [0, num_pdfs);
+ *   logw [num_arcs] natural-log weight, finite (drop an arc instead of -inf);
+ *   init_prob, final_prob [num_states] linear, >= 0, finite, not normalised.
+ * Limits: num_states <= 16320, num_pdfs <= 16384 (LDS residency), else
+ * LFMMI_ERR_UNSUPPORTED. num_arcs may be 0.
+ * lfmmi_graph_create packs and uploads to the current HIP device.
+ * lfmmi_graph_pack only packs (no HIP call): for host-side inspection; such a
+ * handle is refused by lfmmi_forward_backward until lfmmi_graph_upload.
+ */
+lfmmi_status lfmmi_graph_create(int32_t num_states, int32_t num_pdfs, int64_t num_arcs,
+                                const int32_t *src, const int32_t *dst,
+                                const int32_t *pdf, const float *logw,
+                                const float *init_prob, const float *final_prob,
+                                lfmmi_graph **out);
+lfmmi_status lfmmi_graph_pack(int32_t num_states, int32_t num_pdfs, int64_t num_arcs,
+                              const int32_t *src, const int32_t *dst,
+                              const int32_t *pdf, const float *logw,
+                              const float *init_prob, const float *final_prob,
+                              lfmmi_graph **out);
+
+/*
+ * n graphs in one handle (Section 3.3, the batch of numerator graphs; ragged
+ * offsets instead of zero padding). Graph g owns states
+ * [state_off[g], state_off[g+1]) of init_prob / final_prob and arcs
+ * [arc_off[g], arc_off[g+1]); src / dst are local to the graph
+ * (0 .. its state count - 1). All graphs share num_pdfs.
+ */
+lfmmi_status lfmmi_graph_create_batch(int32_t n, int32_t num_pdfs,
+                                      const int64_t *state_off, const int64_t *arc_off,
+                                      const int32_t *src, const int32_t *dst,
+                                      const int32_t *pdf, const float *logw,
+                                      const float *init_prob, const float *final_prob,
+                                      lfmmi_graph **out);
+lfmmi_status lfmmi_graph_pack_batch(int32_t n, int32_t num_pdfs,
+                                    const int64_t *state_off, const int64_t *arc_off,
+                                    const int32_t *src, const int32_t *dst,
+                                    const int32_t *pdf, const float *logw,
+                                    const float *init_prob, const float *final_prob,
+                                    lfmmi_graph **out);
+lfmmi_status lfmmi_graph_upload(lfmmi_graph *graph);
+/* Frees host and device memory, including the cached workspace. NULL is a no-op.
+ * Synchronises the device. */
+void lfmmi_graph_destroy(lfmmi_graph *graph);
+
+/*
+ * Batched forward-backward (Algorithm 1 and its mirrored backward pass; Eq. 3).
+ *
+ *   graph    one graph (shared by all sequences) or a batch handle with n == B
+ *            (graph b goes with sequence b).
+ *   logits   DEVICE, float32 [B, T, P] row-major contiguous; rows t >= lengths[b]
+ *            are never read.
+ *   lengths  HOST, int32 [B], 0 <= lengths[b] <= T, any order.
+ *   P        must equal the graph's num_pdfs.
+ *   leak     leaky-HMM coefficient >= 0 (0 = plain HMM).
+ *   objf     DEVICE float32 [B]:      objf[b]      (=|+=) grad_scale * log Z_b
+ *   grad     DEVICE float32 [B, T, P]: grad[b,t,:] (=|+=) grad_scale * gamma_t
+ *            accumulate == 0 overwrites (rows t >= lengths[b] become 0),
+ *            accumulate != 0 adds (those rows are left alone). The full
+ *            objective of Eq. 2 / Eq. 3 is: numerators with (+1, 0), then the
+ *            denominator with (-1, 1).
+ *   status   DEVICE int32 [B] or NULL: 0 ok; bit 0: zero total probability
+ *            (log Z = -inf, gamma rows 0); bit 1: a non-finite logit was read
+ *            (objf NaN, gamma rows 0).
+ *   hip_stream  hipStream_t (NULL = default stream). The call only enqueues
+ *            work; it does not synchronise. It may allocate (and so
+ *            synchronise) when the handle's cached workspace has to grow.
+ * B == 0 or T == 0 with all lengths 0 are valid. Calls on one handle must be
+ * ordered on one stream (they share the handle's workspace).
+ */
+lfmmi_status lfmmi_forward_backward(const lfmmi_graph *graph, const float *logits,
+                                    const int32_t *lengths, int32_t B, int32_t T,
+                                    int32_t P, float leak, float grad_scale,
+                                    int accumulate, float *objf, float *grad,
+                                    int32_t *status, void *hip_stream);
+
+/* Thread-local description of the last failure on this thread ("" if none). */
+const char *lfmmi_last_error(void);
+
+/* ---- introspection (host side; used by tests and the benchmark) ---------- */
+
+enum { LFMMI_ORD_FWD = 0, LFMMI_ORD_BWD = 1, LFMMI_ORD_OCC = 2 };
+
+/* info[0] number of graphs, [1] num_pdfs, [2] total states, [3] total arcs,
+ * [4] waves per workgroup of the recursion kernel, [5] waves of the occupancy
+ * kernel, [6] 1 if uploaded, [7] workspace bytes currently held. */
+lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
+
+/* Packed ordering `ord` of graph `g`: info[0] rows, [1] slices (64 rows each),
+ * [2] waves, [3] total slots (sum of slice widths), [4] max slots of one wave. */
+lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
+                                       int32_t ord, int64_t info[8]);
+/* Copies the packed ordering out (any pointer may be NULL):
+ *   slice_off  [slices + 1] first slot of each slice
+ *   wave_first [waves + 1]  first slice of each wave
+ *   key, w     [total slots * 64] arc records, lane-minor; key = x-index * 4 in
+ *              the low 16 bits, y-index * 4 in the high 16 bits; padding has w 0
+ *   row_id     [slices * 64] the state (FWD: to-state, BWD: from-state) or
+ *              pdf-id (OCC) a row stands for, -1 for padding rows
+ *   x-index / y-index: FWD (from-state in FWD numbering, pdf), BWD (to-state in
+ *   BWD numbering, pdf), OCC (from-state in FWD numbering, to-state in BWD
+ *   numbering), where a state's number in an ordering is the row it owns. */
+lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph *graph, int32_t g, int32_t ord,
+                                       int32_t *slice_off, int32_t *wave_first,
+                                       uint32_t *key, float *w, int32_t *row_id);
+
+/* Per-kernel timing with HIP events on the caller's stream. enable != 0 makes
+ * every following lfmmi_forward_backward on this handle record events around
+ * its kernels; lfmmi_profile_read waits for the last call and returns
+ * milliseconds: ms[0] emission, [1] recursion (alpha and beta), [2] scales,
+ * [3] occupancy + gradient. */
+lfmmi_status lfmmi_profile_enable(lfmmi_graph *graph, int enable);
+lfmmi_status lfmmi_profile_read(lfmmi_graph *graph, float ms[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LFMMI_H */

@@ -1,0 +1,565 @@
+// C ABI of the LF-MMI forward-backward library: handle management, argument
+// checks, workspace layout and kernel launches. See include/lfmmi.h.
+#include "../../include/lfmmi.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "pack.h"
+
+using namespace lfmmi;
+
+namespace {
+
+thread_local std::string g_error;
+
+lfmmi_status fail(lfmmi_status st, const std::string& msg)
+{
+    g_error = msg;
+    return st;
+}
+
+lfmmi_status fail_hip(hipError_t e, const char* what)
+{
+    return fail(LFMMI_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+constexpr size_t kLdsBytes = 160 * 1024;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int env_int(const char* name, int fallback)
+{
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+}  // namespace
+
+struct lfmmi_graph {
+    int32_t num_graphs = 0;
+    int32_t num_pdfs = 0;
+    int64_t total_states = 0, total_arcs = 0;
+    int rec_waves = 1, occ_waves = 1;
+    std::vector<PackedGraph> packed;
+    std::vector<OrdDesc> ords;  // [num_graphs * 3]
+    int32_t max_rows_f = 0, max_rows_b = 0;
+
+    // device copy
+    bool uploaded = false;
+    int device = -1;
+    void* dev_base = nullptr;
+    DeviceGraph dg{};
+
+    // workspace, grown on demand
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    // pinned staging for per-call descriptors
+    void* stage = nullptr;
+    size_t stage_bytes = 0;
+    hipEvent_t stage_done = nullptr;
+    bool stage_pending = false;
+
+    bool profile = false;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    bool ev_recorded = false;
+};
+
+namespace {
+
+lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
+                      const int64_t* arc_off, const int32_t* src, const int32_t* dst,
+                      const int32_t* pdf, const float* logw, const float* init_prob,
+                      const float* final_prob, lfmmi_graph** out)
+{
+    if (!out) return fail(LFMMI_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (n < 1) return fail(LFMMI_ERR_INVALID_ARG, "number of graphs must be >= 1");
+    if (num_pdfs < 1) return fail(LFMMI_ERR_INVALID_ARG, "num_pdfs must be >= 1");
+    if (num_pdfs > kMaxIndex)
+        return fail(LFMMI_ERR_UNSUPPORTED, "num_pdfs exceeds 16384");
+    if (!state_off || !arc_off) return fail(LFMMI_ERR_INVALID_ARG, "null offset array");
+    if (state_off[0] != 0 || arc_off[0] != 0)
+        return fail(LFMMI_ERR_INVALID_ARG, "offsets must start at 0");
+    for (int32_t g = 0; g < n; ++g) {
+        if (state_off[g + 1] - state_off[g] < 1)
+            return fail(LFMMI_ERR_INVALID_ARG, "graph " + std::to_string(g) + " has no state");
+        if (state_off[g + 1] - state_off[g] > kMaxIndex)
+            return fail(LFMMI_ERR_UNSUPPORTED,
+                        "graph " + std::to_string(g) + " has more than 16384 states");
+        if (arc_off[g + 1] < arc_off[g])
+            return fail(LFMMI_ERR_INVALID_ARG, "arc offsets must not decrease");
+    }
+    lfmmi_graph* h = new (std::nothrow) lfmmi_graph();
+    if (!h) return fail(LFMMI_ERR_OOM, "host allocation failed");
+    try {
+        h->num_graphs = n;
+        h->num_pdfs = num_pdfs;
+        h->total_states = state_off[n];
+        h->total_arcs = arc_off[n];
+        int waves = 1;
+        for (int32_t g = 0; g < n; ++g)
+            waves = std::max(waves, choose_waves(arc_off[g + 1] - arc_off[g],
+                                                 (int32_t)(state_off[g + 1] - state_off[g])));
+        waves = std::max(1, std::min(env_int("LFMMI_WAVES", waves), kMaxWaves));
+        h->rec_waves = waves;
+        h->occ_waves = waves;
+        h->packed.resize(n);
+        for (int32_t g = 0; g < n; ++g) {
+            ArcList al;
+            al.num_states = (int32_t)(state_off[g + 1] - state_off[g]);
+            al.num_arcs = arc_off[g + 1] - arc_off[g];
+            al.src = src ? src + arc_off[g] : nullptr;
+            al.dst = dst ? dst + arc_off[g] : nullptr;
+            al.pdf = pdf ? pdf + arc_off[g] : nullptr;
+            al.logw = logw ? logw + arc_off[g] : nullptr;
+            al.init_prob = init_prob ? init_prob + state_off[g] : nullptr;
+            al.final_prob = final_prob ? final_prob + state_off[g] : nullptr;
+            bool bad = false;
+            std::string err = pack_graph(al, num_pdfs, h->rec_waves, h->occ_waves,
+                                         &h->packed[g], &bad);
+            if (!err.empty()) {
+                delete h;
+                return fail(bad ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
+                            (n > 1 ? "graph " + std::to_string(g) + ": " : std::string()) + err);
+            }
+            h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
+            h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
+        }
+        const size_t ppad = (size_t)(num_pdfs + 63) / 64 * 64;
+        const size_t rows = (size_t)std::max(h->max_rows_f, h->max_rows_b);
+        if ((2 * rows + 2 * ppad + 32) * 4 > kLdsBytes ||
+            ((size_t)h->max_rows_f + h->max_rows_b + 2 * ppad) * 4 > kLdsBytes) {
+            delete h;
+            return fail(LFMMI_ERR_UNSUPPORTED,
+                        "states and pdfs do not fit the 160 KB of LDS of one compute unit");
+        }
+    } catch (const std::bad_alloc&) {
+        delete h;
+        return fail(LFMMI_ERR_OOM, "host allocation failed");
+    }
+    *out = h;
+    return LFMMI_OK;
+}
+
+template <class T>
+size_t reserve(size_t* total, size_t count)
+{
+    const size_t at = *total;
+    *total = align_up(at + count * sizeof(T));
+    return at;
+}
+
+lfmmi_status upload(lfmmi_graph* h)
+{
+    if (h->uploaded) return LFMMI_OK;
+    hipError_t e = hipGetDevice(&h->device);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if ((e = configure_kernels()) != hipSuccess) return fail_hip(e, "hipFuncSetAttribute");
+
+    // concatenate every graph's orderings
+    size_t n_slots = 0, n_soff = 0, n_wf = 0, n_vec = 0, n_rowpdf = 0;
+    h->ords.assign((size_t)h->num_graphs * 3, OrdDesc{});
+    for (int32_t g = 0; g < h->num_graphs; ++g)
+        for (int o = 0; o < 3; ++o) {
+            const Ordering& od = h->packed[g].ord[o];
+            OrdDesc& d = h->ords[(size_t)g * 3 + o];
+            d.num_slices = od.num_slices;
+            d.num_waves = od.num_waves;
+            d.rec_at = (int32_t)n_slots;
+            d.slice_off_at = (int32_t)n_soff;
+            d.wave_first_at = (int32_t)n_wf;
+            d.max_wave_slots = od.max_wave_slots;
+            d.total_slots = od.total_slots;
+            n_slots += od.total_slots;
+            n_soff += od.slice_off.size();
+            n_wf += od.wave_first.size();
+            if (o < 2) {
+                // FWD and BWD vectors of one graph sit back to back
+                d.vec_at = (int32_t)n_vec;
+                n_vec += (size_t)od.num_slices * kLanes;
+            } else {
+                d.vec_at = (int32_t)n_rowpdf;
+                n_rowpdf += (size_t)od.num_slices * kLanes;
+            }
+        }
+    if (n_slots > (size_t)1 << 30) return fail(LFMMI_ERR_UNSUPPORTED, "packed graph too large");
+
+    size_t total = 0;
+    const size_t at_recs = reserve<uint2>(&total, n_slots * kLanes);
+    const size_t at_soff = reserve<int32_t>(&total, n_soff);
+    const size_t at_wf = reserve<int32_t>(&total, n_wf);
+    const size_t at_vinit = reserve<float>(&total, n_vec);
+    const size_t at_va = reserve<float>(&total, n_vec);
+    const size_t at_vb = reserve<float>(&total, n_vec);
+    const size_t at_vfin = reserve<float>(&total, n_vec);
+    const size_t at_rowpdf = reserve<int32_t>(&total, n_rowpdf);
+    const size_t at_ords = reserve<OrdDesc>(&total, h->ords.size());
+    total = std::max<size_t>(total, kAlign);
+
+    std::vector<unsigned char> host;
+    try {
+        host.assign(total, 0);
+    } catch (const std::bad_alloc&) {
+        return fail(LFMMI_ERR_OOM, "host allocation failed");
+    }
+    for (int32_t g = 0; g < h->num_graphs; ++g)
+        for (int o = 0; o < 3; ++o) {
+            const Ordering& od = h->packed[g].ord[o];
+            const OrdDesc& d = h->ords[(size_t)g * 3 + o];
+            uint2* recs = reinterpret_cast<uint2*>(host.data() + at_recs) + (size_t)d.rec_at * kLanes;
+            for (size_t i = 0; i < od.key.size(); ++i) {
+                uint32_t wbits;
+                std::memcpy(&wbits, &od.w[i], 4);
+                recs[i] = make_uint2(od.key[i], wbits);
+            }
+            std::memcpy(host.data() + at_soff + (size_t)d.slice_off_at * 4, od.slice_off.data(),
+                        od.slice_off.size() * 4);
+            std::memcpy(host.data() + at_wf + (size_t)d.wave_first_at * 4, od.wave_first.data(),
+                        od.wave_first.size() * 4);
+            const size_t nrow = (size_t)od.num_slices * kLanes;
+            if (o < 2) {
+                const PackedGraph& pg = h->packed[g];
+                std::memcpy(host.data() + at_vinit + (size_t)d.vec_at * 4, pg.vinit[o].data(), nrow * 4);
+                std::memcpy(host.data() + at_va + (size_t)d.vec_at * 4, pg.va[o].data(), nrow * 4);
+                std::memcpy(host.data() + at_vb + (size_t)d.vec_at * 4, pg.vb[o].data(), nrow * 4);
+                std::memcpy(host.data() + at_vfin + (size_t)d.vec_at * 4, pg.vfin[o].data(), nrow * 4);
+            } else {
+                std::memcpy(host.data() + at_rowpdf + (size_t)d.vec_at * 4,
+                            h->packed[g].row_pdf4.data(), nrow * 4);
+            }
+        }
+    std::memcpy(host.data() + at_ords, h->ords.data(), h->ords.size() * sizeof(OrdDesc));
+
+    if ((e = hipMalloc(&h->dev_base, total)) != hipSuccess) {
+        h->dev_base = nullptr;
+        return fail(LFMMI_ERR_OOM, std::string("hipMalloc: ") + hipGetErrorString(e));
+    }
+    if ((e = hipMemcpy(h->dev_base, host.data(), total, hipMemcpyHostToDevice)) != hipSuccess) {
+        (void)hipFree(h->dev_base);
+        h->dev_base = nullptr;
+        return fail_hip(e, "hipMemcpy");
+    }
+    unsigned char* base = static_cast<unsigned char*>(h->dev_base);
+    h->dg.recs = reinterpret_cast<const uint2*>(base + at_recs);
+    h->dg.slice_off = reinterpret_cast<const int32_t*>(base + at_soff);
+    h->dg.wave_first = reinterpret_cast<const int32_t*>(base + at_wf);
+    h->dg.vinit = reinterpret_cast<const float*>(base + at_vinit);
+    h->dg.va = reinterpret_cast<const float*>(base + at_va);
+    h->dg.vb = reinterpret_cast<const float*>(base + at_vb);
+    h->dg.vfin = reinterpret_cast<const float*>(base + at_vfin);
+    h->dg.row_pdf4 = reinterpret_cast<const int32_t*>(base + at_rowpdf);
+    h->dg.ords = reinterpret_cast<const OrdDesc*>(base + at_ords);
+    h->uploaded = true;
+    return LFMMI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lfmmi_last_error(void) { return g_error.c_str(); }
+
+lfmmi_status lfmmi_graph_pack_batch(int32_t n, int32_t num_pdfs, const int64_t* state_off,
+                                    const int64_t* arc_off, const int32_t* src,
+                                    const int32_t* dst, const int32_t* pdf, const float* logw,
+                                    const float* init_prob, const float* final_prob,
+                                    lfmmi_graph** out)
+{
+    return pack_all(n, num_pdfs, state_off, arc_off, src, dst, pdf, logw, init_prob,
+                    final_prob, out);
+}
+
+lfmmi_status lfmmi_graph_pack(int32_t num_states, int32_t num_pdfs, int64_t num_arcs,
+                              const int32_t* src, const int32_t* dst, const int32_t* pdf,
+                              const float* logw, const float* init_prob,
+                              const float* final_prob, lfmmi_graph** out)
+{
+    const int64_t so[2] = {0, num_states}, ao[2] = {0, num_arcs};
+    if (num_arcs < 0) return fail(LFMMI_ERR_INVALID_ARG, "num_arcs must be >= 0");
+    return pack_all(1, num_pdfs, so, ao, src, dst, pdf, logw, init_prob, final_prob, out);
+}
+
+lfmmi_status lfmmi_graph_upload(lfmmi_graph* graph)
+{
+    if (!graph) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
+    return upload(graph);
+}
+
+lfmmi_status lfmmi_graph_create(int32_t num_states, int32_t num_pdfs, int64_t num_arcs,
+                                const int32_t* src, const int32_t* dst, const int32_t* pdf,
+                                const float* logw, const float* init_prob,
+                                const float* final_prob, lfmmi_graph** out)
+{
+    lfmmi_status st = lfmmi_graph_pack(num_states, num_pdfs, num_arcs, src, dst, pdf, logw,
+                                       init_prob, final_prob, out);
+    if (st != LFMMI_OK) return st;
+    st = upload(*out);
+    if (st != LFMMI_OK) { lfmmi_graph_destroy(*out); *out = nullptr; }
+    return st;
+}
+
+lfmmi_status lfmmi_graph_create_batch(int32_t n, int32_t num_pdfs, const int64_t* state_off,
+                                      const int64_t* arc_off, const int32_t* src,
+                                      const int32_t* dst, const int32_t* pdf,
+                                      const float* logw, const float* init_prob,
+                                      const float* final_prob, lfmmi_graph** out)
+{
+    lfmmi_status st = pack_all(n, num_pdfs, state_off, arc_off, src, dst, pdf, logw,
+                               init_prob, final_prob, out);
+    if (st != LFMMI_OK) return st;
+    st = upload(*out);
+    if (st != LFMMI_OK) { lfmmi_graph_destroy(*out); *out = nullptr; }
+    return st;
+}
+
+void lfmmi_graph_destroy(lfmmi_graph* h)
+{
+    if (!h) return;
+    if (h->uploaded || h->ws || h->stage) {
+        (void)hipDeviceSynchronize();
+        if (h->dev_base) (void)hipFree(h->dev_base);
+        if (h->ws) (void)hipFree(h->ws);
+        if (h->stage) (void)hipHostFree(h->stage);
+        if (h->stage_done) (void)hipEventDestroy(h->stage_done);
+        for (hipEvent_t e : h->ev)
+            if (e) (void)hipEventDestroy(e);
+    }
+    delete h;
+}
+
+lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logits,
+                                    const int32_t* lengths, int32_t B, int32_t T, int32_t P,
+                                    float leak, float grad_scale, int accumulate, float* objf,
+                                    float* grad, int32_t* status, void* hip_stream)
+{
+    lfmmi_graph* h = const_cast<lfmmi_graph*>(graph);  // the workspace is mutable state
+    if (!h) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
+    if (!h->uploaded) return fail(LFMMI_ERR_INVALID_ARG, "graph was packed but not uploaded");
+    if (B < 0 || T < 0) return fail(LFMMI_ERR_INVALID_ARG, "B and T must be >= 0");
+    if (P != h->num_pdfs) return fail(LFMMI_ERR_INVALID_ARG, "P differs from the graph's num_pdfs");
+    if (!(leak >= 0.f) || !(leak < INFINITY)) return fail(LFMMI_ERR_INVALID_ARG, "leak must be finite and >= 0");
+    if (!(grad_scale == grad_scale)) return fail(LFMMI_ERR_INVALID_ARG, "grad_scale is NaN");
+    if (h->num_graphs != 1 && h->num_graphs != B)
+        return fail(LFMMI_ERR_INVALID_ARG, "a batch handle needs one graph per sequence");
+    if (B == 0) return LFMMI_OK;
+    if (!lengths || !objf) return fail(LFMMI_ERR_INVALID_ARG, "lengths / objf is null");
+    if (T > 0 && (!logits || !grad)) return fail(LFMMI_ERR_INVALID_ARG, "logits / grad is null");
+    if (B > 32767) return fail(LFMMI_ERR_UNSUPPORTED, "B exceeds 32767");
+    for (int32_t b = 0; b < B; ++b)
+        if (lengths[b] < 0 || lengths[b] > T)
+            return fail(LFMMI_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, T]");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+
+    // ---- per-sequence descriptors and the launch order (longest first)
+    std::vector<SeqDesc> seqs(B);
+    int64_t a_at = 0, b_at = 0, s_at = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t g = h->num_graphs == 1 ? 0 : b;
+        const int64_t rf = h->packed[g].ord[0].num_slices * kLanes;
+        const int64_t rb = h->packed[g].ord[1].num_slices * kLanes;
+        seqs[b].alpha_at = a_at;
+        seqs[b].beta_at = b_at;
+        seqs[b].T = lengths[b];
+        seqs[b].graph = g;
+        seqs[b].scal_at = (int32_t)s_at;
+        seqs[b].pad = 0;
+        a_at += rf * (lengths[b] + 1);
+        b_at += rb * (lengths[b] + 1);
+        s_at += lengths[b] + 1;
+    }
+    if (s_at > (int64_t)1 << 30) return fail(LFMMI_ERR_UNSUPPORTED, "too many frames in one call");
+    std::vector<int32_t> by_len(B);
+    std::iota(by_len.begin(), by_len.end(), 0);
+    std::stable_sort(by_len.begin(), by_len.end(), [&](int32_t x, int32_t y) {
+        const int64_t wx = (int64_t)lengths[x] * h->packed[seqs[x].graph].num_arcs;
+        const int64_t wy = (int64_t)lengths[y] * h->packed[seqs[y].graph].num_arcs;
+        return wx != wy ? wx > wy : lengths[x] > lengths[y];
+    });
+    std::vector<int32_t> order((size_t)2 * B);
+    for (int32_t i = 0; i < B; ++i) {
+        order[(size_t)2 * i] = by_len[i] << 1;
+        order[(size_t)2 * i + 1] = (by_len[i] << 1) | 1;
+    }
+
+    // ---- workspace layout
+    size_t total = 0;
+    const size_t at_seqs = reserve<SeqDesc>(&total, B);
+    const size_t at_order = reserve<int32_t>(&total, (size_t)2 * B);
+    const size_t stage_need = total;
+    const size_t at_emis = reserve<float>(&total, (size_t)B * T * P);
+    const size_t at_rowmax = reserve<float>(&total, (size_t)B * T);
+    const size_t at_alpha = reserve<float>(&total, (size_t)a_at);
+    const size_t at_beta = reserve<float>(&total, (size_t)b_at);
+    const size_t at_scal = reserve<float>(&total, (size_t)2 * s_at);
+    const size_t at_cfac = reserve<float>(&total, (size_t)s_at);
+    const size_t at_zfin = reserve<float>(&total, (size_t)2 * B);
+    const size_t at_status = reserve<int32_t>(&total, B);
+
+    if (total > h->ws_bytes) {
+        if (h->ws) {
+            (void)hipDeviceSynchronize();
+            (void)hipFree(h->ws);
+            h->ws = nullptr;
+            h->ws_bytes = 0;
+        }
+        if ((e = hipMalloc(&h->ws, total)) != hipSuccess) {
+            h->ws = nullptr;
+            return fail(LFMMI_ERR_OOM, "workspace of " + std::to_string(total) +
+                                           " bytes: " + hipGetErrorString(e));
+        }
+        h->ws_bytes = total;
+    }
+    if (stage_need > h->stage_bytes) {
+        if (h->stage) {
+            if (h->stage_pending) (void)hipEventSynchronize(h->stage_done);
+            (void)hipHostFree(h->stage);
+            h->stage = nullptr;
+            h->stage_bytes = 0;
+        }
+        if ((e = hipHostMalloc(&h->stage, stage_need, hipHostMallocDefault)) != hipSuccess) {
+            h->stage = nullptr;
+            return fail(LFMMI_ERR_OOM, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+        }
+        h->stage_bytes = stage_need;
+    }
+    if (!h->stage_done &&
+        (e = hipEventCreateWithFlags(&h->stage_done, hipEventDisableTiming)) != hipSuccess)
+        return fail_hip(e, "hipEventCreate");
+    if (h->stage_pending) {
+        // the previous call's descriptor copy must have left the staging buffer
+        if ((e = hipEventSynchronize(h->stage_done)) != hipSuccess)
+            return fail_hip(e, "hipEventSynchronize");
+        h->stage_pending = false;
+    }
+    unsigned char* st = static_cast<unsigned char*>(h->stage);
+    std::memcpy(st + at_seqs, seqs.data(), sizeof(SeqDesc) * B);
+    std::memcpy(st + at_order, order.data(), sizeof(int32_t) * 2 * B);
+    unsigned char* ws = static_cast<unsigned char*>(h->ws);
+    if ((e = hipMemcpyAsync(ws, st, stage_need, hipMemcpyHostToDevice, stream)) != hipSuccess)
+        return fail_hip(e, "hipMemcpyAsync");
+    if ((e = hipEventRecord(h->stage_done, stream)) != hipSuccess)
+        return fail_hip(e, "hipEventRecord");
+    h->stage_pending = true;
+
+    FbParams p{};
+    p.g = h->dg;
+    p.seqs = reinterpret_cast<const SeqDesc*>(ws + at_seqs);
+    p.order = reinterpret_cast<const int32_t*>(ws + at_order);
+    p.logits = logits;
+    p.emis = reinterpret_cast<float*>(ws + at_emis);
+    p.rowmax = reinterpret_cast<float*>(ws + at_rowmax);
+    p.alpha = reinterpret_cast<float*>(ws + at_alpha);
+    p.beta = reinterpret_cast<float*>(ws + at_beta);
+    p.scal = reinterpret_cast<float*>(ws + at_scal);
+    p.cfac = reinterpret_cast<float*>(ws + at_cfac);
+    p.zfin = reinterpret_cast<float*>(ws + at_zfin);
+    p.status_ws = reinterpret_cast<int32_t*>(ws + at_status);
+    p.status_out = status;
+    p.objf = objf;
+    p.grad = grad;
+    p.scal_total = s_at;
+    p.B = B;
+    p.T = T;
+    p.P = P;
+    p.lds_rows = std::max(h->max_rows_f, h->max_rows_b);
+    p.lds_rows_occ_a = h->max_rows_f;
+    p.lds_rows_occ_b = h->max_rows_b;
+    p.accumulate = accumulate ? 1 : 0;
+    p.leak = leak;
+    p.grad_scale = grad_scale;
+
+    LaunchShape shape;
+    shape.rec_threads = h->rec_waves * kLanes;
+    shape.occ_threads = h->occ_waves * kLanes;
+    shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
+
+    hipEvent_t* ev = nullptr;
+    if (h->profile) {
+        for (hipEvent_t& x : h->ev)
+            if (!x && (e = hipEventCreate(&x)) != hipSuccess) return fail_hip(e, "hipEventCreate");
+        ev = h->ev;
+    }
+    if ((e = launch_forward_backward(p, shape, stream, ev)) != hipSuccess)
+        return fail_hip(e, "kernel launch");
+    h->ev_recorded = ev != nullptr;
+    return LFMMI_OK;
+}
+
+lfmmi_status lfmmi_graph_info(const lfmmi_graph* h, int64_t info[8])
+{
+    if (!h || !info) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
+    info[0] = h->num_graphs;
+    info[1] = h->num_pdfs;
+    info[2] = h->total_states;
+    info[3] = h->total_arcs;
+    info[4] = h->rec_waves;
+    info[5] = h->occ_waves;
+    info[6] = h->uploaded ? 1 : 0;
+    info[7] = (int64_t)h->ws_bytes;
+    return LFMMI_OK;
+}
+
+lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t ord,
+                                       int64_t info[8])
+{
+    if (!h || !info) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
+    if (g < 0 || g >= h->num_graphs || ord < 0 || ord > 2)
+        return fail(LFMMI_ERR_INVALID_ARG, "graph or ordering index out of range");
+    const Ordering& o = h->packed[g].ord[ord];
+    info[0] = o.num_rows;
+    info[1] = o.num_slices;
+    info[2] = o.num_waves;
+    info[3] = o.total_slots;
+    info[4] = o.max_wave_slots;
+    info[5] = info[6] = info[7] = 0;
+    return LFMMI_OK;
+}
+
+lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph* h, int32_t g, int32_t ord,
+                                       int32_t* slice_off, int32_t* wave_first, uint32_t* key,
+                                       float* w, int32_t* row_id)
+{
+    if (!h) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
+    if (g < 0 || g >= h->num_graphs || ord < 0 || ord > 2)
+        return fail(LFMMI_ERR_INVALID_ARG, "graph or ordering index out of range");
+    const Ordering& o = h->packed[g].ord[ord];
+    if (slice_off) std::memcpy(slice_off, o.slice_off.data(), o.slice_off.size() * 4);
+    if (wave_first) std::memcpy(wave_first, o.wave_first.data(), o.wave_first.size() * 4);
+    if (key) std::memcpy(key, o.key.data(), o.key.size() * 4);
+    if (w) std::memcpy(w, o.w.data(), o.w.size() * 4);
+    if (row_id) std::memcpy(row_id, o.row_id.data(), o.row_id.size() * 4);
+    return LFMMI_OK;
+}
+
+lfmmi_status lfmmi_profile_enable(lfmmi_graph* h, int enable)
+{
+    if (!h) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
+    h->profile = enable != 0;
+    if (!h->profile) h->ev_recorded = false;
+    return LFMMI_OK;
+}
+
+lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4])
+{
+    if (!h || !ms) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
+    if (!h->ev_recorded) return fail(LFMMI_ERR_INVALID_ARG, "no profiled call to read");
+    hipError_t e = hipEventSynchronize(h->ev[4]);
+    if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+    for (int i = 0; i < 4; ++i)
+        if ((e = hipEventElapsedTime(&ms[i], h->ev[i], h->ev[i + 1])) != hipSuccess)
+            return fail_hip(e, "hipEventElapsedTime");
+    return LFMMI_OK;
+}
+
+}  // extern "C"

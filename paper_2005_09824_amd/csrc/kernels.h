@@ -1,0 +1,78 @@
+// Plain-struct interface between the C ABI (api.cpp) and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace lfmmi {
+
+// One packed ordering of one graph; offsets index the concatenated arrays of
+// DeviceGraph.
+struct OrdDesc {
+    int32_t num_slices;     // rows = num_slices * 64
+    int32_t num_waves;      // waves that own slices
+    int32_t rec_at;         // first slot (units of 64 records) in recs
+    int32_t slice_off_at;   // first entry in slice_off (num_slices + 1 entries)
+    int32_t wave_first_at;  // first entry in wave_first (num_waves + 1 entries)
+    int32_t vec_at;         // FWD/BWD: first row in vinit/va/vb/vfin; OCC: in row_pdf4
+    int32_t max_wave_slots;
+    int32_t total_slots;
+};
+
+struct DeviceGraph {
+    const uint2* recs;          // {key, float bits of w}, lane-minor
+    const int32_t* slice_off;   // slot offsets, local to the ordering
+    const int32_t* wave_first;
+    const float* vinit;
+    const float* va;
+    const float* vb;
+    const float* vfin;
+    const int32_t* row_pdf4;
+    const OrdDesc* ords;        // [num_graphs * 3]
+};
+
+struct SeqDesc {
+    int64_t alpha_at;  // first float of this sequence's alpha trellis
+    int64_t beta_at;
+    int32_t T;         // frames of this sequence
+    int32_t graph;     // graph index
+    int32_t scal_at;   // first of its T + 1 per-frame scalars
+    int32_t pad;
+};
+
+struct FbParams {
+    DeviceGraph g;
+    const SeqDesc* seqs;    // [B]
+    const int32_t* order;   // [2B] (b << 1 | direction), longest sequences first
+    const float* logits;    // [B, T, P]
+    float* emis;            // [B, T, P] exp(logit - row max)
+    float* rowmax;          // [B, T]
+    float* alpha;           // ragged trellis, (T_b + 1) rows of rows_f floats
+    float* beta;
+    float* scal;            // [2][scal_total] per-frame normalisers (alpha, beta)
+    float* cfac;            // [scal_total] occupancy scale of frame t at scal_at + t
+    float* zfin;            // [2][B] closing dot products (alpha side, beta side)
+    int32_t* status_ws;     // [B]
+    int32_t* status_out;    // [B] or null
+    float* objf;            // [B]
+    float* grad;            // [B, T, P]
+    int64_t scal_total;
+    int32_t B, T, P;
+    int32_t lds_rows;       // largest padded row count over the handle's graphs
+    int32_t lds_rows_occ_a, lds_rows_occ_b;
+    int32_t accumulate;
+    float leak, grad_scale;
+};
+
+struct LaunchShape {
+    int rec_threads;   // workgroup size of the recursion kernel
+    int occ_threads;   // workgroup size of the occupancy kernel
+    int occ_frames;    // frames per occupancy workgroup
+};
+
+// Each returns the first HIP error met (hipSuccess otherwise). ev, if non-null,
+// holds 5 events recorded before, between and after the four kernels.
+hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
+                                   hipStream_t stream, hipEvent_t* ev);
+hipError_t configure_kernels();
+
+}  // namespace lfmmi

@@ -1,0 +1,428 @@
+// HIP kernels (gfx950) of the batched LF-MMI forward-backward.
+//
+// Pipeline of one call (all on the caller's stream):
+//   k_emit  e_t[d] = exp(x_t[d] - max_d x_t[d]) for every valid frame, in parallel
+//   k_rec   one workgroup per (sequence, direction): the alpha recursion of
+//           Algorithm 1 and the mirrored beta recursion, time loop on device,
+//           the current vector in LDS, arcs streamed as sliced-ELL records,
+//           leaky-HMM mixing and per-frame rescaling fused, scaled trellis rows
+//           and per-frame normalisers spilled to HBM
+//   k_scan  fp64 prefix sums of the log normalisers: log Z, per-frame occupancy
+//           scale, objective and status
+//   k_occ   pdf occupancies of Eq. 3 for every frame in parallel and the
+//           gradient write
+//
+// Scaled quantities: alpha'_t = ahat_t * exp(sum_{tau<=t} log n_tau) * (frame
+// maxima), likewise beta; the frame maxima cancel in the occupancies and are
+// added back into log Z.
+#include "kernels.h"
+
+namespace lfmmi {
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float lds_at(const float* base, uint32_t byte_off)
+{
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
+// ---------------------------------------------------------------------------
+// Emission: one wave per frame row. A row holding NaN or +inf (or nothing but
+// -inf) is flagged by a NaN row maximum and an all-zero emission row.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_emit(FbParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int b = blockIdx.y;
+    if (t >= p.seqs[b].T) return;
+    const size_t at = ((size_t)b * p.T + t) * p.P;
+    const float* x = p.logits + at;
+    float* e = p.emis + at;
+    float m = -INFINITY;
+    bool bad = false;
+    for (int d = lane; d < p.P; d += 64) {
+        const float v = x[d];
+        bad |= !(v == v);
+        m = fmaxf(m, v);
+    }
+    m = wave_max(m);
+    bad = __any(bad) || !(fabsf(m) < INFINITY);
+    for (int d = lane; d < p.P; d += 64) e[d] = bad ? 0.f : expf(x[d] - m);
+    if (lane == 0) p.rowmax[(size_t)b * p.T + t] = bad ? __builtin_nanf("") : m;
+}
+
+// ---------------------------------------------------------------------------
+// Recursion. Direction 0 is alpha (rows = to-states), direction 1 is beta
+// (rows = from-states); both run v <- leak(M v) with
+//   leak(v) = v + eps * (a . v) * b     (alpha: a = 1, b = pi; beta: a = pi, b = 1)
+// and store vhat = leak(v) / n, n = sum(v).
+// ---------------------------------------------------------------------------
+constexpr int kYRegs = 4;
+
+__global__ void __launch_bounds__(1024) k_rec(FbParams p)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nthreads = blockDim.x;
+    const int nwaves = nthreads >> 6;
+    const int code = p.order[blockIdx.x];
+    const int b = code >> 1, dir = code & 1;
+    const SeqDesc sd = p.seqs[b];
+    const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
+    const int T = sd.T;
+    const int P = p.P;
+    const int rows = od.num_slices * 64;
+    const int Ppad = (P + 63) & ~63;
+
+    float* X0 = reinterpret_cast<float*>(lds_raw);
+    float* X1 = X0 + p.lds_rows;
+    float* Y0 = X1 + p.lds_rows;
+    float* Y1 = Y0 + Ppad;
+    float* part = Y1 + Ppad;  // [nwaves][2]
+
+    float* trel = dir == 0 ? p.alpha + sd.alpha_at : p.beta + sd.beta_at;
+    float* scal = p.scal + (size_t)dir * p.scal_total + sd.scal_at;
+    const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+    const int32_t* so = p.g.slice_off + od.slice_off_at;
+    const float* va = p.g.va + od.vec_at;
+    const float* vb = p.g.vb + od.vec_at;
+    const float eps = p.leak;
+
+    int s0 = 0, s1 = 0;
+    if (wave < od.num_waves) {
+        s0 = p.g.wave_first[od.wave_first_at + wave];
+        s1 = p.g.wave_first[od.wave_first_at + wave + 1];
+    }
+    const size_t erow0 = (size_t)b * p.T;
+
+    // ---- step 0: vhat_0 = leak(init) / sum(init)
+    {
+        float n = 0.f, s = 0.f;
+        for (int sl = s0; sl < s1; ++sl) {
+            const int row = sl * 64 + lane;
+            const float v = p.g.vinit[od.vec_at + row];
+            X0[row] = v;
+            n += v;
+            s = fmaf(va[row], v, s);
+        }
+        n = wave_sum(n);
+        s = wave_sum(s);
+        if (lane == 0) { part[wave * 2] = n; part[wave * 2 + 1] = s; }
+        __syncthreads();
+        float N = 0.f, Sd = 0.f;
+        for (int w = 0; w < nwaves; ++w) { N += part[w * 2]; Sd += part[w * 2 + 1]; }
+        const float inv = N > 0.f ? 1.f / N : 0.f;
+        const float c = eps * Sd * inv;
+        const int ti = dir == 0 ? 0 : T;
+        for (int sl = s0; sl < s1; ++sl) {
+            const int row = sl * 64 + lane;
+            const float v = fmaf(c, vb[row], X0[row] * inv);
+            X0[row] = v;
+            trel[(size_t)ti * rows + row] = v;
+        }
+        if (tid == 0) scal[ti] = N;
+        if (T > 0) {
+            const int fr = dir == 0 ? 0 : T - 1;
+            const float* e = p.emis + (erow0 + fr) * P;
+            for (int d = tid; d < P; d += nthreads) Y0[d] = e[d];
+        }
+        __syncthreads();
+    }
+
+    // ---- steps 1..T
+    for (int k = 1; k <= T; ++k) {
+        const float* Xc = (k & 1) ? X0 : X1;
+        float* Xn = (k & 1) ? X1 : X0;
+        const float* Yc = (k & 1) ? Y0 : Y1;
+        float* Yn = (k & 1) ? Y1 : Y0;
+
+        // emission row of the next step, issued early
+        float yreg[kYRegs];
+        const bool more = k < T;
+        const int frn = dir == 0 ? k : T - k - 1;
+        const float* en = p.emis + (erow0 + (more ? frn : 0)) * P;
+#pragma unroll
+        for (int i = 0; i < kYRegs; ++i) {
+            const int d = tid + i * nthreads;
+            yreg[i] = (more && d < P) ? en[d] : 0.f;
+        }
+
+        float n = 0.f, s = 0.f;
+        for (int sl = s0; sl < s1; ++sl) {
+            const int o0 = so[sl], o1 = so[sl + 1];
+            const uint2* rp = recs + (size_t)o0 * 64;
+            float acc = 0.f;
+            int i = o0;
+            for (; i + 4 <= o1; i += 4) {
+                const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
+                rp += 256;
+                acc = fmaf(__uint_as_float(r0.y) * lds_at(Yc, r0.x >> 16), lds_at(Xc, r0.x & 0xffffu), acc);
+                acc = fmaf(__uint_as_float(r1.y) * lds_at(Yc, r1.x >> 16), lds_at(Xc, r1.x & 0xffffu), acc);
+                acc = fmaf(__uint_as_float(r2.y) * lds_at(Yc, r2.x >> 16), lds_at(Xc, r2.x & 0xffffu), acc);
+                acc = fmaf(__uint_as_float(r3.y) * lds_at(Yc, r3.x >> 16), lds_at(Xc, r3.x & 0xffffu), acc);
+            }
+            for (; i < o1; ++i) {
+                const uint2 r0 = rp[0];
+                rp += 64;
+                acc = fmaf(__uint_as_float(r0.y) * lds_at(Yc, r0.x >> 16), lds_at(Xc, r0.x & 0xffffu), acc);
+            }
+            const int row = sl * 64 + lane;
+            Xn[row] = acc;
+            n += acc;
+            s = fmaf(va[row], acc, s);
+        }
+        n = wave_sum(n);
+        s = wave_sum(s);
+        if (lane == 0) { part[wave * 2] = n; part[wave * 2 + 1] = s; }
+        __syncthreads();
+
+        float N = 0.f, Sd = 0.f;
+        for (int w = 0; w < nwaves; ++w) { N += part[w * 2]; Sd += part[w * 2 + 1]; }
+        const float inv = N > 0.f ? 1.f / N : 0.f;
+        const float c = eps * Sd * inv;
+        const int ti = dir == 0 ? k : T - k;
+        float* tr = trel + (size_t)ti * rows;
+        for (int sl = s0; sl < s1; ++sl) {
+            const int row = sl * 64 + lane;
+            const float v = fmaf(c, vb[row], Xn[row] * inv);
+            Xn[row] = v;
+            tr[row] = v;
+        }
+        if (tid == 0) scal[ti] = N;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < kYRegs; ++i) {
+                const int d = tid + i * nthreads;
+                if (d < P) Yn[d] = yreg[i];
+            }
+            for (int d = tid + kYRegs * nthreads; d < P; d += nthreads) Yn[d] = en[d];
+        }
+        __syncthreads();
+    }
+
+    // ---- closing dot product: alpha side sum_j f[j] ahat_T[j], beta side sum_i pi[i] bhat_0[i]
+    {
+        const float* Xc = (T & 1) ? X1 : X0;
+        float z = 0.f;
+        for (int sl = s0; sl < s1; ++sl) {
+            const int row = sl * 64 + lane;
+            z = fmaf(p.g.vfin[od.vec_at + row], Xc[row], z);
+        }
+        z = wave_sum(z);
+        if (lane == 0) part[wave * 2] = z;
+        __syncthreads();
+        if (tid == 0) {
+            float Z = 0.f;
+            for (int w = 0; w < nwaves; ++w) Z += part[w * 2];
+            p.zfin[(size_t)dir * p.B + b] = Z;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Scales: log Z_b = log(zfin) + sum_t log n_t (+ the frame maxima), and the
+// factor that turns ahat_{t-1} * w * e_t * bhat_t into an occupancy:
+//   c_t = exp(A_{t-1} + B_t - log Z'),  A, B = prefix / suffix sums of log n.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_scan(FbParams p)
+{
+    __shared__ double sa[256], sb[256], sm[256];
+    __shared__ double tot[3];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const SeqDesc sd = p.seqs[b];
+    const int T = sd.T;
+    const int n = T + 1;
+    const float* na = p.scal + sd.scal_at;
+    const float* nb = p.scal + p.scal_total + sd.scal_at;
+    const int chunk = (n + 255) / 256;
+    const int i0 = min(tid * chunk, n), i1 = min(i0 + chunk, n);
+    double la = 0.0, lb = 0.0, lm = 0.0;
+    for (int i = i0; i < i1; ++i) {
+        la += log((double)na[i]);
+        lb += log((double)nb[i]);
+    }
+    for (int t = tid; t < T; t += 256) lm += (double)p.rowmax[(size_t)b * p.T + t];
+    sa[tid] = la; sb[tid] = lb; sm[tid] = lm;
+    __syncthreads();
+    if (tid == 0) {
+        double ra = 0.0, rb = 0.0, rm = 0.0;
+        for (int i = 0; i < 256; ++i) {
+            const double xa = sa[i], xb = sb[i];
+            sa[i] = ra; sb[i] = rb;  // exclusive prefixes
+            ra += xa; rb += xb; rm += sm[i];
+        }
+        tot[0] = ra; tot[1] = rb; tot[2] = rm;
+    }
+    __syncthreads();
+    const double totB = tot[1], msum = tot[2];
+    const double lz = log((double)p.zfin[b]) + tot[0];
+    const bool nonfinite_in = !(msum == msum);
+    const bool dead = !(lz > -INFINITY && lz < INFINITY) || nonfinite_in;
+    double ra = sa[tid], rb = sb[tid];
+    for (int i = i0; i < i1; ++i) {
+        if (i >= 1) p.cfac[sd.scal_at + i] = dead ? 0.f : (float)exp(ra + (totB - rb) - lz);
+        ra += log((double)na[i]);
+        rb += log((double)nb[i]);
+    }
+    if (tid == 0) {
+        int st = 0;
+        if (nonfinite_in) st |= 2;
+        if (dead) st |= 1;
+        const float val = nonfinite_in ? __builtin_nanf("") : (float)(lz + msum);
+        const float out = p.grad_scale * val;
+        p.objf[b] = p.accumulate ? p.objf[b] + out : out;
+        p.status_ws[b] = st;
+        if (p.status_out) p.status_out[b] = p.accumulate ? (p.status_out[b] | st) : st;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Occupancy and gradient, frames in parallel. Rows of the OCC ordering are
+// pieces of one pdf's arc list; a row's sum goes to its pdf's LDS bin.
+//   gamma_t[d] = c_t * e_t[d] * sum_{a: pdf_a = d} w_a * ahat_{t-1}[src_a] * bhat_t[dst_a]
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nthreads = blockDim.x;
+    const int b = blockIdx.y;
+    const SeqDesc sd = p.seqs[b];
+    const int T = sd.T;
+    const int P = p.P;
+    const int Ppad = (P + 63) & ~63;
+    const OrdDesc od = p.g.ords[sd.graph * 3 + 2];
+    const int rows_f = p.g.ords[sd.graph * 3 + 0].num_slices * 64;
+    const int rows_b = p.g.ords[sd.graph * 3 + 1].num_slices * 64;
+
+    float* XA = reinterpret_cast<float*>(lds_raw);
+    float* XB = XA + p.lds_rows_occ_a;
+    float* bins0 = XB + p.lds_rows_occ_b;
+    float* bins1 = bins0 + Ppad;
+
+    const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+    const int32_t* so = p.g.slice_off + od.slice_off_at;
+    const int32_t* row_pdf4 = p.g.row_pdf4 + od.vec_at;
+    int s0 = 0, s1 = 0;
+    if (wave < od.num_waves) {
+        s0 = p.g.wave_first[od.wave_first_at + wave];
+        s1 = p.g.wave_first[od.wave_first_at + wave + 1];
+    }
+
+    const int t_first = blockIdx.x * frames_per_wg + 1;
+    const int t_last = min(t_first + frames_per_wg - 1, p.T);
+    for (int t = t_first; t <= t_last; ++t) {
+        const size_t at = ((size_t)b * p.T + (t - 1)) * P;
+        float* g = p.grad + at;
+        const float c = t <= T ? p.cfac[sd.scal_at + t] : 0.f;
+        if (t > T || c == 0.f) {  // beyond the sequence, or a dead sequence
+            if (!p.accumulate)
+                for (int d = tid; d < P; d += nthreads) g[d] = 0.f;
+            continue;
+        }
+        float* bins = (t & 1) ? bins1 : bins0;
+        const float* ar = p.alpha + sd.alpha_at + (size_t)(t - 1) * rows_f;
+        const float* br = p.beta + sd.beta_at + (size_t)t * rows_b;
+        for (int r = tid; r < rows_f; r += nthreads) XA[r] = ar[r];
+        for (int r = tid; r < rows_b; r += nthreads) XB[r] = br[r];
+        for (int d = tid; d < P; d += nthreads) bins[d] = 0.f;
+        __syncthreads();
+        for (int sl = s0; sl < s1; ++sl) {
+            const int o0 = so[sl], o1 = so[sl + 1];
+            const uint2* rp = recs + (size_t)o0 * 64;
+            float acc = 0.f;
+            int i = o0;
+            for (; i + 4 <= o1; i += 4) {
+                const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
+                rp += 256;
+                acc = fmaf(__uint_as_float(r0.y) * lds_at(XB, r0.x >> 16), lds_at(XA, r0.x & 0xffffu), acc);
+                acc = fmaf(__uint_as_float(r1.y) * lds_at(XB, r1.x >> 16), lds_at(XA, r1.x & 0xffffu), acc);
+                acc = fmaf(__uint_as_float(r2.y) * lds_at(XB, r2.x >> 16), lds_at(XA, r2.x & 0xffffu), acc);
+                acc = fmaf(__uint_as_float(r3.y) * lds_at(XB, r3.x >> 16), lds_at(XA, r3.x & 0xffffu), acc);
+            }
+            for (; i < o1; ++i) {
+                const uint2 r0 = rp[0];
+                rp += 64;
+                acc = fmaf(__uint_as_float(r0.y) * lds_at(XB, r0.x >> 16), lds_at(XA, r0.x & 0xffffu), acc);
+            }
+            const int pd = row_pdf4[sl * 64 + lane];
+            if (pd >= 0)
+                atomicAdd(reinterpret_cast<float*>(reinterpret_cast<char*>(bins) + pd), acc);
+        }
+        __syncthreads();
+        const float scale = p.grad_scale * c;
+        const float* e = p.emis + at;
+        for (int d = tid; d < P; d += nthreads) {
+            const float v = scale * e[d] * bins[d];
+            g[d] = p.accumulate ? g[d] + v : v;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t configure_kernels()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_rec),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_occ),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
+                                   hipStream_t stream, hipEvent_t* ev)
+{
+    hipError_t e;
+#define LFMMI_EV(i)                                                   \
+    if (ev) { e = hipEventRecord(ev[i], stream); if (e != hipSuccess) return e; }
+    const int Ppad = (p.P + 63) & ~63;
+    LFMMI_EV(0)
+    if (p.T > 0) {
+        dim3 grid((p.T + 3) / 4, p.B);
+        hipLaunchKernelGGL(k_emit, grid, dim3(256), 0, stream, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    LFMMI_EV(1)
+    {
+        const size_t lds = (size_t)(2 * p.lds_rows + 2 * Ppad + 2 * 16) * sizeof(float);
+        hipLaunchKernelGGL(k_rec, dim3(2 * p.B), dim3(shape.rec_threads), lds, stream, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    LFMMI_EV(2)
+    hipLaunchKernelGGL(k_scan, dim3(p.B), dim3(256), 0, stream, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    LFMMI_EV(3)
+    if (p.T > 0) {
+        const size_t lds =
+            (size_t)(p.lds_rows_occ_a + p.lds_rows_occ_b + 2 * Ppad) * sizeof(float);
+        dim3 grid((p.T + shape.occ_frames - 1) / shape.occ_frames, p.B);
+        hipLaunchKernelGGL(k_occ, grid, dim3(shape.occ_threads), lds, stream, p,
+                           shape.occ_frames);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    LFMMI_EV(4)
+#undef LFMMI_EV
+    return hipSuccess;
+}
+
+}  // namespace lfmmi

@@ -1,0 +1,68 @@
+// Host-side graph packing: three sliced-ELL (64 rows per slice) arc orderings.
+//
+// Section 3.3 keeps the transition list twice, sorted by from-state and by
+// to-state, each with per-state index ranges. The same information is kept here
+// as three orderings whose rows are owned by lanes of a wavefront:
+//   FWD  rows = to-states    record (from-state, pdf)      alpha recursion
+//   BWD  rows = from-states  record (to-state, pdf)        beta recursion
+//   OCC  rows = pieces of a pdf-id's arc list, record (from-state, to-state)
+//        pdf occupancies of Eq. 3
+// Rows are sorted by length so that the 64 rows of a slice are padded little,
+// slices are dealt to the waves of a workgroup by longest-processing-time, and
+// states are renumbered per ordering so that the row a lane owns is
+// slice * 64 + lane (coalesced trellis rows, conflict-free owner accesses).
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+namespace lfmmi {
+
+constexpr int kLanes = 64;
+constexpr int kMaxWaves = 16;
+constexpr int kMaxIndex = 16384;  // x / y index * 4 must fit 16 bits
+
+struct Ordering {
+    int32_t num_rows = 0;        // real rows
+    int32_t num_slices = 0;      // rows padded to kLanes
+    int32_t num_waves = 0;       // waves that own slices
+    int32_t total_slots = 0;     // sum of slice widths
+    int32_t max_wave_slots = 0;  // largest per-wave sum of widths
+    std::vector<int32_t> slice_off;   // [num_slices + 1]
+    std::vector<int32_t> wave_first;  // [num_waves + 1]
+    std::vector<uint32_t> key;        // [total_slots * 64]
+    std::vector<float> w;             // [total_slots * 64]
+    std::vector<int32_t> row_id;      // [num_slices * 64], -1 = padding row
+};
+
+struct PackedGraph {
+    int32_t num_states = 0;
+    int64_t num_arcs = 0;
+    Ordering ord[3];
+    // Per-direction vectors in that direction's row numbering, padded with 0:
+    //   init: start vector (FWD pi, BWD final)      fin: closing dot (FWD final, BWD pi)
+    //   a:    leak dot weights (FWD 1, BWD pi)      b:   leak target (FWD pi, BWD 1)
+    std::vector<float> vinit[2], va[2], vb[2], vfin[2];
+    std::vector<int32_t> row_pdf4;  // OCC: pdf * 4 of each row, -1 = padding row
+};
+
+struct ArcList {
+    int32_t num_states;
+    int64_t num_arcs;
+    const int32_t* src;
+    const int32_t* dst;
+    const int32_t* pdf;
+    const float* logw;
+    const float* init_prob;
+    const float* final_prob;
+};
+
+// Waves per workgroup that suit a graph with this many arcs.
+int choose_waves(int64_t num_arcs, int32_t num_states);
+
+// Validates and packs one graph. Returns an empty string on success, else the
+// reason (bad_graph says whether the graph or an argument is at fault).
+std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int occ_waves,
+                       PackedGraph* out, bool* bad_graph);
+
+}  // namespace lfmmi

@@ -1,0 +1,159 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle,
+element by element on the same seeded inputs.
+
+Tolerances (fp32 path vs fp64 oracle): |objf - oracle| <= 1e-4 * |oracle|
+(for num - den: 1e-4 * max(|num|, |den|, 1)), |grad - oracle| <= 1e-4 absolute.
+"""
+import numpy as np
+import pytest
+
+from oracle import lfmmi_oracle as oracle
+from paper_2005_09824_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+OBJF_RTOL = 1e-4
+GRAD_ATOL = 1e-4
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def run_gpu(handle, logits, lengths, leak, **kw):
+    torch = _torch()
+    x = torch.from_numpy(np.ascontiguousarray(logits)).cuda()
+    objf, grad, status = binding.lfmmi_forward_backward(handle, x, lengths, leak, **kw)
+    torch.cuda.synchronize()
+    return objf.cpu().numpy(), grad.cpu().numpy(), status.cpu().numpy()
+
+
+def check(objf, grad, status, lz, gamma, what=""):
+    assert np.all(status == 0), (what, status)
+    rel = np.abs(objf.astype(np.float64) - lz) / np.maximum(np.abs(lz), 1e-30)
+    assert np.all(rel <= OBJF_RTOL), (what, "objf", rel.max())
+    err = np.abs(grad.astype(np.float64) - gamma).max() if gamma.size else 0.0
+    assert err <= GRAD_ATOL, (what, "grad", err)
+    return float(rel.max()) if rel.size else 0.0, float(err)
+
+
+def test_config1_denominator_numerators_and_full_loss():
+    wl = workloads.make_workload(1, pad_value=np.nan)
+    den = binding.lfmmi_graph_create(wl["den"])
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    lz_d, g_d = oracle.forward_backward(wl["den"], x, lens, leak)
+    lz_n, g_n = oracle.forward_backward_per_utt(wl["num"], x, lens, leak)
+    check(*run_gpu(den, x, lens, leak), lz_d, g_d, "den")
+    check(*run_gpu(num, x, lens, leak), lz_n, g_n, "num")
+    # Eq. 2 / Eq. 3: numerators with (+1, overwrite), denominator with (-1, accumulate)
+    torch = _torch()
+    xd = torch.from_numpy(x).cuda()
+    objf, grad, status = binding.lfmmi_forward_backward(num, xd, lens, leak, 1.0, False)
+    binding.lfmmi_forward_backward(den, xd, lens, leak, -1.0, True, objf, grad, status)
+    torch.cuda.synchronize()
+    objf, grad = objf.cpu().numpy().astype(np.float64), grad.cpu().numpy().astype(np.float64)
+    tol = OBJF_RTOL * np.maximum(np.maximum(np.abs(lz_n), np.abs(lz_d)), 1.0)
+    assert np.all(np.abs(objf - (lz_n - lz_d)) <= tol)
+    assert np.abs(grad - (g_n - g_d)).max() <= GRAD_ATOL
+    assert np.all(status.cpu().numpy() == 0)
+    den.close(); num.close()
+
+
+@pytest.mark.parametrize("config,scale", [
+    (2, {"S": 300, "B": 5, "Tlo": 30, "Thi": 70}),          # several slices, ragged tail
+    (2, {"S": 2000, "B": 3, "Tlo": 20, "Thi": 40}),          # the metric's graph, short
+    (3, {"S": 700, "P": 300, "B": 4, "Tlo": 20, "Thi": 50}),  # Zipf pdfs, P > 256
+    (4, {"S": 500, "B": 4, "Tlo": 100, "Thi": 400}),         # unsorted lengths, +-30 spikes
+])
+def test_scaled_configs_every_element(config, scale):
+    wl = workloads.make_workload(config, scale=scale, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    lz, gamma = oracle.forward_backward(wl["den"], wl["logits"], wl["lengths"], wl["leak"])
+    out = run_gpu(h, wl["logits"], wl["lengths"], wl["leak"])
+    check(*out, lz, gamma, "config %d scaled" % config)
+    # padded rows are exactly zero and valid rows sum to one
+    for b, Tb in enumerate(wl["lengths"]):
+        assert np.all(out[1][b, Tb:] == 0.0)
+        assert np.allclose(out[1][b, :Tb].sum(1), 1.0, atol=2e-4)
+    h.close()
+
+
+def test_config5_scaled_full_loss():
+    wl = workloads.make_workload(5, scale={"S": 400, "B": 6, "nlo": 5, "nhi": 25})
+    den = binding.lfmmi_graph_create(wl["den"])
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    lz_n, g_n = oracle.forward_backward_per_utt(wl["num"], x, lens, leak)
+    lz_d, g_d = oracle.forward_backward(wl["den"], x, lens, leak)
+    want_objf, want_grad = lz_n - lz_d, g_n - g_d
+    check(*run_gpu(num, x, lens, leak), lz_n, g_n, "num")
+    o_d = run_gpu(den, x, lens, leak)
+    check(*o_d, lz_d, g_d, "den")
+    torch = _torch()
+    xd = torch.from_numpy(x).cuda()
+    objf, grad, status = binding.lfmmi_forward_backward(num, xd, lens, leak, 1.0, False)
+    binding.lfmmi_forward_backward(den, xd, lens, leak, -1.0, True, objf, grad, status)
+    torch.cuda.synchronize()
+    tol = OBJF_RTOL * np.maximum(np.maximum(np.abs(lz_n), np.abs(lz_d)), 1.0)
+    assert np.all(np.abs(objf.cpu().numpy().astype(np.float64) - want_objf) <= tol)
+    assert np.abs(grad.cpu().numpy().astype(np.float64) - want_grad).max() <= GRAD_ATOL
+    den.close(); num.close()
+
+
+def test_edge_cases_lengths_zero_empty_batch_and_leak_zero():
+    torch = _torch()
+    wl = workloads.make_workload(2, scale={"S": 130, "B": 4, "Tlo": 3, "Thi": 9})
+    g = wl["den"]
+    g["init_prob"] = np.random.default_rng(0).uniform(0, 1, 130).astype(np.float32)
+    g["final_prob"] = np.random.default_rng(1).uniform(0, 1, 130).astype(np.float32)
+    h = binding.lfmmi_graph_create(g)
+    lens = wl["lengths"].copy()
+    lens[1] = 0                       # an empty sequence: log Z = log(f^T L pi)
+    lens[2] = 1
+    for leak in (0.0, 1e-5, 0.25):
+        lz, gamma = oracle.forward_backward(g, wl["logits"], lens, leak)
+        check(*run_gpu(h, wl["logits"], lens, leak), lz, gamma, "leak %g" % leak)
+    # B = 0 and T = 0
+    x0 = torch.zeros((0, 4, 84), dtype=torch.float32, device="cuda")
+    binding.lfmmi_forward_backward(h, x0, np.zeros(0, np.int32), 1e-5)
+    x1 = torch.zeros((2, 0, 84), dtype=torch.float32, device="cuda")
+    objf, grad, status = binding.lfmmi_forward_backward(h, x1, np.zeros(2, np.int32), 1e-5)
+    torch.cuda.synchronize()
+    lz, _ = oracle.forward_backward(g, np.zeros((2, 0, 84), np.float32), np.zeros(2, np.int32), 1e-5)
+    assert np.allclose(objf.cpu().numpy(), lz, rtol=1e-5)
+    h.close()
+
+
+def test_dead_sequences_and_nonfinite_logits_are_flagged():
+    # a chain that needs exactly 5 frames: T = 4 has zero probability without a leak
+    K, P = 6, 3
+    src = np.arange(K - 1, dtype=np.int32)
+    g = {"num_states": K, "num_pdfs": P, "src": src, "dst": src + 1,
+         "pdf": (src % P).astype(np.int32), "logw": np.zeros(K - 1, np.float32),
+         "init_prob": np.eye(K, dtype=np.float32)[0], "final_prob": np.eye(K, dtype=np.float32)[K - 1]}
+    h = binding.lfmmi_graph_create(g)
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(3, 5, P)).astype(np.float32)
+    lens = np.array([5, 4, 5], dtype=np.int32)
+    x[2, 3, 1] = np.nan
+    objf, grad, status = run_gpu(h, x, lens, 0.0)
+    lz, gamma = oracle.forward_backward(g, x[:1], lens[:1], 0.0)
+    assert status.tolist() == [0, 1, 3]
+    assert abs(objf[0] - lz[0]) <= OBJF_RTOL * abs(lz[0])
+    assert np.abs(grad[0] - gamma[0]).max() <= GRAD_ATOL
+    assert objf[1] == -np.inf and np.isnan(objf[2])
+    assert np.all(grad[1:] == 0.0)
+    h.close()
+
+
+def test_sequence_result_does_not_depend_on_batch_neighbours():
+    wl = workloads.make_workload(2, scale={"S": 200, "B": 6, "Tlo": 10, "Thi": 30})
+    h = binding.lfmmi_graph_create(wl["den"])
+    full = run_gpu(h, wl["logits"], wl["lengths"], wl["leak"])
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    part = run_gpu(h, wl["logits"][perm], wl["lengths"][perm], wl["leak"])
+    assert np.allclose(full[0][perm], part[0], rtol=1e-6)
+    assert np.allclose(full[1][perm], part[1], atol=1e-6)
+    h.close()

@@ -1,0 +1,175 @@
+"""CPU-side tests: the C-ABI library loads and exports what include/lfmmi.h
+declares, the graph packer keeps every arc exactly once in each of its three
+orderings, and argument errors come back as status codes with a message.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2005_09824_amd import binding, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "lfmmi.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)  # declarations only
+    declared = set(re.findall(r"\b(lfmmi_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = binding.load_library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+def _unpack(graph_handle, g, graph):
+    """Rebuild (src, dst, pdf, w) lists from each packed ordering."""
+    od = [binding.lfmmi_graph_ordering_copy(graph_handle, g, o) for o in range(3)]
+    state_of = [od[0]["row_id"], od[1]["row_id"]]  # position -> state, per numbering
+    out = []
+    for o in range(3):
+        d = od[o]
+        arcs = []
+        assert d["slice_off"][0] == 0 and d["slice_off"][-1] == d["total_slots"]
+        assert d["wave_first"][0] == 0 and d["wave_first"][-1] == d["slices"]
+        assert np.all(np.diff(d["wave_first"]) >= 0)
+        per_wave = []
+        for wv in range(d["waves"]):
+            s0, s1 = d["wave_first"][wv], d["wave_first"][wv + 1]
+            per_wave.append(int(d["slice_off"][s1] - d["slice_off"][s0]))
+        assert max(per_wave) == d["max_wave_slots"]
+        for s in range(d["slices"]):
+            o0, o1 = d["slice_off"][s], d["slice_off"][s + 1]
+            for lane in range(64):
+                row = s * 64 + lane
+                seen_pad = False
+                for i in range(o0, o1):
+                    k, w = int(d["key"][i * 64 + lane]), float(d["w"][i * 64 + lane])
+                    if w == 0.0:
+                        seen_pad = True
+                        assert k == 0
+                        continue
+                    assert not seen_pad, "real arcs must come before the padding of a row"
+                    assert d["row_id"][row] >= 0
+                    x, y = (k & 0xFFFF) // 4, (k >> 16) // 4
+                    if o == 0:
+                        arcs.append((int(state_of[0][x]), int(d["row_id"][row]), y, w))
+                    elif o == 1:
+                        arcs.append((int(d["row_id"][row]), int(state_of[1][x]), y, w))
+                    else:
+                        arcs.append((int(state_of[0][x]), int(state_of[1][y]),
+                                     int(d["row_id"][row]), w))
+        out.append(sorted(arcs))
+    want = sorted(zip(graph["src"].tolist(), graph["dst"].tolist(), graph["pdf"].tolist(),
+                      np.exp(graph["logw"].astype(np.float64)).astype(np.float32).tolist()))
+    return out, want, od
+
+
+@pytest.mark.parametrize("which", ["tiny", "den_scaled", "zipf"])
+def test_pack_keeps_every_arc_once(which):
+    if which == "tiny":
+        g = workloads.make_workload(1)["den"]
+    elif which == "den_scaled":
+        g = workloads.make_workload(2, scale={"S": 300, "B": 2, "Tlo": 5, "Thi": 6})["den"]
+    else:
+        g = workloads.make_workload(3, scale={"S": 200, "P": 50, "B": 2, "Tlo": 5, "Thi": 6})["den"]
+    h = binding.lfmmi_graph_pack(g)
+    got, want, od = _unpack(h, 0, g)
+    for o in range(3):
+        assert got[o] == want, "ordering %d lost or changed arcs" % o
+    S = g["num_states"]
+    for o in range(2):
+        ids = od[o]["row_id"]
+        assert sorted(ids[ids >= 0].tolist()) == list(range(S))  # a permutation of the states
+        assert od[o]["rows"] == S and od[o]["slices"] == (S + 63) // 64
+    info = binding.lfmmi_graph_info(h)
+    assert info["num_graphs"] == 1 and info["total_arcs"] == len(g["src"]) and info["uploaded"] == 0
+    h.close()
+
+
+def test_pack_batch_of_numerators():
+    wl = workloads.make_workload(5, scale={"B": 5, "nlo": 3, "nhi": 9})
+    h = binding.lfmmi_graph_pack_batch(wl["num"])
+    assert binding.lfmmi_graph_info(h)["num_graphs"] == 5
+    for g in range(5):
+        got, want, _ = _unpack(h, g, wl["num"][g])
+        for o in range(3):
+            assert got[o] == want
+    h.close()
+
+
+def test_pack_waves_are_balanced():
+    g = workloads.make_workload(2)["den"]
+    h = binding.lfmmi_graph_pack(g)
+    info = binding.lfmmi_graph_info(h)
+    assert info["rec_waves"] == 16
+    for o in range(3):
+        oi = binding.lfmmi_graph_ordering_info(h, 0, o)
+        ideal = len(g["src"]) / (64.0 * oi["waves"])
+        assert oi["max_wave_slots"] <= 1.35 * ideal + 2, (o, oi, ideal)
+    h.close()
+
+
+def test_graph_with_no_arcs_and_isolated_states():
+    g = {"num_states": 3, "num_pdfs": 2, "src": np.zeros(0, np.int32), "dst": np.zeros(0, np.int32),
+         "pdf": np.zeros(0, np.int32), "logw": np.zeros(0, np.float32),
+         "init_prob": np.ones(3, np.float32), "final_prob": np.ones(3, np.float32)}
+    h = binding.lfmmi_graph_pack(g)
+    assert binding.lfmmi_graph_ordering_info(h, 0, 0)["total_slots"] == 0
+    h.close()
+
+
+def _tiny():
+    return {"num_states": 2, "num_pdfs": 2, "src": np.array([0, 1], np.int32),
+            "dst": np.array([1, 0], np.int32), "pdf": np.array([0, 1], np.int32),
+            "logw": np.zeros(2, np.float32), "init_prob": np.array([1, 0], np.float32),
+            "final_prob": np.array([0, 1], np.float32)}
+
+
+@pytest.mark.parametrize("field,value,code", [
+    ("src", np.array([0, 2], np.int32), 2),
+    ("dst", np.array([-1, 0], np.int32), 2),
+    ("pdf", np.array([0, 2], np.int32), 2),
+    ("logw", np.array([0, np.nan], np.float32), 2),
+    ("logw", np.array([-np.inf, 0], np.float32), 2),
+    ("init_prob", np.array([-1, 0], np.float32), 2),
+    ("final_prob", np.array([np.inf, 0], np.float32), 2),
+])
+def test_bad_graphs_are_refused(field, value, code):
+    g = _tiny()
+    g[field] = value
+    with pytest.raises(binding.LfmmiError) as ei:
+        binding.lfmmi_graph_pack(g)
+    assert ei.value.code == code and str(ei.value)
+
+
+def test_unsupported_sizes_and_invalid_arguments():
+    g = _tiny()
+    g["num_pdfs"] = 20000
+    with pytest.raises(binding.LfmmiError) as ei:
+        binding.lfmmi_graph_pack(g)
+    assert ei.value.code == 5
+    big = {"num_states": 17000, "num_pdfs": 2, "src": np.zeros(1, np.int32),
+           "dst": np.zeros(1, np.int32), "pdf": np.zeros(1, np.int32),
+           "logw": np.zeros(1, np.float32), "init_prob": np.ones(17000, np.float32),
+           "final_prob": np.ones(17000, np.float32)}
+    with pytest.raises(binding.LfmmiError) as ei:
+        binding.lfmmi_graph_pack(big)
+    assert ei.value.code == 5
+    lib = binding.load_library()
+    out = ctypes.c_void_p()
+    assert lib.lfmmi_graph_pack(0, 1, 0, None, None, None, None, None, None, ctypes.byref(out)) == 1
+    assert lib.lfmmi_graph_pack(1, 1, 0, None, None, None, None, None, None, ctypes.byref(out)) == 1
+    assert "null" in binding.lfmmi_last_error()
+    assert lib.lfmmi_forward_backward(None, None, None, 1, 1, 1, 0.0, 1.0, 0, None, None, None, None) == 1
+    # a packed-only handle cannot run
+    h = binding.lfmmi_graph_pack(_tiny())
+    lens = np.array([1], np.int32)
+    rc = lib.lfmmi_forward_backward(h.handle, None, ctypes.c_void_p(lens.ctypes.data), 1, 1, 2,
+                                    0.0, 1.0, 0, None, None, None, None)
+    assert rc == 1 and "not uploaded" in binding.lfmmi_last_error()
+    h.close()
+    lib.lfmmi_graph_destroy(None)  # no-op
