@@ -1,0 +1,136 @@
+#!/usr/bin/env python3
+"""Benchmark of the LF-MMI forward-backward hot path on one MI355X.
+
+A step is one lfmmi_forward_backward call (emission, alpha/beta recursion,
+scale scan, occupancy + gradient) over one synthetic batch already resident in
+HBM. Default workload: the WSJ-monophone-shaped case the headline metric is
+quoted on (2,000-state / 20,000-arc denominator graph, 84 pdfs, B = 64,
+T in [100, 500]). Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 128 B/clk LDS x 2.4 GHz
+LDS_PEAK_GBPS = 256 * 128 * 2.4
+HBM_PEAK_GBPS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 is the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; sequences are independent, so "
+              "several GPUs would each take a share of the batch with no communication. "
+              "Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2005_09824_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    wl = workloads.make_workload(args.config)
+    lengths, leak = wl["lengths"], wl["leak"]
+    frames = int(lengths.sum())
+    B, T, P = wl["logits"].shape
+    x = torch.from_numpy(wl["logits"]).cuda()
+    den = binding.lfmmi_graph_create(wl["den"])
+    num = binding.lfmmi_graph_create_batch(wl["num"]) if args.config == 5 else None
+    S, A = wl["den"]["num_states"], len(wl["den"]["src"])
+    objf = torch.empty(B, dtype=torch.float32, device="cuda")
+    grad = torch.empty((B, T, P), dtype=torch.float32, device="cuda")
+    status = torch.zeros(B, dtype=torch.int32, device="cuda")
+
+    def step():
+        if num is not None:  # Eq. 2 / Eq. 3: numerator minus denominator
+            binding.lfmmi_forward_backward(num, x, lengths, leak, 1.0, False, objf, grad, status)
+            binding.lfmmi_forward_backward(den, x, lengths, leak, -1.0, True, objf, grad, status)
+        else:
+            binding.lfmmi_forward_backward(den, x, lengths, leak, 1.0, False, objf, grad, status)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.lfmmi_profile_enable(den, True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern = binding.lfmmi_profile_read(den)
+    binding.lfmmi_profile_enable(den, False)
+    if int(status.abs().sum().item()) != 0:
+        print("bench.py: a sequence was flagged", file=sys.stderr)
+        return 1
+
+    ms_per_step = dt / args.steps * 1e3
+    fps = frames / (dt / args.steps)
+
+    # dominant kernel: the alpha/beta recursion. Algorithmic LDS bytes per frame:
+    # per arc and direction two 4-byte gathers (state vector, emission), per state
+    # and direction 12 bytes (write, re-read for the rescale, write back).
+    rec_bytes = frames * (16.0 * A + 24.0 * S)
+    rec_s = kern["rec"] * 1e-3
+    achieved = rec_bytes / rec_s / 1e9
+    info = binding.lfmmi_graph_info(den)
+    out = {
+        "metric": "LF-MMI forward-backward frames/sec (loss+grad), 2k-state den graph, B=64",
+        "value": fps,
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl["name"], "states": S, "arcs": A, "pdfs": P, "batch": B,
+                   "frames": frames, "max_len": T, "leak": leak,
+                   "numerators": num is not None},
+        "roofline": {"bound": "lds", "kernel": "k_rec", "achieved": achieved,
+                     "peak": LDS_PEAK_GBPS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBPS,
+                     "traffic": None,
+                     "workgroups": 2 * B, "compute_units": 256},
+        "kernels_ms": {k: kern[k] for k in ("emit", "rec", "scan", "occ")},
+        "arc_updates_per_s": 2.0 * A * fps,
+        "workspace_bytes": info["workspace_bytes"],
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import lfmmi_oracle as oracle
+        threads = oracle.max_threads()
+        t0 = time.perf_counter()
+        if num is not None:
+            oracle.loss(wl["num"], wl["den"], wl["logits"], lengths, leak)
+        else:
+            oracle.forward_backward(wl["den"], wl["logits"], lengths, leak)
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": frames / cdt, "unit": "frames/s", "cores": threads,
+                               "kind": "oracle",
+                               "sample": "the whole batch once (%d frames), fp64 log-domain, "
+                                         "OpenMP over sequences" % frames}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

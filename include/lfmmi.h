@@ -49,8 +49,10 @@ typedef enum {
  *   src, dst [num_arcs] in [0, num_states); pdf [num_arcs] in [0, num_pdfs);
  *   logw [num_arcs] natural-log weight, finite (drop an arc instead of -inf);
  *   init_prob, final_prob [num_states] linear, >= 0, finite, not normalised.
- * Limits: num_states <= 16320, num_pdfs <= 16384 (LDS residency), else
- * LFMMI_ERR_UNSUPPORTED. num_arcs may be 0.
+ * Limits (the recursion keeps two state vectors and two emission rows in the
+ * 160 KB of LDS of a compute unit): num_states <= 16384, num_pdfs <= 16384 and
+ * 8 * (num_states rounded up to 64) + 8 * (num_pdfs rounded up to 64) + 128
+ * <= 163840 bytes, else LFMMI_ERR_UNSUPPORTED. num_arcs may be 0.
  * lfmmi_graph_create packs and uploads to the current HIP device.
  * lfmmi_graph_pack only packs (no HIP call): for host-side inspection; such a
  * handle is refused by lfmmi_forward_backward until lfmmi_graph_upload.
@@ -151,13 +153,14 @@ lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph *graph, int32_t g, int3
                                        int32_t *slice_off, int32_t *wave_first,
                                        uint32_t *key, float *w, int32_t *row_id);
 
-/* Per-kernel timing with HIP events on the caller's stream. enable != 0 makes
- * every following lfmmi_forward_backward on this handle record events around
- * its kernels; lfmmi_profile_read waits for the last call and returns
- * milliseconds: ms[0] emission, [1] recursion (alpha and beta), [2] scales,
- * [3] occupancy + gradient. */
+/* Per-kernel timing with HIP events on the caller's stream. While enabled,
+ * every lfmmi_forward_backward on this handle records events around its four
+ * kernels. lfmmi_profile_read waits for the last such call, returns the mean
+ * duration per call in milliseconds - ms[0] emission, [1] recursion (alpha and
+ * beta), [2] scales, [3] occupancy + gradient - and the number of calls averaged
+ * in *calls (may be NULL), then forgets them. */
 lfmmi_status lfmmi_profile_enable(lfmmi_graph *graph, int enable);
-lfmmi_status lfmmi_profile_read(lfmmi_graph *graph, float ms[4]);
+lfmmi_status lfmmi_profile_read(lfmmi_graph *graph, float ms[4], int32_t *calls);
 
 #ifdef __cplusplus
 }

@@ -69,9 +69,9 @@ struct lfmmi_graph {
     hipEvent_t stage_done = nullptr;
     bool stage_pending = false;
 
+    // profiling: one set of 5 events per call made while enabled
     bool profile = false;
-    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
-    bool ev_recorded = false;
+    std::vector<hipEvent_t> ev;
 };
 
 namespace {
@@ -331,8 +331,7 @@ void lfmmi_graph_destroy(lfmmi_graph* h)
         if (h->ws) (void)hipFree(h->ws);
         if (h->stage) (void)hipHostFree(h->stage);
         if (h->stage_done) (void)hipEventDestroy(h->stage_done);
-        for (hipEvent_t e : h->ev)
-            if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
     }
     delete h;
 }
@@ -486,13 +485,18 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
 
     hipEvent_t* ev = nullptr;
     if (h->profile) {
-        for (hipEvent_t& x : h->ev)
-            if (!x && (e = hipEventCreate(&x)) != hipSuccess) return fail_hip(e, "hipEventCreate");
-        ev = h->ev;
+        const size_t first = h->ev.size();
+        h->ev.resize(first + 5, nullptr);
+        for (size_t i = first; i < first + 5; ++i)
+            if ((e = hipEventCreate(&h->ev[i])) != hipSuccess) {
+                for (size_t j = first; j < i; ++j) (void)hipEventDestroy(h->ev[j]);
+                h->ev.resize(first);
+                return fail_hip(e, "hipEventCreate");
+            }
+        ev = h->ev.data() + first;
     }
     if ((e = launch_forward_backward(p, shape, stream, ev)) != hipSuccess)
         return fail_hip(e, "kernel launch");
-    h->ev_recorded = ev != nullptr;
     return LFMMI_OK;
 }
 
@@ -546,20 +550,34 @@ lfmmi_status lfmmi_profile_enable(lfmmi_graph* h, int enable)
 {
     if (!h) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
     h->profile = enable != 0;
-    if (!h->profile) h->ev_recorded = false;
     return LFMMI_OK;
 }
 
-lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4])
+lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4], int32_t* calls)
 {
     if (!h || !ms) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
-    if (!h->ev_recorded) return fail(LFMMI_ERR_INVALID_ARG, "no profiled call to read");
-    hipError_t e = hipEventSynchronize(h->ev[4]);
-    if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
-    for (int i = 0; i < 4; ++i)
-        if ((e = hipEventElapsedTime(&ms[i], h->ev[i], h->ev[i + 1])) != hipSuccess)
-            return fail_hip(e, "hipEventElapsedTime");
-    return LFMMI_OK;
+    const size_t n = h->ev.size() / 5;
+    if (calls) *calls = (int32_t)n;
+    for (int i = 0; i < 4; ++i) ms[i] = 0.f;
+    if (n == 0) return fail(LFMMI_ERR_INVALID_ARG, "no profiled call to read");
+    hipError_t e = hipEventSynchronize(h->ev.back());
+    lfmmi_status st = LFMMI_OK;
+    if (e != hipSuccess) st = fail_hip(e, "hipEventSynchronize");
+    double sum[4] = {0, 0, 0, 0};
+    for (size_t c = 0; c < n && st == LFMMI_OK; ++c)
+        for (int i = 0; i < 4; ++i) {
+            float t = 0.f;
+            if ((e = hipEventElapsedTime(&t, h->ev[c * 5 + i], h->ev[c * 5 + i + 1])) != hipSuccess) {
+                st = fail_hip(e, "hipEventElapsedTime");
+                break;
+            }
+            sum[i] += t;
+        }
+    for (hipEvent_t x : h->ev) (void)hipEventDestroy(x);
+    h->ev.clear();
+    if (st == LFMMI_OK)
+        for (int i = 0; i < 4; ++i) ms[i] = (float)(sum[i] / (double)n);
+    return st;
 }
 
 }  // extern "C"
