@@ -53,6 +53,9 @@ typedef enum {
  * 160 KB of LDS of a compute unit): num_states <= 16384, num_pdfs <= 16384 and
  * 8 * (num_states rounded up to 64) + 8 * (num_pdfs rounded up to 64) + 128
  * <= 163840 bytes, else LFMMI_ERR_UNSUPPORTED. num_arcs may be 0.
+ * When some state has final_prob == 0 (numerator-like graphs) the state
+ * vectors, trellis and scales are kept in fp64 and the limit above counts 16
+ * bytes per state; when every state is final they are fp32.
  * lfmmi_graph_create packs and uploads to the current HIP device.
  * lfmmi_graph_pack only packs (no HIP call): for host-side inspection; such a
  * handle is refused by lfmmi_forward_backward until lfmmi_graph_upload.
@@ -132,7 +135,8 @@ enum { LFMMI_ORD_FWD = 0, LFMMI_ORD_BWD = 1, LFMMI_ORD_OCC = 2 };
 
 /* info[0] number of graphs, [1] num_pdfs, [2] total states, [3] total arcs,
  * [4] waves per workgroup of the recursion kernel, [5] waves of the occupancy
- * kernel, [6] 1 if uploaded, [7] workspace bytes currently held. */
+ * kernel, [6] flags (bit 0: uploaded; bit 1: state vectors kept in fp64, which
+ * is chosen when some state has final_prob 0), [7] workspace bytes held. */
 lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
 
 /* Packed ordering `ord` of graph `g`: info[0] rows, [1] slices (64 rows each),

@@ -180,8 +180,11 @@ def lfmmi_graph_info(graph):
     info = np.zeros(8, dtype=np.int64)
     _check(load_library().lfmmi_graph_info(graph.handle, _hp(info)))
     keys = ("num_graphs", "num_pdfs", "total_states", "total_arcs", "rec_waves",
-            "occ_waves", "uploaded", "workspace_bytes")
-    return dict(zip(keys, (int(v) for v in info)))
+            "occ_waves", "flags", "workspace_bytes")
+    out = dict(zip(keys, (int(v) for v in info)))
+    out["uploaded"] = out["flags"] & 1
+    out["fp64"] = (out["flags"] >> 1) & 1
+    return out
 
 
 def lfmmi_graph_ordering_info(graph, g, ord_):

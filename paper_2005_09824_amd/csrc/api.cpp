@@ -53,6 +53,7 @@ struct lfmmi_graph {
     std::vector<PackedGraph> packed;
     std::vector<OrdDesc> ords;  // [num_graphs * 3]
     int32_t max_rows_f = 0, max_rows_b = 0;
+    bool wide = false;  // fp64 state vectors (some state is not final)
 
     // device copy
     bool uploaded = false;
@@ -135,10 +136,19 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
             h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
         }
-        const size_t ppad = (size_t)(num_pdfs + 63) / 64 * 64;
-        const size_t rows = (size_t)std::max(h->max_rows_f, h->max_rows_b);
-        if ((2 * rows + 2 * ppad + 32) * 4 > kLdsBytes ||
-            ((size_t)h->max_rows_f + h->max_rows_b + 2 * ppad) * 4 > kLdsBytes) {
+        // Every state final: the scaled alpha / beta stay comparable across the
+        // states that carry posterior mass, and fp32 holds them. Otherwise
+        // (left-to-right numerator graphs) that mass can sit tens of orders of
+        // magnitude below the frame total: fp64.
+        bool all_final = true;
+        for (int64_t s = 0; s < state_off[n]; ++s) all_final = all_final && final_prob[s] > 0.f;
+        h->wide = !all_final;
+        if (const char* v = std::getenv("LFMMI_PRECISION")) {
+            if (std::atoi(v) == 64) h->wide = true;
+            if (std::atoi(v) == 32) h->wide = false;
+        }
+        if (rec_lds_bytes(std::max(h->max_rows_f, h->max_rows_b), num_pdfs, h->wide) > kLdsBytes ||
+            occ_lds_bytes(h->max_rows_f, h->max_rows_b, num_pdfs, h->wide) > kLdsBytes) {
             delete h;
             return fail(LFMMI_ERR_UNSUPPORTED,
                         "states and pdfs do not fit the 160 KB of LDS of one compute unit");
@@ -398,11 +408,12 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     const size_t stage_need = total;
     const size_t at_emis = reserve<float>(&total, (size_t)B * T * P);
     const size_t at_rowmax = reserve<float>(&total, (size_t)B * T);
-    const size_t at_alpha = reserve<float>(&total, (size_t)a_at);
-    const size_t at_beta = reserve<float>(&total, (size_t)b_at);
-    const size_t at_scal = reserve<float>(&total, (size_t)2 * s_at);
-    const size_t at_cfac = reserve<float>(&total, (size_t)s_at);
-    const size_t at_zfin = reserve<float>(&total, (size_t)2 * B);
+    const size_t real = h->wide ? 2 : 1;  // floats per value
+    const size_t at_alpha = reserve<float>(&total, (size_t)a_at * real);
+    const size_t at_beta = reserve<float>(&total, (size_t)b_at * real);
+    const size_t at_scal = reserve<float>(&total, (size_t)2 * s_at * real);
+    const size_t at_cfac = reserve<float>(&total, (size_t)s_at * real);
+    const size_t at_zfin = reserve<float>(&total, (size_t)2 * B * real);
     const size_t at_status = reserve<int32_t>(&total, B);
 
     if (total > h->ws_bytes) {
@@ -458,11 +469,12 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     p.logits = logits;
     p.emis = reinterpret_cast<float*>(ws + at_emis);
     p.rowmax = reinterpret_cast<float*>(ws + at_rowmax);
-    p.alpha = reinterpret_cast<float*>(ws + at_alpha);
-    p.beta = reinterpret_cast<float*>(ws + at_beta);
-    p.scal = reinterpret_cast<float*>(ws + at_scal);
-    p.cfac = reinterpret_cast<float*>(ws + at_cfac);
-    p.zfin = reinterpret_cast<float*>(ws + at_zfin);
+    p.alpha = ws + at_alpha;
+    p.beta = ws + at_beta;
+    p.scal = ws + at_scal;
+    p.cfac = ws + at_cfac;
+    p.zfin = ws + at_zfin;
+    p.wide = h->wide ? 1 : 0;
     p.status_ws = reinterpret_cast<int32_t*>(ws + at_status);
     p.status_out = status;
     p.objf = objf;
@@ -509,7 +521,7 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph* h, int64_t info[8])
     info[3] = h->total_arcs;
     info[4] = h->rec_waves;
     info[5] = h->occ_waves;
-    info[6] = h->uploaded ? 1 : 0;
+    info[6] = (h->uploaded ? 1 : 0) | (h->wide ? 2 : 0);
     info[7] = (int64_t)h->ws_bytes;
     return LFMMI_OK;
 }

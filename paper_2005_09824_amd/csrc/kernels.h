@@ -46,11 +46,12 @@ struct FbParams {
     const float* logits;    // [B, T, P]
     float* emis;            // [B, T, P] exp(logit - row max)
     float* rowmax;          // [B, T]
-    float* alpha;           // ragged trellis, (T_b + 1) rows of rows_f floats
-    float* beta;
-    float* scal;            // [2][scal_total] per-frame normalisers (alpha, beta)
-    float* cfac;            // [scal_total] occupancy scale of frame t at scal_at + t
-    float* zfin;            // [2][B] closing dot products (alpha side, beta side)
+    // the next five hold float, or double when `wide` is set
+    void* alpha;            // ragged trellis, (T_b + 1) rows of rows_f values
+    void* beta;
+    void* scal;             // [2][scal_total] per-frame normalisers (alpha, beta)
+    void* cfac;             // [scal_total] occupancy scale of frame t at scal_at + t
+    void* zfin;             // [2][B] closing dot products (alpha side, beta side)
     int32_t* status_ws;     // [B]
     int32_t* status_out;    // [B] or null
     float* objf;            // [B]
@@ -60,6 +61,7 @@ struct FbParams {
     int32_t lds_rows;       // largest padded row count over the handle's graphs
     int32_t lds_rows_occ_a, lds_rows_occ_b;
     int32_t accumulate;
+    int32_t wide;           // 1: state vectors, trellis and scales in fp64
     float leak, grad_scale;
 };
 
@@ -74,5 +76,8 @@ struct LaunchShape {
 hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
                                    hipStream_t stream, hipEvent_t* ev);
 hipError_t configure_kernels();
+// Dynamic LDS the recursion / occupancy kernels need.
+size_t rec_lds_bytes(int lds_rows, int P, bool wide);
+size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide);
 
 }  // namespace lfmmi

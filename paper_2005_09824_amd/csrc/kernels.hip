@@ -20,7 +20,8 @@
 namespace lfmmi {
 namespace {
 
-__device__ __forceinline__ float wave_sum(float v)
+template <typename Real>
+__device__ __forceinline__ Real wave_sum(Real v)
 {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -34,9 +35,12 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-__device__ __forceinline__ float lds_at(const float* base, uint32_t byte_off)
+// Element of an LDS array addressed by the record's index * 4 field.
+template <typename Real>
+__device__ __forceinline__ Real lds_at(const Real* base, uint32_t index4)
 {
-    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+    return *reinterpret_cast<const Real*>(reinterpret_cast<const char*>(base) +
+                                          index4 * (uint32_t)(sizeof(Real) / 4));
 }
 
 // ---------------------------------------------------------------------------
@@ -73,6 +77,18 @@ __global__ void __launch_bounds__(256) k_emit(FbParams p)
 // ---------------------------------------------------------------------------
 constexpr int kYRegs = 4;
 
+// One arc slot: w * e[pdf] in fp32, times the gathered state value in Real.
+template <typename Real>
+__device__ __forceinline__ Real arc_term(const uint2 r, const Real* X, const float* Y)
+{
+    return (Real)(__uint_as_float(r.y) * lds_at(Y, r.x >> 16)) * lds_at(X, r.x & 0xffffu);
+}
+
+// Real = float for graphs whose states are all final (denominator-like: the
+// scaled vectors stay within fp32 range), double otherwise (numerator-like
+// left-to-right graphs, where the states that matter can hold a fraction of the
+// frame's mass far below 1e-38).
+template <typename Real>
 __global__ void __launch_bounds__(1024) k_rec(FbParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -90,19 +106,20 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
     const int rows = od.num_slices * 64;
     const int Ppad = (P + 63) & ~63;
 
-    float* X0 = reinterpret_cast<float*>(lds_raw);
-    float* X1 = X0 + p.lds_rows;
-    float* Y0 = X1 + p.lds_rows;
+    Real* X0 = reinterpret_cast<Real*>(lds_raw);
+    Real* X1 = X0 + p.lds_rows;
+    Real* part = X1 + p.lds_rows;  // [16][2]
+    float* Y0 = reinterpret_cast<float*>(part + 32);
     float* Y1 = Y0 + Ppad;
-    float* part = Y1 + Ppad;  // [nwaves][2]
 
-    float* trel = dir == 0 ? p.alpha + sd.alpha_at : p.beta + sd.beta_at;
-    float* scal = p.scal + (size_t)dir * p.scal_total + sd.scal_at;
+    Real* trel = static_cast<Real*>(dir == 0 ? p.alpha : p.beta) +
+                 (dir == 0 ? sd.alpha_at : sd.beta_at);
+    Real* scal = static_cast<Real*>(p.scal) + (size_t)dir * p.scal_total + sd.scal_at;
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const float* va = p.g.va + od.vec_at;
     const float* vb = p.g.vb + od.vec_at;
-    const float eps = p.leak;
+    const Real eps = (Real)p.leak;
 
     int s0 = 0, s1 = 0;
     if (wave < od.num_waves) {
@@ -113,26 +130,26 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
 
     // ---- step 0: vhat_0 = leak(init) / sum(init)
     {
-        float n = 0.f, s = 0.f;
+        Real n = 0, s = 0;
         for (int sl = s0; sl < s1; ++sl) {
             const int row = sl * 64 + lane;
-            const float v = p.g.vinit[od.vec_at + row];
+            const Real v = (Real)p.g.vinit[od.vec_at + row];
             X0[row] = v;
             n += v;
-            s = fmaf(va[row], v, s);
+            s += (Real)va[row] * v;
         }
         n = wave_sum(n);
         s = wave_sum(s);
         if (lane == 0) { part[wave * 2] = n; part[wave * 2 + 1] = s; }
         __syncthreads();
-        float N = 0.f, Sd = 0.f;
+        Real N = 0, Sd = 0;
         for (int w = 0; w < nwaves; ++w) { N += part[w * 2]; Sd += part[w * 2 + 1]; }
-        const float inv = N > 0.f ? 1.f / N : 0.f;
-        const float c = eps * Sd * inv;
+        const Real inv = N > 0 ? (Real)1 / N : (Real)0;
+        const Real c = eps * Sd * inv;
         const int ti = dir == 0 ? 0 : T;
         for (int sl = s0; sl < s1; ++sl) {
             const int row = sl * 64 + lane;
-            const float v = fmaf(c, vb[row], X0[row] * inv);
+            const Real v = c * (Real)vb[row] + X0[row] * inv;
             X0[row] = v;
             trel[(size_t)ti * rows + row] = v;
         }
@@ -147,8 +164,8 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
 
     // ---- steps 1..T
     for (int k = 1; k <= T; ++k) {
-        const float* Xc = (k & 1) ? X0 : X1;
-        float* Xn = (k & 1) ? X1 : X0;
+        const Real* Xc = (k & 1) ? X0 : X1;
+        Real* Xn = (k & 1) ? X1 : X0;
         const float* Yc = (k & 1) ? Y0 : Y1;
         float* Yn = (k & 1) ? Y1 : Y0;
 
@@ -163,44 +180,43 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
             yreg[i] = (more && d < P) ? en[d] : 0.f;
         }
 
-        float n = 0.f, s = 0.f;
+        Real n = 0, s = 0;
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
             const uint2* rp = recs + (size_t)o0 * 64;
-            float acc = 0.f;
+            Real acc = 0;
             int i = o0;
             for (; i + 4 <= o1; i += 4) {
                 const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
                 rp += 256;
-                acc = fmaf(__uint_as_float(r0.y) * lds_at(Yc, r0.x >> 16), lds_at(Xc, r0.x & 0xffffu), acc);
-                acc = fmaf(__uint_as_float(r1.y) * lds_at(Yc, r1.x >> 16), lds_at(Xc, r1.x & 0xffffu), acc);
-                acc = fmaf(__uint_as_float(r2.y) * lds_at(Yc, r2.x >> 16), lds_at(Xc, r2.x & 0xffffu), acc);
-                acc = fmaf(__uint_as_float(r3.y) * lds_at(Yc, r3.x >> 16), lds_at(Xc, r3.x & 0xffffu), acc);
+                acc += arc_term(r0, Xc, Yc);
+                acc += arc_term(r1, Xc, Yc);
+                acc += arc_term(r2, Xc, Yc);
+                acc += arc_term(r3, Xc, Yc);
             }
             for (; i < o1; ++i) {
-                const uint2 r0 = rp[0];
+                acc += arc_term(rp[0], Xc, Yc);
                 rp += 64;
-                acc = fmaf(__uint_as_float(r0.y) * lds_at(Yc, r0.x >> 16), lds_at(Xc, r0.x & 0xffffu), acc);
             }
             const int row = sl * 64 + lane;
             Xn[row] = acc;
             n += acc;
-            s = fmaf(va[row], acc, s);
+            s += (Real)va[row] * acc;
         }
         n = wave_sum(n);
         s = wave_sum(s);
         if (lane == 0) { part[wave * 2] = n; part[wave * 2 + 1] = s; }
         __syncthreads();
 
-        float N = 0.f, Sd = 0.f;
+        Real N = 0, Sd = 0;
         for (int w = 0; w < nwaves; ++w) { N += part[w * 2]; Sd += part[w * 2 + 1]; }
-        const float inv = N > 0.f ? 1.f / N : 0.f;
-        const float c = eps * Sd * inv;
+        const Real inv = N > 0 ? (Real)1 / N : (Real)0;
+        const Real c = eps * Sd * inv;
         const int ti = dir == 0 ? k : T - k;
-        float* tr = trel + (size_t)ti * rows;
+        Real* tr = trel + (size_t)ti * rows;
         for (int sl = s0; sl < s1; ++sl) {
             const int row = sl * 64 + lane;
-            const float v = fmaf(c, vb[row], Xn[row] * inv);
+            const Real v = c * (Real)vb[row] + Xn[row] * inv;
             Xn[row] = v;
             tr[row] = v;
         }
@@ -218,19 +234,19 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
 
     // ---- closing dot product: alpha side sum_j f[j] ahat_T[j], beta side sum_i pi[i] bhat_0[i]
     {
-        const float* Xc = (T & 1) ? X1 : X0;
-        float z = 0.f;
+        const Real* Xc = (T & 1) ? X1 : X0;
+        Real z = 0;
         for (int sl = s0; sl < s1; ++sl) {
             const int row = sl * 64 + lane;
-            z = fmaf(p.g.vfin[od.vec_at + row], Xc[row], z);
+            z += (Real)p.g.vfin[od.vec_at + row] * Xc[row];
         }
         z = wave_sum(z);
         if (lane == 0) part[wave * 2] = z;
         __syncthreads();
         if (tid == 0) {
-            float Z = 0.f;
+            Real Z = 0;
             for (int w = 0; w < nwaves; ++w) Z += part[w * 2];
-            p.zfin[(size_t)dir * p.B + b] = Z;
+            static_cast<Real*>(p.zfin)[(size_t)dir * p.B + b] = Z;
         }
     }
 }
@@ -240,6 +256,7 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
 // factor that turns ahat_{t-1} * w * e_t * bhat_t into an occupancy:
 //   c_t = exp(A_{t-1} + B_t - log Z'),  A, B = prefix / suffix sums of log n.
 // ---------------------------------------------------------------------------
+template <typename Real>
 __global__ void __launch_bounds__(256) k_scan(FbParams p)
 {
     __shared__ double sa[256], sb[256], sm[256];
@@ -249,8 +266,9 @@ __global__ void __launch_bounds__(256) k_scan(FbParams p)
     const SeqDesc sd = p.seqs[b];
     const int T = sd.T;
     const int n = T + 1;
-    const float* na = p.scal + sd.scal_at;
-    const float* nb = p.scal + p.scal_total + sd.scal_at;
+    const Real* na = static_cast<const Real*>(p.scal) + sd.scal_at;
+    const Real* nb = static_cast<const Real*>(p.scal) + p.scal_total + sd.scal_at;
+    Real* cfac = static_cast<Real*>(p.cfac) + sd.scal_at;
     const int chunk = (n + 255) / 256;
     const int i0 = min(tid * chunk, n), i1 = min(i0 + chunk, n);
     double la = 0.0, lb = 0.0, lm = 0.0;
@@ -272,12 +290,12 @@ __global__ void __launch_bounds__(256) k_scan(FbParams p)
     }
     __syncthreads();
     const double totB = tot[1], msum = tot[2];
-    const double lz = log((double)p.zfin[b]) + tot[0];
+    const double lz = log((double)static_cast<const Real*>(p.zfin)[b]) + tot[0];
     const bool nonfinite_in = !(msum == msum);
     const bool dead = !(lz > -INFINITY && lz < INFINITY) || nonfinite_in;
     double ra = sa[tid], rb = sb[tid];
     for (int i = i0; i < i1; ++i) {
-        if (i >= 1) p.cfac[sd.scal_at + i] = dead ? 0.f : (float)exp(ra + (totB - rb) - lz);
+        if (i >= 1) cfac[i] = dead ? (Real)0 : (Real)exp(ra + (totB - rb) - lz);
         ra += log((double)na[i]);
         rb += log((double)nb[i]);
     }
@@ -298,6 +316,13 @@ __global__ void __launch_bounds__(256) k_scan(FbParams p)
 // pieces of one pdf's arc list; a row's sum goes to its pdf's LDS bin.
 //   gamma_t[d] = c_t * e_t[d] * sum_{a: pdf_a = d} w_a * ahat_{t-1}[src_a] * bhat_t[dst_a]
 // ---------------------------------------------------------------------------
+template <typename Real>
+__device__ __forceinline__ Real occ_term(const uint2 r, const Real* XA, const Real* XB)
+{
+    return (Real)__uint_as_float(r.y) * lds_at(XB, r.x >> 16) * lds_at(XA, r.x & 0xffffu);
+}
+
+template <typename Real>
 __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -314,14 +339,15 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     const int rows_f = p.g.ords[sd.graph * 3 + 0].num_slices * 64;
     const int rows_b = p.g.ords[sd.graph * 3 + 1].num_slices * 64;
 
-    float* XA = reinterpret_cast<float*>(lds_raw);
-    float* XB = XA + p.lds_rows_occ_a;
-    float* bins0 = XB + p.lds_rows_occ_b;
-    float* bins1 = bins0 + Ppad;
+    Real* XA = reinterpret_cast<Real*>(lds_raw);
+    Real* XB = XA + p.lds_rows_occ_a;
+    Real* bins0 = XB + p.lds_rows_occ_b;
+    Real* bins1 = bins0 + Ppad;
 
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* row_pdf4 = p.g.row_pdf4 + od.vec_at;
+    const Real* cfac = static_cast<const Real*>(p.cfac) + sd.scal_at;
     int s0 = 0, s1 = 0;
     if (wave < od.num_waves) {
         s0 = p.g.wave_first[od.wave_first_at + wave];
@@ -333,46 +359,44 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     for (int t = t_first; t <= t_last; ++t) {
         const size_t at = ((size_t)b * p.T + (t - 1)) * P;
         float* g = p.grad + at;
-        const float c = t <= T ? p.cfac[sd.scal_at + t] : 0.f;
-        if (t > T || c == 0.f) {  // beyond the sequence, or a dead sequence
+        const Real c = t <= T ? cfac[t] : (Real)0;
+        if (t > T || c == (Real)0) {  // beyond the sequence, or a dead sequence
             if (!p.accumulate)
                 for (int d = tid; d < P; d += nthreads) g[d] = 0.f;
             continue;
         }
-        float* bins = (t & 1) ? bins1 : bins0;
-        const float* ar = p.alpha + sd.alpha_at + (size_t)(t - 1) * rows_f;
-        const float* br = p.beta + sd.beta_at + (size_t)t * rows_b;
+        Real* bins = (t & 1) ? bins1 : bins0;
+        const Real* ar = static_cast<const Real*>(p.alpha) + sd.alpha_at + (size_t)(t - 1) * rows_f;
+        const Real* br = static_cast<const Real*>(p.beta) + sd.beta_at + (size_t)t * rows_b;
         for (int r = tid; r < rows_f; r += nthreads) XA[r] = ar[r];
         for (int r = tid; r < rows_b; r += nthreads) XB[r] = br[r];
-        for (int d = tid; d < P; d += nthreads) bins[d] = 0.f;
+        for (int d = tid; d < P; d += nthreads) bins[d] = 0;
         __syncthreads();
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
             const uint2* rp = recs + (size_t)o0 * 64;
-            float acc = 0.f;
+            Real acc = 0;
             int i = o0;
             for (; i + 4 <= o1; i += 4) {
                 const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
                 rp += 256;
-                acc = fmaf(__uint_as_float(r0.y) * lds_at(XB, r0.x >> 16), lds_at(XA, r0.x & 0xffffu), acc);
-                acc = fmaf(__uint_as_float(r1.y) * lds_at(XB, r1.x >> 16), lds_at(XA, r1.x & 0xffffu), acc);
-                acc = fmaf(__uint_as_float(r2.y) * lds_at(XB, r2.x >> 16), lds_at(XA, r2.x & 0xffffu), acc);
-                acc = fmaf(__uint_as_float(r3.y) * lds_at(XB, r3.x >> 16), lds_at(XA, r3.x & 0xffffu), acc);
+                acc += occ_term(r0, XA, XB);
+                acc += occ_term(r1, XA, XB);
+                acc += occ_term(r2, XA, XB);
+                acc += occ_term(r3, XA, XB);
             }
             for (; i < o1; ++i) {
-                const uint2 r0 = rp[0];
+                acc += occ_term(rp[0], XA, XB);
                 rp += 64;
-                acc = fmaf(__uint_as_float(r0.y) * lds_at(XB, r0.x >> 16), lds_at(XA, r0.x & 0xffffu), acc);
             }
             const int pd = row_pdf4[sl * 64 + lane];
-            if (pd >= 0)
-                atomicAdd(reinterpret_cast<float*>(reinterpret_cast<char*>(bins) + pd), acc);
+            if (pd >= 0) atomicAdd(bins + (pd >> 2), acc);
         }
         __syncthreads();
-        const float scale = p.grad_scale * c;
+        const Real scale = (Real)p.grad_scale * c;
         const float* e = p.emis + at;
         for (int d = tid; d < P; d += nthreads) {
-            const float v = scale * e[d] * bins[d];
+            const float v = (float)(scale * (Real)e[d] * bins[d]);
             g[d] = p.accumulate ? g[d] + v : v;
         }
     }
@@ -382,20 +406,38 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 
 hipError_t configure_kernels()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_rec),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_occ),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    const void* fns[] = {reinterpret_cast<const void*>(k_rec<float>),
+                         reinterpret_cast<const void*>(k_rec<double>),
+                         reinterpret_cast<const void*>(k_occ<float>),
+                         reinterpret_cast<const void*>(k_occ<double>)};
+    for (const void* f : fns) {
+        hipError_t e =
+            hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
-hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
-                                   hipStream_t stream, hipEvent_t* ev)
+size_t rec_lds_bytes(int lds_rows, int P, bool wide)
+{
+    const size_t Ppad = (size_t)((P + 63) & ~63);
+    return (2 * (size_t)lds_rows + 32) * (wide ? 8 : 4) + 2 * Ppad * 4;
+}
+
+size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide)
+{
+    const size_t Ppad = (size_t)((P + 63) & ~63);
+    return ((size_t)rows_a + rows_b + 2 * Ppad) * (wide ? 8 : 4);
+}
+
+template <typename Real>
+static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipStream_t stream,
+                               hipEvent_t* ev)
 {
     hipError_t e;
+    const bool wide = sizeof(Real) == 8;
 #define LFMMI_EV(i)                                                   \
     if (ev) { e = hipEventRecord(ev[i], stream); if (e != hipSuccess) return e; }
-    const int Ppad = (p.P + 63) & ~63;
     LFMMI_EV(0)
     if (p.T > 0) {
         dim3 grid((p.T + 3) / 4, p.B);
@@ -403,26 +445,30 @@ hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     LFMMI_EV(1)
-    {
-        const size_t lds = (size_t)(2 * p.lds_rows + 2 * Ppad + 2 * 16) * sizeof(float);
-        hipLaunchKernelGGL(k_rec, dim3(2 * p.B), dim3(shape.rec_threads), lds, stream, p);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
+    hipLaunchKernelGGL(k_rec<Real>, dim3(2 * p.B), dim3(shape.rec_threads),
+                       rec_lds_bytes(p.lds_rows, p.P, wide), stream, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     LFMMI_EV(2)
-    hipLaunchKernelGGL(k_scan, dim3(p.B), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(k_scan<Real>, dim3(p.B), dim3(256), 0, stream, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     LFMMI_EV(3)
     if (p.T > 0) {
-        const size_t lds =
-            (size_t)(p.lds_rows_occ_a + p.lds_rows_occ_b + 2 * Ppad) * sizeof(float);
         dim3 grid((p.T + shape.occ_frames - 1) / shape.occ_frames, p.B);
-        hipLaunchKernelGGL(k_occ, grid, dim3(shape.occ_threads), lds, stream, p,
-                           shape.occ_frames);
+        hipLaunchKernelGGL(k_occ<Real>, grid, dim3(shape.occ_threads),
+                           occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b, p.P, wide), stream,
+                           p, shape.occ_frames);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     LFMMI_EV(4)
 #undef LFMMI_EV
     return hipSuccess;
+}
+
+hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
+                                   hipStream_t stream, hipEvent_t* ev)
+{
+    return p.wide ? launch_typed<double>(p, shape, stream, ev)
+                  : launch_typed<float>(p, shape, stream, ev);
 }
 
 }  // namespace lfmmi

@@ -157,3 +157,65 @@ def test_sequence_result_does_not_depend_on_batch_neighbours():
     assert np.allclose(full[0][perm], part[0], rtol=1e-6)
     assert np.allclose(full[1][perm], part[1], atol=1e-6)
     h.close()
+
+
+# ---- the five workloads at full size, in the launch configuration bench.py times.
+# The oracle recomputes a sample of sequences one by one (sequences are
+# independent); properties that hold at any size are checked on every sequence.
+def _full_size(config, sample):
+    wl = workloads.make_workload(config)
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    den = binding.lfmmi_graph_create(wl["den"])
+    objf, grad, status = run_gpu(den, x, lens, leak)
+    assert np.all(status == 0)
+    assert np.all(np.isfinite(objf))
+    for b, Tb in enumerate(lens):
+        assert np.all(grad[b, Tb:] == 0.0)
+        rows = grad[b, :Tb].astype(np.float64).sum(1)
+        assert np.abs(rows - 1.0).max() <= 2e-4, (b, np.abs(rows - 1.0).max())
+        assert grad[b, :Tb].min() >= 0.0
+    idx = np.asarray(sample)
+    lz, gamma = oracle.forward_backward(wl["den"], x[idx], lens[idx], leak)
+    rel, err = check(objf[idx], grad[idx], status[idx], lz, gamma, "config %d" % config)
+    print("config %d full size: objf max rel err %.2e, grad max abs err %.2e" % (config, rel, err))
+    den.close()
+    return wl
+
+
+def test_config2_full_size_all_sequences():
+    _full_size(2, list(range(64)))
+
+
+def test_config3_full_size_sampled():
+    _full_size(3, [0, 31, 77, 127])
+
+
+def test_config4_full_size_sampled():
+    wl = workloads.make_workload(4)
+    longest, shortest = int(np.argmax(wl["lengths"])), int(np.argmin(wl["lengths"]))
+    _full_size(4, sorted({longest, shortest, 5, 20}))
+
+
+def test_config5_full_size_num_all_den_sampled():
+    wl = workloads.make_workload(5)
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    torch = _torch()
+    den = binding.lfmmi_graph_create(wl["den"])
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    lz_n, g_n = oracle.forward_backward_per_utt(wl["num"], x, lens, leak)
+    check(*run_gpu(num, x, lens, leak), lz_n, g_n, "config 5 numerators")
+    xd = torch.from_numpy(x).cuda()
+    objf, grad, status = binding.lfmmi_forward_backward(num, xd, lens, leak, 1.0, False)
+    binding.lfmmi_forward_backward(den, xd, lens, leak, -1.0, True, objf, grad, status)
+    torch.cuda.synchronize()
+    objf, grad = objf.cpu().numpy().astype(np.float64), grad.cpu().numpy().astype(np.float64)
+    assert np.all(status.cpu().numpy() == 0)
+    for b, Tb in enumerate(lens):   # gamma_num and gamma_den each sum to one per frame
+        assert np.abs(grad[b, :Tb].sum(1)).max() <= 4e-4
+        assert np.all(grad[b, Tb:] == 0.0)
+    idx = np.asarray([0, 17, 64, 127, int(np.argmax(lens))])
+    lz_d, g_d = oracle.forward_backward(wl["den"], x[idx], lens[idx], leak)
+    tol = OBJF_RTOL * np.maximum(np.maximum(np.abs(lz_n[idx]), np.abs(lz_d)), 1.0)
+    assert np.all(np.abs(objf[idx] - (lz_n[idx] - lz_d)) <= tol)
+    assert np.abs(grad[idx] - (g_n[idx] - g_d)).max() <= GRAD_ATOL
+    den.close(); num.close()
