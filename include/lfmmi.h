@@ -140,14 +140,20 @@ enum { LFMMI_ORD_FWD = 0, LFMMI_ORD_BWD = 1, LFMMI_ORD_OCC = 2 };
 lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
 
 /* Packed ordering `ord` of graph `g`: info[0] rows, [1] slices (64 rows each),
- * [2] waves, [3] total slots (sum of slice widths), [4] max slots of one wave. */
+ * [2] waves, [3] total slots (sum of slice widths), [4] max slots of one wave,
+ * [5] arc slots the recursion kernel keeps in registers (0: streamed),
+ * [6] 1 if the emission row is replicated per LDS bank, [7] 1 if the arcs carry
+ * a per-arc leak factor (FWD with non-uniform init_prob). */
 lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
                                        int32_t ord, int64_t info[8]);
 /* Copies the packed ordering out (any pointer may be NULL):
  *   slice_off  [slices + 1] first slot of each slice
  *   wave_first [waves + 1]  first slice of each wave
  *   key, w     [total slots * 64] arc records, lane-minor; key = x-index * 4 in
- *              the low 16 bits, y-index * 4 in the high 16 bits; padding has w 0
+ *              the low 16 bits, y-index * 4 in the high 16 bits; padding has w 0.
+ *              In FWD and BWD the last slot of every slice holds no arc: its
+ *              key is 0 and its w is the row's leak-dot weight (FWD: 1 on real
+ *              rows; BWD: init_prob of the row's state)
  *   row_id     [slices * 64] the state (FWD: to-state, BWD: from-state) or
  *              pdf-id (OCC) a row stands for, -1 for padding rows
  *   x-index / y-index: FWD (from-state in FWD numbering, pdf), BWD (to-state in

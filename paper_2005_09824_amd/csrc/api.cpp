@@ -54,6 +54,9 @@ struct lfmmi_graph {
     std::vector<OrdDesc> ords;  // [num_graphs * 3]
     int32_t max_rows_f = 0, max_rows_b = 0;
     bool wide = false;  // fp64 state vectors (some state is not final)
+    int rec_nslot = 0;  // register-resident arc slots of the recursion kernel (0: streamed)
+    bool rec_yrep = false;
+    bool has_wb = false;  // arcs carry a per-arc leak factor (some init_prob is not uniform)
 
     // device copy
     bool uploaded = false;
@@ -107,15 +110,19 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         h->num_pdfs = num_pdfs;
         h->total_states = state_off[n];
         h->total_arcs = arc_off[n];
-        int waves = 1;
-        for (int32_t g = 0; g < n; ++g)
-            waves = std::max(waves, choose_waves(arc_off[g + 1] - arc_off[g],
-                                                 (int32_t)(state_off[g + 1] - state_off[g])));
-        waves = std::max(1, std::min(env_int("LFMMI_WAVES", waves), kMaxWaves));
-        h->rec_waves = waves;
-        h->occ_waves = waves;
-        h->packed.resize(n);
-        for (int32_t g = 0; g < n; ++g) {
+        // Every state final: the scaled alpha / beta stay comparable across the
+        // states that carry posterior mass, and fp32 holds them. Otherwise
+        // (left-to-right numerator graphs) that mass can sit tens of orders of
+        // magnitude below the frame total: fp64.
+        bool all_final = true;
+        if (final_prob)
+            for (int64_t s = 0; s < state_off[n]; ++s) all_final = all_final && final_prob[s] > 0.f;
+        h->wide = !all_final;
+        if (const char* v = std::getenv("LFMMI_PRECISION")) {
+            if (std::atoi(v) == 64) h->wide = true;
+            if (std::atoi(v) == 32) h->wide = false;
+        }
+        auto arcs_of = [&](int32_t g) {
             ArcList al;
             al.num_states = (int32_t)(state_off[g + 1] - state_off[g]);
             al.num_arcs = arc_off[g + 1] - arc_off[g];
@@ -125,34 +132,62 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             al.logw = logw ? logw + arc_off[g] : nullptr;
             al.init_prob = init_prob ? init_prob + state_off[g] : nullptr;
             al.final_prob = final_prob ? final_prob + state_off[g] : nullptr;
-            bool bad = false;
-            std::string err = pack_graph(al, num_pdfs, h->rec_waves, h->occ_waves,
-                                         &h->packed[g], &bad);
-            if (!err.empty()) {
-                delete h;
-                return fail(bad ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
-                            (n > 1 ? "graph " + std::to_string(g) + ": " : std::string()) + err);
+            return al;
+        };
+        h->has_wb = false;
+        if (init_prob)
+            for (int32_t g = 0; g < n; ++g) h->has_wb = h->has_wb || !uniform_init(arcs_of(g));
+
+        int waves = 1;
+        for (int32_t g = 0; g < n; ++g)
+            waves = std::max(waves, choose_waves(arc_off[g + 1] - arc_off[g],
+                                                 (int32_t)(state_off[g + 1] - state_off[g])));
+        const int forced = env_int("LFMMI_WAVES", 0);
+        if (forced > 0) waves = std::min(forced, kMaxWaves);
+        // Pack for `waves` waves; when the arcs of a wave then fit no register-resident
+        // variant of the recursion kernel, try half the waves (twice the registers per
+        // lane) before settling for streamed arcs.
+        for (int attempt = 0; attempt < 2; ++attempt) {
+            h->rec_waves = waves;
+            h->occ_waves = waves;
+            h->packed.assign(n, PackedGraph());
+            h->max_rows_f = h->max_rows_b = 0;
+            int max_slots = 0;
+            for (int32_t g = 0; g < n; ++g) {
+                bool bad = false;
+                std::string err = pack_graph(arcs_of(g), num_pdfs, h->rec_waves, h->occ_waves,
+                                             h->has_wb, &h->packed[g], &bad);
+                if (!err.empty()) {
+                    delete h;
+                    return fail(bad ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
+                                (n > 1 ? "graph " + std::to_string(g) + ": " : std::string()) + err);
+                }
+                h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
+                h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
+                for (int o = 0; o < 2; ++o)
+                    max_slots = std::max(max_slots, h->packed[g].ord[o].max_wave_slots);
             }
-            h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
-            h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
+            h->rec_nslot = rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
+            if (env_int("LFMMI_STREAM", 0) != 0) h->rec_nslot = 0;
+            if (h->rec_nslot > 0 || h->wide || forced > 0 || waves <= 8 || attempt == 1) break;
+            const int half = waves / 2;
+            if (rec_register_slots(h->wide, h->has_wb, 2 * max_slots, half * kLanes) == 0) break;
+            waves = half;
         }
-        // Every state final: the scaled alpha / beta stay comparable across the
-        // states that carry posterior mass, and fp32 holds them. Otherwise
-        // (left-to-right numerator graphs) that mass can sit tens of orders of
-        // magnitude below the frame total: fp64.
-        bool all_final = true;
-        for (int64_t s = 0; s < state_off[n]; ++s) all_final = all_final && final_prob[s] > 0.f;
-        h->wide = !all_final;
-        if (const char* v = std::getenv("LFMMI_PRECISION")) {
-            if (std::atoi(v) == 64) h->wide = true;
-            if (std::atoi(v) == 32) h->wide = false;
-        }
-        if (rec_lds_bytes(std::max(h->max_rows_f, h->max_rows_b), num_pdfs, h->wide) > kLdsBytes ||
+        const int rows = std::max(h->max_rows_f, h->max_rows_b);
+        if (rec_lds_bytes(rows, num_pdfs, h->wide, false) > kLdsBytes ||
             occ_lds_bytes(h->max_rows_f, h->max_rows_b, num_pdfs, h->wide) > kLdsBytes) {
             delete h;
             return fail(LFMMI_ERR_UNSUPPORTED,
                         "states and pdfs do not fit the 160 KB of LDS of one compute unit");
         }
+        // emission row replicated once per LDS bank when it is small
+        h->rec_yrep = num_pdfs <= 255 && rec_lds_bytes(rows, num_pdfs, h->wide, true) <= 96 * 1024;
+        if (env_int("LFMMI_YREP", 1) == 0) h->rec_yrep = false;
+        // the register-resident kernel has a fixed LDS map: 32 KB per buffer
+        if (h->rec_nslot > 0 &&
+            (rows > 8192 || (h->rec_yrep ? (size_t)num_pdfs * 128 : (size_t)num_pdfs * 4) > 32764))
+            h->rec_nslot = 0;
     } catch (const std::bad_alloc&) {
         delete h;
         return fail(LFMMI_ERR_OOM, "host allocation failed");
@@ -177,7 +212,7 @@ lfmmi_status upload(lfmmi_graph* h)
     if ((e = configure_kernels()) != hipSuccess) return fail_hip(e, "hipFuncSetAttribute");
 
     // concatenate every graph's orderings
-    size_t n_slots = 0, n_soff = 0, n_wf = 0, n_vec = 0, n_rowpdf = 0;
+    size_t n_slots = 0, n_soff = 0, n_wf = 0, n_vec = 0, n_rowpdf = 0, n_mask = 0;
     h->ords.assign((size_t)h->num_graphs * 3, OrdDesc{});
     for (int32_t g = 0; g < h->num_graphs; ++g)
         for (int o = 0; o < 3; ++o) {
@@ -190,6 +225,10 @@ lfmmi_status upload(lfmmi_graph* h)
             d.wave_first_at = (int32_t)n_wf;
             d.max_wave_slots = od.max_wave_slots;
             d.total_slots = od.total_slots;
+            d.mask_at = (int32_t)n_mask;
+            d.has_wb = od.has_wb;
+            d.b_const = od.b_const;
+            n_mask += od.wave_mask.size();
             n_slots += od.total_slots;
             n_soff += od.slice_off.size();
             n_wf += od.wave_first.size();
@@ -206,6 +245,8 @@ lfmmi_status upload(lfmmi_graph* h)
 
     size_t total = 0;
     const size_t at_recs = reserve<uint2>(&total, n_slots * kLanes);
+    const size_t at_wb = reserve<float>(&total, n_slots * kLanes);
+    const size_t at_mask = reserve<uint64_t>(&total, n_mask);
     const size_t at_soff = reserve<int32_t>(&total, n_soff);
     const size_t at_wf = reserve<int32_t>(&total, n_wf);
     const size_t at_vinit = reserve<float>(&total, n_vec);
@@ -232,6 +273,12 @@ lfmmi_status upload(lfmmi_graph* h)
                 std::memcpy(&wbits, &od.w[i], 4);
                 recs[i] = make_uint2(od.key[i], wbits);
             }
+            if (!od.wb.empty())
+                std::memcpy(host.data() + at_wb + (size_t)d.rec_at * kLanes * 4, od.wb.data(),
+                            od.wb.size() * 4);
+            if (!od.wave_mask.empty())
+                std::memcpy(host.data() + at_mask + (size_t)d.mask_at * 8, od.wave_mask.data(),
+                            od.wave_mask.size() * 8);
             std::memcpy(host.data() + at_soff + (size_t)d.slice_off_at * 4, od.slice_off.data(),
                         od.slice_off.size() * 4);
             std::memcpy(host.data() + at_wf + (size_t)d.wave_first_at * 4, od.wave_first.data(),
@@ -261,6 +308,8 @@ lfmmi_status upload(lfmmi_graph* h)
     }
     unsigned char* base = static_cast<unsigned char*>(h->dev_base);
     h->dg.recs = reinterpret_cast<const uint2*>(base + at_recs);
+    h->dg.wb = reinterpret_cast<const float*>(base + at_wb);
+    h->dg.wave_mask = reinterpret_cast<const uint64_t*>(base + at_mask);
     h->dg.slice_off = reinterpret_cast<const int32_t*>(base + at_soff);
     h->dg.wave_first = reinterpret_cast<const int32_t*>(base + at_wf);
     h->dg.vinit = reinterpret_cast<const float*>(base + at_vinit);
@@ -411,7 +460,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     const size_t real = h->wide ? 2 : 1;  // floats per value
     const size_t at_alpha = reserve<float>(&total, (size_t)a_at * real);
     const size_t at_beta = reserve<float>(&total, (size_t)b_at * real);
-    const size_t at_scal = reserve<float>(&total, (size_t)2 * s_at * real);
+    const size_t at_scal = reserve<float>(&total, (size_t)4 * s_at * real);
     const size_t at_cfac = reserve<float>(&total, (size_t)s_at * real);
     const size_t at_zfin = reserve<float>(&total, (size_t)2 * B * real);
     const size_t at_status = reserve<int32_t>(&total, B);
@@ -475,6 +524,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     p.cfac = ws + at_cfac;
     p.zfin = ws + at_zfin;
     p.wide = h->wide ? 1 : 0;
+    p.debug = env_int("LFMMI_DEBUG", 0);
     p.status_ws = reinterpret_cast<int32_t*>(ws + at_status);
     p.status_out = status;
     p.objf = objf;
@@ -492,6 +542,9 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
 
     LaunchShape shape;
     shape.rec_threads = h->rec_waves * kLanes;
+    shape.rec_nslot = h->rec_nslot;
+    shape.rec_yrep = h->rec_yrep ? 1 : 0;
+    shape.rec_has_wb = h->has_wb ? 1 : 0;
     shape.occ_threads = h->occ_waves * kLanes;
     shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
 
@@ -538,7 +591,9 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t 
     info[2] = o.num_waves;
     info[3] = o.total_slots;
     info[4] = o.max_wave_slots;
-    info[5] = info[6] = info[7] = 0;
+    info[5] = ord < 2 ? h->rec_nslot : 0;
+    info[6] = ord < 2 && h->rec_yrep ? 1 : 0;
+    info[7] = o.has_wb;
     return LFMMI_OK;
 }
 

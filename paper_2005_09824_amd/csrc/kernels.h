@@ -16,10 +16,16 @@ struct OrdDesc {
     int32_t vec_at;         // FWD/BWD: first row in vinit/va/vb/vfin; OCC: in row_pdf4
     int32_t max_wave_slots;
     int32_t total_slots;
+    int32_t mask_at;        // FWD/BWD: first entry in wave_mask (num_waves entries)
+    int32_t has_wb;         // FWD: the leak target differs per state
+    float b_const;          // the leak target when it is one constant
+    int32_t pad;
 };
 
 struct DeviceGraph {
     const uint2* recs;          // {key, float bits of w}, lane-minor
+    const float* wb;            // w * b[from] per record (0 where unused), same indexing
+    const uint64_t* wave_mask;  // closing-slot bit masks of the FWD/BWD waves
     const int32_t* slice_off;   // slot offsets, local to the ordering
     const int32_t* wave_first;
     const float* vinit;
@@ -49,7 +55,7 @@ struct FbParams {
     // the next five hold float, or double when `wide` is set
     void* alpha;            // ragged trellis, (T_b + 1) rows of rows_f values
     void* beta;
-    void* scal;             // [2][scal_total] per-frame normalisers (alpha, beta)
+    void* scal;             // [4][scal_total] per frame: alpha n, alpha s, beta n, beta s
     void* cfac;             // [scal_total] occupancy scale of frame t at scal_at + t
     void* zfin;             // [2][B] closing dot products (alpha side, beta side)
     int32_t* status_ws;     // [B]
@@ -62,11 +68,15 @@ struct FbParams {
     int32_t lds_rows_occ_a, lds_rows_occ_b;
     int32_t accumulate;
     int32_t wide;           // 1: state vectors, trellis and scales in fp64
+    int32_t debug;          // experiments only (LFMMI_DEBUG): bit 0 skips the trellis stores
     float leak, grad_scale;
 };
 
 struct LaunchShape {
     int rec_threads;   // workgroup size of the recursion kernel
+    int rec_nslot;     // arc slots held in registers per lane (0: streamed)
+    int rec_yrep;      // emission row replicated across LDS banks
+    int rec_has_wb;    // arcs carry a per-arc leak factor
     int occ_threads;   // workgroup size of the occupancy kernel
     int occ_frames;    // frames per occupancy workgroup
 };
@@ -77,7 +87,9 @@ hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
                                    hipStream_t stream, hipEvent_t* ev);
 hipError_t configure_kernels();
 // Dynamic LDS the recursion / occupancy kernels need.
-size_t rec_lds_bytes(int lds_rows, int P, bool wide);
+size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
+// Register-resident slot count the recursion kernel offers for this shape (0: none).
+int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
 size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide);
 
 }  // namespace lfmmi

@@ -75,51 +75,69 @@ __global__ void __launch_bounds__(256) k_emit(FbParams p)
 //   leak(v) = v + eps * (a . v) * b     (alpha: a = 1, b = pi; beta: a = pi, b = 1)
 // and store vhat = leak(v) / n, n = sum(v).
 // ---------------------------------------------------------------------------
-constexpr int kYRegs = 4;
 
-// One arc slot: w * e[pdf] in fp32, times the gathered state value in Real.
-template <typename Real>
-__device__ __forceinline__ Real arc_term(const uint2 r, const Real* X, const float* Y)
+// Y (emission row) index of a record: plain, or replicated 32 times so that
+// lane l always reads bank l % 32 (conflict-free; small pdf counts only).
+template <bool YREP>
+__device__ __forceinline__ uint32_t y_offset(uint32_t key, int lane)
 {
-    return (Real)(__uint_as_float(r.y) * lds_at(Y, r.x >> 16)) * lds_at(X, r.x & 0xffffu);
+    return YREP ? (key >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (key >> 16);
 }
 
-// Real = float for graphs whose states are all final (denominator-like: the
-// scaled vectors stay within fp32 range), double otherwise (numerator-like
-// left-to-right graphs, where the states that matter can hold a fraction of the
-// frame's mass far below 1e-38).
-template <typename Real>
-__global__ void __launch_bounds__(1024) k_rec(FbParams p)
+__device__ __forceinline__ float lds_f32(const float* base, uint32_t byte_off)
 {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
+// The recursion of one (sequence, direction).
+//
+// Real   float when every state of the graph is final (denominator-like: the
+//        scaled vectors stay within fp32 range), double otherwise (left-to-right
+//        numerator graphs, where the states that matter can hold a fraction of
+//        the frame's mass far below 1e-38).
+//        Arc records are streamed from global memory / L2 every frame here;
+//        rec_run_regs below keeps them in registers.
+// YREP   emission row replicated across banks.
+// HAS_WB the leak target differs per state, so every arc carries w * b[from].
+//
+// Normalisation is lazy: LDS and the trellis hold the raw v_t = M vhat'_{t-1};
+// the consumer of v_t applies vhat'_t = v_t / n_t + (eps * s_t / n_t) * b with
+// n_t = sum(v_t), s_t = a . v_t, which every lane derives from the 16 wave
+// partials after the single barrier of the step. For an arc into row j:
+//   v_{t+1}[j] = (1/n_t) * sum w e v_t[from] + (eps s_t / n_t) * sum (w b[from]) e
+template <typename Real, bool YREP, bool HAS_WB, int NT>
+__device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
+                                        const int b, const int dir, unsigned char* lds_raw)
+{
+    // registers that carry the next emission row across a step: enough for a
+    // replicated 84-pdf row at the full workgroup size
+    constexpr int kYRegs = NT >= 1024 ? 3 : 6;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = blockDim.x;
     const int nwaves = nthreads >> 6;
-    const int code = p.order[blockIdx.x];
-    const int b = code >> 1, dir = code & 1;
-    const SeqDesc sd = p.seqs[b];
-    const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
     const int T = sd.T;
     const int P = p.P;
     const int rows = od.num_slices * 64;
-    const int Ppad = (P + 63) & ~63;
+    const int ylen = YREP ? P * 32 : P;           // floats of one emission buffer
+    const int ypad = (ylen + 63) & ~63;
 
     Real* X0 = reinterpret_cast<Real*>(lds_raw);
     Real* X1 = X0 + p.lds_rows;
-    Real* part = X1 + p.lds_rows;  // [16][2]
-    float* Y0 = reinterpret_cast<float*>(part + 32);
-    float* Y1 = Y0 + Ppad;
+    Real* part = X1 + p.lds_rows;  // [2][16][2]
+    float* Y0 = reinterpret_cast<float*>(part + 64);
+    float* Y1 = Y0 + ypad;
 
     Real* trel = static_cast<Real*>(dir == 0 ? p.alpha : p.beta) +
                  (dir == 0 ? sd.alpha_at : sd.beta_at);
-    Real* scal = static_cast<Real*>(p.scal) + (size_t)dir * p.scal_total + sd.scal_at;
+    Real* scalN = static_cast<Real*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
+    Real* scalS = scalN + p.scal_total;
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+    const float* wbp = p.g.wb + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
-    const float* va = p.g.va + od.vec_at;
-    const float* vb = p.g.vb + od.vec_at;
     const Real eps = (Real)p.leak;
+    const Real bconst = (Real)od.b_const;
 
     int s0 = 0, s1 = 0;
     if (wave < od.num_waves) {
@@ -128,36 +146,28 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
     }
     const size_t erow0 = (size_t)b * p.T;
 
-    // ---- step 0: vhat_0 = leak(init) / sum(init)
+    if (tid < 64) part[tid] = 0;  // partials of waves that do not exist stay 0
+    __syncthreads();
+
+    // ---- step 0: v_0 = init
     {
         Real n = 0, s = 0;
+        const int ti = dir == 0 ? 0 : T;
         for (int sl = s0; sl < s1; ++sl) {
             const int row = sl * 64 + lane;
             const Real v = (Real)p.g.vinit[od.vec_at + row];
             X0[row] = v;
+            trel[(size_t)ti * rows + row] = v;
             n += v;
-            s += (Real)va[row] * v;
+            s += (Real)p.g.va[od.vec_at + row] * v;
         }
         n = wave_sum(n);
         s = wave_sum(s);
         if (lane == 0) { part[wave * 2] = n; part[wave * 2 + 1] = s; }
-        __syncthreads();
-        Real N = 0, Sd = 0;
-        for (int w = 0; w < nwaves; ++w) { N += part[w * 2]; Sd += part[w * 2 + 1]; }
-        const Real inv = N > 0 ? (Real)1 / N : (Real)0;
-        const Real c = eps * Sd * inv;
-        const int ti = dir == 0 ? 0 : T;
-        for (int sl = s0; sl < s1; ++sl) {
-            const int row = sl * 64 + lane;
-            const Real v = c * (Real)vb[row] + X0[row] * inv;
-            X0[row] = v;
-            trel[(size_t)ti * rows + row] = v;
-        }
-        if (tid == 0) scal[ti] = N;
         if (T > 0) {
             const int fr = dir == 0 ? 0 : T - 1;
             const float* e = p.emis + (erow0 + fr) * P;
-            for (int d = tid; d < P; d += nthreads) Y0[d] = e[d];
+            for (int q = tid; q < ylen; q += nthreads) Y0[q] = e[YREP ? q >> 5 : q];
         }
         __syncthreads();
     }
@@ -168,6 +178,8 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
         Real* Xn = (k & 1) ? X1 : X0;
         const float* Yc = (k & 1) ? Y0 : Y1;
         float* Yn = (k & 1) ? Y1 : Y0;
+        const Real* partc = part + ((k & 1) ? 0 : 32);
+        Real* partn = part + ((k & 1) ? 32 : 0);
 
         // emission row of the next step, issued early
         float yreg[kYRegs];
@@ -176,78 +188,438 @@ __global__ void __launch_bounds__(1024) k_rec(FbParams p)
         const float* en = p.emis + (erow0 + (more ? frn : 0)) * P;
 #pragma unroll
         for (int i = 0; i < kYRegs; ++i) {
-            const int d = tid + i * nthreads;
-            yreg[i] = (more && d < P) ? en[d] : 0.f;
+            const int q = tid + i * nthreads;
+            yreg[i] = (more && q < ylen) ? en[YREP ? q >> 5 : q] : 0.f;
         }
 
+        // scalars of the previous step from the wave partials
+        Real N = 0, Sd = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { N += partc[w * 2]; Sd += partc[w * 2 + 1]; }
+        const Real inv = N > 0 ? (Real)1 / N : (Real)0;
+        const Real c = eps * Sd * inv;
+        const Real cb = HAS_WB ? c : c * bconst;
+        {
+            const int tp = dir == 0 ? k - 1 : T - k + 1;
+            if (tid == 0) { scalN[tp] = N; scalS[tp] = Sd; }
+        }
+        const int ti = dir == 0 ? k : T - k;
+        Real* tr = trel + (size_t)ti * rows;
+
         Real n = 0, s = 0;
-        for (int sl = s0; sl < s1; ++sl) {
-            const int o0 = so[sl], o1 = so[sl + 1];
-            const uint2* rp = recs + (size_t)o0 * 64;
-            Real acc = 0;
-            int i = o0;
-            for (; i + 4 <= o1; i += 4) {
-                const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
-                rp += 256;
-                acc += arc_term(r0, Xc, Yc);
-                acc += arc_term(r1, Xc, Yc);
-                acc += arc_term(r2, Xc, Yc);
-                acc += arc_term(r3, Xc, Yc);
+        {
+            for (int sl = s0; sl < s1; ++sl) {
+                const int o0 = so[sl], o1 = so[sl + 1] - 1;  // o1: the closing slot
+                const uint2* rp = recs + (size_t)o0 * 64;
+                const float* wp = wbp + (size_t)o0 * 64;
+                Real acc1 = 0, acc2 = 0;
+                int i = o0;
+                for (; i + 4 <= o1; i += 4) {
+                    uint2 r[4];
+                    float wbv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        r[u] = rp[u * 64];
+                        if (HAS_WB) wbv[u] = wp[u * 64];
+                    }
+                    rp += 256;
+                    wp += 256;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float e = lds_f32(Yc, y_offset<YREP>(r[u].x, lane));
+                        const Real x = lds_at(Xc, r[u].x & 0xffffu);
+                        const float t = __uint_as_float(r[u].y) * e;
+                        acc1 += (Real)t * x;
+                        acc2 += HAS_WB ? (Real)(wbv[u] * e) : (Real)t;
+                    }
+                }
+                for (; i < o1; ++i) {
+                    const uint2 r = rp[0];
+                    const float e = lds_f32(Yc, y_offset<YREP>(r.x, lane));
+                    const Real x = lds_at(Xc, r.x & 0xffffu);
+                    const float t = __uint_as_float(r.y) * e;
+                    acc1 += (Real)t * x;
+                    acc2 += HAS_WB ? (Real)(wp[0] * e) : (Real)t;
+                    rp += 64;
+                    wp += 64;
+                }
+                const Real arow = (Real)__uint_as_float(rp[0].y);
+                const Real v = inv * acc1 + cb * acc2;
+                const int row = sl * 64 + lane;
+                Xn[row] = v;
+                tr[row] = v;
+                n += v;
+                s += arow * v;
             }
-            for (; i < o1; ++i) {
-                acc += arc_term(rp[0], Xc, Yc);
-                rp += 64;
-            }
-            const int row = sl * 64 + lane;
-            Xn[row] = acc;
-            n += acc;
-            s += (Real)va[row] * acc;
         }
         n = wave_sum(n);
         s = wave_sum(s);
-        if (lane == 0) { part[wave * 2] = n; part[wave * 2 + 1] = s; }
-        __syncthreads();
-
-        Real N = 0, Sd = 0;
-        for (int w = 0; w < nwaves; ++w) { N += part[w * 2]; Sd += part[w * 2 + 1]; }
-        const Real inv = N > 0 ? (Real)1 / N : (Real)0;
-        const Real c = eps * Sd * inv;
-        const int ti = dir == 0 ? k : T - k;
-        Real* tr = trel + (size_t)ti * rows;
-        for (int sl = s0; sl < s1; ++sl) {
-            const int row = sl * 64 + lane;
-            const Real v = c * (Real)vb[row] + Xn[row] * inv;
-            Xn[row] = v;
-            tr[row] = v;
-        }
-        if (tid == 0) scal[ti] = N;
+        if (lane == 0) { partn[wave * 2] = n; partn[wave * 2 + 1] = s; }
         if (more) {
 #pragma unroll
             for (int i = 0; i < kYRegs; ++i) {
-                const int d = tid + i * nthreads;
-                if (d < P) Yn[d] = yreg[i];
+                const int q = tid + i * nthreads;
+                if (q < ylen) Yn[q] = yreg[i];
             }
-            for (int d = tid + kYRegs * nthreads; d < P; d += nthreads) Yn[d] = en[d];
+            for (int q = tid + kYRegs * nthreads; q < ylen; q += nthreads)
+                Yn[q] = en[YREP ? q >> 5 : q];
         }
         __syncthreads();
     }
 
-    // ---- closing dot product: alpha side sum_j f[j] ahat_T[j], beta side sum_i pi[i] bhat_0[i]
+    // ---- last scalars and the closing dot product:
+    // alpha side sum_j f[j] ahat'_T[j], beta side sum_i pi[i] bhat'_0[i]
     {
         const Real* Xc = (T & 1) ? X1 : X0;
+        const Real* partc = part + ((T & 1) ? 32 : 0);
+        Real N = 0, Sd = 0;
+        for (int w = 0; w < nwaves; ++w) { N += partc[w * 2]; Sd += partc[w * 2 + 1]; }
+        const Real inv = N > 0 ? (Real)1 / N : (Real)0;
+        const Real c = eps * Sd * inv;
+        const int tp = dir == 0 ? T : 0;
+        if (tid == 0) { scalN[tp] = N; scalS[tp] = Sd; }
         Real z = 0;
         for (int sl = s0; sl < s1; ++sl) {
             const int row = sl * 64 + lane;
-            z += (Real)p.g.vfin[od.vec_at + row] * Xc[row];
+            const Real v = Xc[row] * inv + c * (Real)p.g.vb[od.vec_at + row];
+            z += (Real)p.g.vfin[od.vec_at + row] * v;
         }
         z = wave_sum(z);
-        if (lane == 0) part[wave * 2] = z;
+        __syncthreads();  // every wave has read its partials
+        if (lane == 0) part[wave] = z;
         __syncthreads();
         if (tid == 0) {
             Real Z = 0;
-            for (int w = 0; w < nwaves; ++w) Z += part[w * 2];
+            for (int w = 0; w < nwaves; ++w) Z += part[w];
             static_cast<Real*>(p.zfin)[(size_t)dir * p.B + b] = Z;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Wave-level sums on the DPP cross-lane path (no LDS traffic).
+// ---------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    // lanes of rows outside ROW_MASK, and lanes whose source is out of range, add 0
+    const int moved =
+        __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+    return v + __int_as_float(moved);
+}
+
+// After this every lane holds the sum over its row of 16 lanes.
+__device__ __forceinline__ float row16_allsum(float v)
+{
+    v = dpp_add<0xB1, 0xf>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xf>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141, 0xf>(v);  // row_half_mirror
+    v = dpp_add<0x140, 0xf>(v);  // row_mirror
+    return v;
+}
+
+// Sum over the 64 lanes, returned as a wave-uniform value.
+__device__ __forceinline__ float wave_sum_uniform(float v)
+{
+    v = row16_allsum(v);
+    v = dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// ---------------------------------------------------------------------------
+// The recursion with the wave's arc records in registers (fp32 graphs whose
+// waves own at most NSLOT slots). Fixed LDS map, so that the buffer of the
+// current parity is an immediate offset on every LDS instruction:
+//   [0, 32K) X0   [32K, 64K) X1   [64K, 96K) Y0   [96K, 128K) Y1   [128K, ...) partials
+// The last word of each Y buffer is 0: closing slots read it as their emission,
+// so that the slot loop needs no special case for them.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kRegX1 = 32768, kRegY0 = 65536, kRegY1 = 98304, kRegPart = 131072;
+constexpr uint32_t kRegYZero = 32764;  // byte offset of the zero word inside a Y buffer
+
+__host__ __device__ constexpr size_t reg_lds_bytes() { return kRegPart + 3 * 32 * sizeof(float); }
+
+template <bool YREP, bool HAS_WB, int NSLOT, int NT>
+struct RecRegs {
+    static constexpr int kYRegs = NT >= 1024 ? 3 : 6;
+    static constexpr int kPrefetch = NT >= 1024 ? 4 : 8;
+
+    uint32_t xa[NSLOT];  // byte address of the state value inside X0
+    uint32_t ya[NSLOT];  // LDS byte address of the emission value in Y0 (absolute)
+    float wr[NSLOT];     // arc weight; closing slots: the row's leak-dot weight
+    float wbr[HAS_WB ? NSLOT : 1];
+    float yreg[kYRegs];
+
+    template <int PAR>
+    __device__ __forceinline__ void step(const FbParams& p, unsigned char* lds, const int k,
+                                         const int T, const int dir, const int tid, const int lane,
+                                         const int wave, const int nthreads, const int ylen,
+                                         const size_t erow0, const float eps, const float bconst,
+                                         const uint64_t mask, const int row0, float* trel,
+                                         const int rows, float* scalN, float* scalS)
+    {
+        // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
+        constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
+        // Y addresses in ya[] are absolute addresses inside Y0; Y1 is 32 KB further
+        constexpr uint32_t yc = PAR ? 0u : (kRegY1 - kRegY0), yn = PAR ? kRegY1 : kRegY0;
+        constexpr uint32_t pc = kRegPart + (PAR ? 0u : 128u), pn = kRegPart + (PAR ? 128u : 0u);
+        const int P = p.P;
+
+        // emission row of step k + 1 (loaded one step ago) into the other Y buffer,
+        // then the loads for step k + 2
+        if (k < T) {
+#pragma unroll
+            for (int i = 0; i < kYRegs; ++i) {
+                const int q = tid + i * nthreads;
+                if (q < ylen) *reinterpret_cast<float*>(lds + yn + q * 4) = yreg[i];
+            }
+            if (ylen > kYRegs * nthreads) {
+                const int fr = dir == 0 ? k : T - k - 1;
+                const float* e = p.emis + (erow0 + fr) * P;
+                for (int q = tid + kYRegs * nthreads; q < ylen; q += nthreads)
+                    *reinterpret_cast<float*>(lds + yn + q * 4) = e[YREP ? q >> 5 : q];
+            }
+        }
+        if (k + 1 < T && !(p.debug & 2)) {
+            const int fr = dir == 0 ? k + 1 : T - k - 2;
+            const float* e = p.emis + (erow0 + fr) * P;
+#pragma unroll
+            for (int i = 0; i < kYRegs; ++i) {
+                const int q = tid + i * nthreads;
+                if (q < ylen) yreg[i] = e[YREP ? q >> 5 : q];
+            }
+        }
+
+        // scalars of step k - 1: lanes 0-15 fetch the n partials, 16-31 the s partials
+        float pv = *reinterpret_cast<const float*>(lds + pc + (lane & 31) * 4);
+        pv = row16_allsum(pv);
+        const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
+        const float Sd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16));
+        float inv = 0.f;
+        if (N > 0.f) {
+            inv = __builtin_amdgcn_rcpf(N);
+            inv = fmaf(fmaf(-N, inv, 1.f), inv, inv);  // one Newton step
+        }
+        const float c = eps * Sd * inv;
+        const float cb = HAS_WB ? c : c * bconst;
+        if (tid == 0 && !(p.debug & 4)) {
+            const int tp = dir == 0 ? k - 1 : T - k + 1;
+            scalN[tp] = N;
+            scalS[tp] = Sd;
+        }
+        const int ti = dir == 0 ? k : T - k;
+        float* tr = trel + (size_t)ti * rows;
+
+        float xv[kPrefetch], ev[kPrefetch];
+#pragma unroll
+        for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
+            xv[i] = *reinterpret_cast<const float*>(lds + xc + xa[i]);
+            ev[i] = *reinterpret_cast<const float*>(lds + yc + ya[i]);
+        }
+        float acc1 = 0.f, acc2 = 0.f, n = 0.f, s = 0.f;
+        uint64_t left = mask;
+        int next_close = left ? __builtin_ctzll(left) : 64;
+        int row = row0 + lane;
+#pragma unroll
+        for (int i = 0; i < NSLOT; ++i) {
+            const float x = xv[i % kPrefetch];
+            const float e = ev[i % kPrefetch];
+#if defined(LFMMI_EXP) && (LFMMI_EXP & 8)
+            if (false) {
+#else
+            if (i + kPrefetch < NSLOT) {
+#endif
+                xv[i % kPrefetch] = *reinterpret_cast<const float*>(lds + xc + xa[i + kPrefetch]);
+                ev[i % kPrefetch] = *reinterpret_cast<const float*>(lds + yc + ya[i + kPrefetch]);
+            }
+            // an arc slot; closing and padding slots see e == 0 or w == 0 and add nothing
+            const float t = wr[i] * e;
+            acc1 = fmaf(t, x, acc1);
+            acc2 = HAS_WB ? fmaf(wbr[i], e, acc2) : acc2 + t;
+#if defined(LFMMI_EXP) && (LFMMI_EXP & 1)
+            if (false) {
+#else
+            if (i == next_close) {  // wave-uniform: the slice ends here
+#endif
+                const float v = fmaf(inv, acc1, cb * acc2);
+                *reinterpret_cast<float*>(lds + xn + row * 4) = v;
+                if (!(p.debug & 1)) tr[row] = v;
+                n += v;
+                s = fmaf(wr[i], v, s);
+                acc1 = 0.f;
+                acc2 = 0.f;
+                row += 64;
+                left &= left - 1;
+                next_close = left ? __builtin_ctzll(left) : 64;
+            }
+        }
+#if !(defined(LFMMI_EXP) && (LFMMI_EXP & 4))
+        n = wave_sum_uniform(n);
+        s = wave_sum_uniform(s);
+#endif
+        if (lane == 0) {
+            *reinterpret_cast<float*>(lds + pn + wave * 4) = n;
+            *reinterpret_cast<float*>(lds + pn + 64 + wave * 4) = s;
+        }
+#if !(defined(LFMMI_EXP) && (LFMMI_EXP & 2))
+        __syncthreads();
+#endif
+    }
+
+    __device__ __forceinline__ void run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
+                                        const int b, const int dir, unsigned char* lds)
+    {
+        const int tid = threadIdx.x;
+        const int lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int nthreads = blockDim.x;
+        const int T = sd.T;
+        const int P = p.P;
+        const int rows = od.num_slices * 64;
+        const int ylen = YREP ? P * 32 : P;
+        float* trel = static_cast<float*>(dir == 0 ? p.alpha : p.beta) +
+                      (dir == 0 ? sd.alpha_at : sd.beta_at);
+        float* scalN = static_cast<float*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
+        float* scalS = scalN + p.scal_total;
+        const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+        const float* wbp = p.g.wb + (size_t)od.rec_at * 64 + lane;
+        const int32_t* so = p.g.slice_off + od.slice_off_at;
+        const float eps = p.leak;
+        const float bconst = od.b_const;
+        const size_t erow0 = (size_t)b * p.T;
+
+        int s0 = 0, s1 = 0;
+        uint64_t mask = 0;
+        if (wave < od.num_waves) {
+            s0 = p.g.wave_first[od.wave_first_at + wave];
+            s1 = p.g.wave_first[od.wave_first_at + wave + 1];
+            mask = p.g.wave_mask[od.mask_at + wave];
+        }
+        const int first = so[s0];
+        const int nsl = so[s1] - first;
+#pragma unroll
+        for (int i = 0; i < NSLOT; ++i) {
+            const bool on = i < nsl;
+            const bool closing = (mask >> i) & 1;
+            const uint2 r = on ? recs[(size_t)(first + i) * 64] : make_uint2(0u, 0u);
+            xa[i] = r.x & 0xffffu;
+#if defined(LFMMI_EXP) && (LFMMI_EXP & 16)
+            xa[i] = (uint32_t)((lane * 4 + i * 256) & 8191);  // conflict-free pattern (timing only)
+#endif
+            ya[i] = kRegY0 +
+                    ((on && !closing)
+                         ? (YREP ? (r.x >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (r.x >> 16))
+                         : kRegYZero);
+            wr[i] = __uint_as_float(r.y);
+            if (HAS_WB) wbr[i] = (on && !closing) ? wbp[(size_t)(first + i) * 64] : 0.f;
+        }
+
+        // zero words of the Y buffers, partial slots
+        if (tid == 0) {
+            *reinterpret_cast<float*>(lds + kRegY0 + kRegYZero) = 0.f;
+            *reinterpret_cast<float*>(lds + kRegY1 + kRegYZero) = 0.f;
+        }
+        if (tid < 64) *reinterpret_cast<float*>(lds + kRegPart + tid * 4) = 0.f;
+        __syncthreads();
+
+        // ---- step 0: v_0 = init into X0, partials into slot set 0
+        {
+            float n = 0.f, s = 0.f;
+            const int ti = dir == 0 ? 0 : T;
+            for (int sl = s0; sl < s1; ++sl) {
+                const int row = sl * 64 + lane;
+                const float v = p.g.vinit[od.vec_at + row];
+                *reinterpret_cast<float*>(lds + row * 4) = v;
+                trel[(size_t)ti * rows + row] = v;
+                n += v;
+                s = fmaf(p.g.va[od.vec_at + row], v, s);
+            }
+            n = wave_sum_uniform(n);
+            s = wave_sum_uniform(s);
+            if (lane == 0) {
+                *reinterpret_cast<float*>(lds + kRegPart + wave * 4) = n;
+                *reinterpret_cast<float*>(lds + kRegPart + 64 + wave * 4) = s;
+            }
+            if (T > 0) {
+                const int fr = dir == 0 ? 0 : T - 1;
+                const float* e = p.emis + (erow0 + fr) * P;
+                for (int q = tid; q < ylen; q += nthreads)
+                    *reinterpret_cast<float*>(lds + kRegY0 + q * 4) = e[YREP ? q >> 5 : q];
+            }
+            if (T > 1) {
+                const int fr = dir == 0 ? 1 : T - 2;
+                const float* e = p.emis + (erow0 + fr) * P;
+#pragma unroll
+                for (int i = 0; i < kYRegs; ++i) {
+                    const int q = tid + i * nthreads;
+                    yreg[i] = q < ylen ? e[YREP ? q >> 5 : q] : 0.f;
+                }
+            }
+            __syncthreads();
+        }
+
+        const int row0 = s0 * 64;
+        int k = 1;
+        for (; k + 1 <= T; k += 2) {
+            step<1>(p, lds, k, T, dir, tid, lane, wave, nthreads, ylen, erow0, eps, bconst, mask,
+                    row0, trel, rows, scalN, scalS);
+            step<0>(p, lds, k + 1, T, dir, tid, lane, wave, nthreads, ylen, erow0, eps, bconst,
+                    mask, row0, trel, rows, scalN, scalS);
+        }
+        if (k <= T)
+            step<1>(p, lds, k, T, dir, tid, lane, wave, nthreads, ylen, erow0, eps, bconst, mask,
+                    row0, trel, rows, scalN, scalS);
+
+        // ---- last scalars and the closing dot product
+        {
+            const uint32_t xc = (T & 1) ? kRegX1 : 0u;
+            const uint32_t pc = kRegPart + ((T & 1) ? 128u : 0u);
+            float pv = *reinterpret_cast<const float*>(lds + pc + (lane & 31) * 4);
+            pv = row16_allsum(pv);
+            const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
+            const float Sd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16));
+            const float inv = N > 0.f ? 1.f / N : 0.f;
+            const float c = eps * Sd * inv;
+            if (tid == 0) {
+                const int tp = dir == 0 ? T : 0;
+                scalN[tp] = N;
+                scalS[tp] = Sd;
+            }
+            float z = 0.f;
+            for (int sl = s0; sl < s1; ++sl) {
+                const int row = sl * 64 + lane;
+                const float v = fmaf(*reinterpret_cast<const float*>(lds + xc + row * 4), inv,
+                                     c * p.g.vb[od.vec_at + row]);
+                z = fmaf(p.g.vfin[od.vec_at + row], v, z);
+            }
+            z = wave_sum_uniform(z);
+            __syncthreads();  // every wave has read the partials
+            if (lane == 0) *reinterpret_cast<float*>(lds + kRegPart + 256 + wave * 4) = z;
+            __syncthreads();
+            if (tid == 0) {
+                float Z = 0.f;
+                for (int w = 0; w < (nthreads >> 6); ++w)
+                    Z += *reinterpret_cast<const float*>(lds + kRegPart + 256 + w * 4);
+                static_cast<float*>(p.zfin)[(size_t)dir * p.B + b] = Z;
+            }
+        }
+    }
+};
+
+template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT>
+__global__ void __launch_bounds__(NT) k_rec(FbParams p)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int code = p.order[blockIdx.x];
+    const int b = code >> 1, dir = code & 1;
+    const SeqDesc sd = p.seqs[b];
+    const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
+    if constexpr (NSLOT > 0) {
+        RecRegs<YREP, HAS_WB, NSLOT, NT> r;
+        r.run(p, sd, od, b, dir, lds_raw);
+    } else {
+        rec_run<Real, YREP, HAS_WB, NT>(p, sd, od, b, dir, lds_raw);
     }
 }
 
@@ -267,7 +639,7 @@ __global__ void __launch_bounds__(256) k_scan(FbParams p)
     const int T = sd.T;
     const int n = T + 1;
     const Real* na = static_cast<const Real*>(p.scal) + sd.scal_at;
-    const Real* nb = static_cast<const Real*>(p.scal) + p.scal_total + sd.scal_at;
+    const Real* nb = static_cast<const Real*>(p.scal) + 2 * p.scal_total + sd.scal_at;
     Real* cfac = static_cast<Real*>(p.cfac) + sd.scal_at;
     const int chunk = (n + 255) / 256;
     const int i0 = min(tid * chunk, n), i1 = min(i0 + chunk, n);
@@ -348,6 +720,10 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* row_pdf4 = p.g.row_pdf4 + od.vec_at;
     const Real* cfac = static_cast<const Real*>(p.cfac) + sd.scal_at;
+    const Real* scal = static_cast<const Real*>(p.scal) + sd.scal_at;
+    const float* vb_f = p.g.vb + p.g.ords[sd.graph * 3 + 0].vec_at;
+    const float* vb_b = p.g.vb + p.g.ords[sd.graph * 3 + 1].vec_at;
+    const Real eps = (Real)p.leak;
     int s0 = 0, s1 = 0;
     if (wave < od.num_waves) {
         s0 = p.g.wave_first[od.wave_first_at + wave];
@@ -366,10 +742,15 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
             continue;
         }
         Real* bins = (t & 1) ? bins1 : bins0;
+        // the trellis holds raw vectors: vhat' = v / n + (eps * s / n) * b
+        const Real na = scal[t - 1], sa = scal[p.scal_total + t - 1];
+        const Real nb = scal[2 * p.scal_total + t], sb = scal[3 * p.scal_total + t];
+        const Real inva = (Real)1 / na, ca = eps * sa * inva;
+        const Real invb = (Real)1 / nb, cb = eps * sb * invb;
         const Real* ar = static_cast<const Real*>(p.alpha) + sd.alpha_at + (size_t)(t - 1) * rows_f;
         const Real* br = static_cast<const Real*>(p.beta) + sd.beta_at + (size_t)t * rows_b;
-        for (int r = tid; r < rows_f; r += nthreads) XA[r] = ar[r];
-        for (int r = tid; r < rows_b; r += nthreads) XB[r] = br[r];
+        for (int r = tid; r < rows_f; r += nthreads) XA[r] = ar[r] * inva + ca * (Real)vb_f[r];
+        for (int r = tid; r < rows_b; r += nthreads) XB[r] = br[r] * invb + cb * (Real)vb_b[r];
         for (int d = tid; d < P; d += nthreads) bins[d] = 0;
         __syncthreads();
         for (int sl = s0; sl < s1; ++sl) {
@@ -402,13 +783,60 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     }
 }
 
+// ---- kernel variants ---------------------------------------------------------
+using RecKernel = void (*)(FbParams);
+
+struct RecVariant {
+    int wide, nslot, yrep, has_wb, max_threads;
+    RecKernel fn;
+};
+
+#define LFMMI_REC(REAL, WIDE, NSLOT, WB, NT)                                  \
+    {WIDE, NSLOT, 0, WB, NT, k_rec<REAL, NSLOT, false, (WB != 0), NT>},       \
+    {WIDE, NSLOT, 1, WB, NT, k_rec<REAL, NSLOT, true, (WB != 0), NT>}
+const RecVariant kRecVariants[] = {
+    // streamed arcs
+    LFMMI_REC(float, 0, 0, 0, 1024), LFMMI_REC(float, 0, 0, 1, 1024),
+    LFMMI_REC(double, 1, 0, 0, 1024), LFMMI_REC(double, 1, 0, 1, 1024),
+    // register-resident arcs, 16 waves (128 VGPRs per lane)
+    LFMMI_REC(float, 0, 16, 0, 1024), LFMMI_REC(float, 0, 24, 0, 1024),
+    LFMMI_REC(float, 0, 28, 0, 1024),
+    LFMMI_REC(float, 0, 16, 1, 1024),
+    // register-resident arcs, 8 waves (256 VGPRs per lane)
+    LFMMI_REC(float, 0, 32, 0, 512), LFMMI_REC(float, 0, 48, 0, 512),
+    LFMMI_REC(float, 0, 32, 1, 512), LFMMI_REC(float, 0, 48, 1, 512),
+};
+#undef LFMMI_REC
+
+const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb)
+{
+    for (const RecVariant& v : kRecVariants)
+        if (v.wide == (wide ? 1 : 0) && v.nslot == nslot && v.yrep == (yrep ? 1 : 0) &&
+            v.has_wb == (has_wb ? 1 : 0))
+            return &v;
+    return nullptr;
+}
+
 }  // namespace
+
+int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
+{
+    int best = 0;
+    for (const RecVariant& v : kRecVariants)
+        if (v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) && v.nslot > 0 &&
+            v.nslot >= max_wave_slots && threads <= v.max_threads && (best == 0 || v.nslot < best))
+            best = v.nslot;
+    return best;
+}
 
 hipError_t configure_kernels()
 {
-    const void* fns[] = {reinterpret_cast<const void*>(k_rec<float>),
-                         reinterpret_cast<const void*>(k_rec<double>),
-                         reinterpret_cast<const void*>(k_occ<float>),
+    for (const RecVariant& v : kRecVariants) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    const void* fns[] = {reinterpret_cast<const void*>(k_occ<float>),
                          reinterpret_cast<const void*>(k_occ<double>)};
     for (const void* f : fns) {
         hipError_t e =
@@ -418,10 +846,11 @@ hipError_t configure_kernels()
     return hipSuccess;
 }
 
-size_t rec_lds_bytes(int lds_rows, int P, bool wide)
+size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep)
 {
-    const size_t Ppad = (size_t)((P + 63) & ~63);
-    return (2 * (size_t)lds_rows + 32) * (wide ? 8 : 4) + 2 * Ppad * 4;
+    const size_t ylen = yrep ? (size_t)P * 32 : (size_t)P;
+    const size_t ypad = (ylen + 63) & ~(size_t)63;
+    return (2 * (size_t)lds_rows + 64) * (wide ? 8 : 4) + 2 * ypad * 4;
 }
 
 size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide)
@@ -436,6 +865,9 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
 {
     hipError_t e;
     const bool wide = sizeof(Real) == 8;
+    const RecVariant* rv =
+        find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0);
+    if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
 #define LFMMI_EV(i)                                                   \
     if (ev) { e = hipEventRecord(ev[i], stream); if (e != hipSuccess) return e; }
     LFMMI_EV(0)
@@ -445,8 +877,11 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     LFMMI_EV(1)
-    hipLaunchKernelGGL(k_rec<Real>, dim3(2 * p.B), dim3(shape.rec_threads),
-                       rec_lds_bytes(p.lds_rows, p.P, wide), stream, p);
+    hipLaunchKernelGGL(rv->fn, dim3(2 * p.B), dim3(shape.rec_threads),
+                       shape.rec_nslot > 0
+                           ? reg_lds_bytes()
+                           : rec_lds_bytes(p.lds_rows, p.P, wide, shape.rec_yrep != 0),
+                       stream, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     LFMMI_EV(2)
     hipLaunchKernelGGL(k_scan<Real>, dim3(p.B), dim3(256), 0, stream, p);

@@ -18,7 +18,7 @@ struct Arrangement {
     int32_t num_slices = 0, num_waves = 0, max_wave_slots = 0;
 };
 
-Arrangement arrange(const std::vector<int32_t>& len, int waves)
+Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots)
 {
     Arrangement ar;
     const int32_t R = (int32_t)len.size();
@@ -29,7 +29,8 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves)
     std::stable_sort(idx.begin(), idx.end(),
                      [&](int32_t a, int32_t b) { return len[a] > len[b]; });
     std::vector<int32_t> sorted_width(ar.num_slices);
-    for (int32_t s = 0; s < ar.num_slices; ++s) sorted_width[s] = len[idx[(size_t)s * kLanes]];
+    for (int32_t s = 0; s < ar.num_slices; ++s)
+        sorted_width[s] = len[idx[(size_t)s * kLanes]] + extra_slots;
 
     std::vector<std::vector<int32_t>> owned(ar.num_waves);
     std::vector<int64_t> load(ar.num_waves, 0);
@@ -42,6 +43,39 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves)
         owned[best].push_back(s);
         load[best] += sorted_width[s];
     }
+    // refine: move or swap slices out of the fullest wave while that lowers its load
+    for (int round = 0; round < 256; ++round) {
+        int top = 0;
+        for (int w = 1; w < ar.num_waves; ++w)
+            if (load[w] > load[top]) top = w;
+        bool improved = false;
+        for (size_t a = 0; a < owned[top].size() && !improved; ++a) {
+            const int64_t wa = sorted_width[owned[top][a]];
+            for (int w = 0; w < ar.num_waves && !improved; ++w) {
+                if (w == top) continue;
+                if (load[w] + wa < load[top]) {  // move
+                    owned[w].push_back(owned[top][a]);
+                    owned[top].erase(owned[top].begin() + a);
+                    load[w] += wa;
+                    load[top] -= wa;
+                    improved = true;
+                    break;
+                }
+                for (size_t c = 0; c < owned[w].size(); ++c) {  // swap
+                    const int64_t wc = sorted_width[owned[w][c]];
+                    if (wc < wa && load[w] - wc + wa < load[top]) {
+                        std::swap(owned[top][a], owned[w][c]);
+                        load[top] += wc - wa;
+                        load[w] += wa - wc;
+                        improved = true;
+                        break;
+                    }
+                }
+            }
+        }
+        if (!improved) break;
+    }
+    for (int w = 0; w < ar.num_waves; ++w) std::sort(owned[w].begin(), owned[w].end());
     ar.pos.assign(R, 0);
     ar.slice_width.clear();
     ar.wave_first.assign(ar.num_waves + 1, 0);
@@ -98,8 +132,15 @@ int choose_waves(int64_t num_arcs, int32_t num_states)
     return (int)std::min<int64_t>(w, kMaxWaves);
 }
 
+bool uniform_init(const ArcList& g)
+{
+    for (int32_t s = 1; s < g.num_states; ++s)
+        if (g.init_prob[s] != g.init_prob[0]) return false;
+    return true;
+}
+
 std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int occ_waves,
-                       PackedGraph* out, bool* bad_graph)
+                       bool per_arc_leak, PackedGraph* out, bool* bad_graph)
 {
     *bad_graph = false;
     const int32_t S = g.num_states;
@@ -133,8 +174,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     // ---- FWD (rows = to-states) and BWD (rows = from-states) arrangements
     std::vector<int32_t> indeg(S, 0), outdeg(S, 0);
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
-    const Arrangement af = arrange(indeg, rec_waves);
-    const Arrangement ab = arrange(outdeg, rec_waves);
+    const Arrangement af = arrange(indeg, rec_waves, 1);
+    const Arrangement ab = arrange(outdeg, rec_waves, 1);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     start_ordering(af, S, &out->ord[0]);
     start_ordering(ab, S, &out->ord[1]);
@@ -169,6 +210,48 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             out->va[d][p] = d == 0 ? 1.f : pi;
             out->vb[d][p] = d == 0 ? pi : 1.f;
         }
+        // closing slot of every slice: the row's leak-dot weight
+        Ordering& o = out->ord[d];
+        for (int32_t sl = 0; sl < o.num_slices; ++sl)
+            for (int l = 0; l < kLanes; ++l) {
+                const size_t at = (size_t)(o.slice_off[sl + 1] - 1) * kLanes + l;
+                o.key[at] = 0u;
+                o.w[at] = out->va[d][(size_t)sl * kLanes + l];
+            }
+        o.wave_mask.assign(o.num_waves, 0);
+        for (int32_t wv = 0; wv < o.num_waves; ++wv) {
+            const int32_t first = o.slice_off[o.wave_first[wv]];
+            const int32_t count = o.slice_off[o.wave_first[wv + 1]] - first;
+            if (count > 64) continue;
+            for (int32_t sl = o.wave_first[wv]; sl < o.wave_first[wv + 1]; ++sl)
+                o.wave_mask[wv] |= (uint64_t)1 << (o.slice_off[sl + 1] - 1 - first);
+        }
+    }
+    // leak target: BWD adds the same amount to every state; FWD adds pi, which
+    // is one constant when pi is uniform. Otherwise (or when another graph of
+    // the same handle needs it) every arc carries the factor w * b[from]
+    // (FWD: w * pi[from]; BWD: w), so that all of them run the same code.
+    {
+        const bool uniform = uniform_init(g);
+        if (!uniform && !per_arc_leak) return "internal: per-arc leak factors are required";
+        out->ord[0].has_wb = per_arc_leak ? 1 : 0;
+        out->ord[0].b_const = uniform ? g.init_prob[0] : 0.f;
+        out->ord[1].has_wb = per_arc_leak ? 1 : 0;
+        out->ord[1].b_const = 1.f;
+        if (per_arc_leak) {
+            Ordering& of = out->ord[0];
+            Ordering& ob = out->ord[1];
+            of.wb.assign(of.w.size(), 0.f);
+            ob.wb.assign(ob.w.size(), 0.f);
+            std::vector<int32_t> nf(S, 0), nb(S, 0);
+            for (int64_t a = 0; a < A; ++a) {
+                const int32_t i = g.src[a], j = g.dst[a];
+                const int32_t pf = af.pos[j], pb = ab.pos[i];
+                of.wb[(size_t)(of.slice_off[pf / kLanes] + nf[j]++) * kLanes + pf % kLanes] =
+                    w[a] * g.init_prob[i];
+                ob.wb[(size_t)(ob.slice_off[pb / kLanes] + nb[i]++) * kLanes + pb % kLanes] = w[a];
+            }
+        }
     }
 
     // ---- OCC: arcs grouped by pdf, each pdf's list cut into pieces
@@ -190,7 +273,7 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
                 left -= len[r];
                 pdf_of[r] = d;
             }
-        const Arrangement ao = arrange(len, occ_waves);
+        const Arrangement ao = arrange(len, occ_waves, 0);
         start_ordering(ao, (int32_t)R, &out->ord[2]);
         out->row_pdf4.assign((size_t)ao.num_slices * kLanes, -1);
         for (int64_t r = 0; r < R; ++r) {

@@ -32,7 +32,15 @@ struct Ordering {
     std::vector<int32_t> wave_first;  // [num_waves + 1]
     std::vector<uint32_t> key;        // [total_slots * 64]
     std::vector<float> w;             // [total_slots * 64]
+    std::vector<float> wb;            // non-uniform pi only: FWD w * pi[from-state], BWD w
     std::vector<int32_t> row_id;      // [num_slices * 64], -1 = padding row
+    // FWD / BWD only: every slice ends in one extra slot that holds no arc but
+    // the row's leak-dot weight (FWD 1, BWD pi[row], 0 on padding rows).
+    // wave_mask[w] has bit i set when slot i of wave w is such a closing slot
+    // (0 when the wave owns more than 64 slots).
+    std::vector<uint64_t> wave_mask;  // [num_waves]
+    float b_const = 0.f;              // leak target when it is one constant (BWD 1, FWD uniform pi)
+    int32_t has_wb = 0;               // wb is filled
 };
 
 struct PackedGraph {
@@ -62,7 +70,11 @@ int choose_waves(int64_t num_arcs, int32_t num_states);
 
 // Validates and packs one graph. Returns an empty string on success, else the
 // reason (bad_graph says whether the graph or an argument is at fault).
+// per_arc_leak: fill the per-arc leak factors (required when init_prob is not
+// uniform over the states).
 std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int occ_waves,
-                       PackedGraph* out, bool* bad_graph);
+                       bool per_arc_leak, PackedGraph* out, bool* bad_graph);
+// True when every state has the same initial probability.
+bool uniform_init(const ArcList& g);
 
 }  // namespace lfmmi
