@@ -143,9 +143,11 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
  * [2] waves, [3] total slots (sum of slice widths), [4] max slots of one wave,
  * [5] arc slots the recursion kernel keeps in registers (0: streamed),
  * [6] 1 if the emission row is replicated per LDS bank, [7] 1 if the arcs carry
- * a per-arc leak factor (FWD with non-uniform init_prob). */
+ * a per-arc leak factor (non-uniform init_prob), [8] modelled LDS cycles of the
+ * gathers of one frame (per slot and half-wave, the largest number of distinct
+ * addresses in one of the 32 banks), [9..11] 0. */
 lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
-                                       int32_t ord, int64_t info[8]);
+                                       int32_t ord, int64_t info[12]);
 /* Copies the packed ordering out (any pointer may be NULL):
  *   slice_off  [slices + 1] first slot of each slice
  *   wave_first [waves + 1]  first slice of each wave

@@ -138,6 +138,21 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         if (init_prob)
             for (int32_t g = 0; g < n; ++g) h->has_wb = h->has_wb || !uniform_init(arcs_of(g));
 
+        // the emission row is replicated once per LDS bank when it is small
+        {
+            int64_t max_states = 0;
+            for (int32_t g = 0; g < n; ++g)
+                max_states = std::max(max_states, state_off[g + 1] - state_off[g]);
+            const int rows_guess = (int)((max_states + kLanes - 1) / kLanes * kLanes);
+            h->rec_yrep = num_pdfs <= 255 &&
+                          rec_lds_bytes(rows_guess, num_pdfs, h->wide, true) <= 96 * 1024;
+            if (env_int("LFMMI_YREP", 1) == 0) h->rec_yrep = false;
+        }
+        PackTuning tune;
+        tune.emission_conflicts = !h->rec_yrep;
+        tune.balance_banks = !h->wide && env_int("LFMMI_BALANCE", 1) != 0;
+        tune.order_slots = !h->wide && env_int("LFMMI_ORDER", 1) != 0;
+
         int waves = 1;
         for (int32_t g = 0; g < n; ++g)
             waves = std::max(waves, choose_waves(arc_off[g + 1] - arc_off[g],
@@ -156,7 +171,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             for (int32_t g = 0; g < n; ++g) {
                 bool bad = false;
                 std::string err = pack_graph(arcs_of(g), num_pdfs, h->rec_waves, h->occ_waves,
-                                             h->has_wb, &h->packed[g], &bad);
+                                             h->has_wb, tune, &h->packed[g], &bad);
                 if (!err.empty()) {
                     delete h;
                     return fail(bad ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
@@ -181,9 +196,6 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             return fail(LFMMI_ERR_UNSUPPORTED,
                         "states and pdfs do not fit the 160 KB of LDS of one compute unit");
         }
-        // emission row replicated once per LDS bank when it is small
-        h->rec_yrep = num_pdfs <= 255 && rec_lds_bytes(rows, num_pdfs, h->wide, true) <= 96 * 1024;
-        if (env_int("LFMMI_YREP", 1) == 0) h->rec_yrep = false;
         // the register-resident kernel has a fixed LDS map: 32 KB per buffer
         if (h->rec_nslot > 0 &&
             (rows > 8192 || (h->rec_yrep ? (size_t)num_pdfs * 128 : (size_t)num_pdfs * 4) > 32764))
@@ -580,7 +592,7 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph* h, int64_t info[8])
 }
 
 lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t ord,
-                                       int64_t info[8])
+                                       int64_t info[12])
 {
     if (!h || !info) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
     if (g < 0 || g >= h->num_graphs || ord < 0 || ord > 2)
@@ -594,6 +606,8 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t 
     info[5] = ord < 2 ? h->rec_nslot : 0;
     info[6] = ord < 2 && h->rec_yrep ? 1 : 0;
     info[7] = o.has_wb;
+    info[8] = o.gather_cycles;
+    info[9] = info[10] = info[11] = 0;
     return LFMMI_OK;
 }
 

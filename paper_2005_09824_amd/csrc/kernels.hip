@@ -340,10 +340,23 @@ constexpr uint32_t kRegYZero = 32764;  // byte offset of the zero word inside a 
 
 __host__ __device__ constexpr size_t reg_lds_bytes() { return kRegPart + 3 * 32 * sizeof(float); }
 
+// LDS access by absolute byte address (the kernel's dynamic LDS starts at 0: it
+// declares no static LDS), so that the address register goes straight into the
+// ds instruction and constant parts fold into its immediate offset.
+typedef __attribute__((address_space(3))) float lds_float_t;
+__device__ __forceinline__ float lds_ld(uint32_t addr)
+{
+    return *reinterpret_cast<const lds_float_t*>(static_cast<uintptr_t>(addr));
+}
+__device__ __forceinline__ void lds_st(uint32_t addr, float v)
+{
+    *reinterpret_cast<lds_float_t*>(static_cast<uintptr_t>(addr)) = v;
+}
+
 template <bool YREP, bool HAS_WB, int NSLOT, int NT>
 struct RecRegs {
-    static constexpr int kYRegs = NT >= 1024 ? 3 : 6;
-    static constexpr int kPrefetch = NT >= 1024 ? 4 : 8;
+    static constexpr int kYRegs = NT >= 1024 ? 3 : (NT >= 768 ? 4 : 6);
+    static constexpr int kPrefetch = NT >= 1024 ? 4 : 6;
 
     uint32_t xa[NSLOT];  // byte address of the state value inside X0
     uint32_t ya[NSLOT];  // LDS byte address of the emission value in Y0 (absolute)
@@ -372,13 +385,13 @@ struct RecRegs {
 #pragma unroll
             for (int i = 0; i < kYRegs; ++i) {
                 const int q = tid + i * nthreads;
-                if (q < ylen) *reinterpret_cast<float*>(lds + yn + q * 4) = yreg[i];
+                if (q < ylen) lds_st(yn + q * 4, yreg[i]);
             }
             if (ylen > kYRegs * nthreads) {
                 const int fr = dir == 0 ? k : T - k - 1;
                 const float* e = p.emis + (erow0 + fr) * P;
                 for (int q = tid + kYRegs * nthreads; q < ylen; q += nthreads)
-                    *reinterpret_cast<float*>(lds + yn + q * 4) = e[YREP ? q >> 5 : q];
+                    lds_st(yn + q * 4, e[YREP ? q >> 5 : q]);
             }
         }
         if (k + 1 < T && !(p.debug & 2)) {
@@ -392,7 +405,7 @@ struct RecRegs {
         }
 
         // scalars of step k - 1: lanes 0-15 fetch the n partials, 16-31 the s partials
-        float pv = *reinterpret_cast<const float*>(lds + pc + (lane & 31) * 4);
+        float pv = lds_ld(pc + (lane & 31) * 4);
         pv = row16_allsum(pv);
         const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
         const float Sd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16));
@@ -414,8 +427,8 @@ struct RecRegs {
         float xv[kPrefetch], ev[kPrefetch];
 #pragma unroll
         for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
-            xv[i] = *reinterpret_cast<const float*>(lds + xc + xa[i]);
-            ev[i] = *reinterpret_cast<const float*>(lds + yc + ya[i]);
+            xv[i] = lds_ld(xc + xa[i]);
+            ev[i] = lds_ld(yc + ya[i]);
         }
         float acc1 = 0.f, acc2 = 0.f, n = 0.f, s = 0.f;
         uint64_t left = mask;
@@ -430,8 +443,8 @@ struct RecRegs {
 #else
             if (i + kPrefetch < NSLOT) {
 #endif
-                xv[i % kPrefetch] = *reinterpret_cast<const float*>(lds + xc + xa[i + kPrefetch]);
-                ev[i % kPrefetch] = *reinterpret_cast<const float*>(lds + yc + ya[i + kPrefetch]);
+                xv[i % kPrefetch] = lds_ld(xc + xa[i + kPrefetch]);
+                ev[i % kPrefetch] = lds_ld(yc + ya[i + kPrefetch]);
             }
             // an arc slot; closing and padding slots see e == 0 or w == 0 and add nothing
             const float t = wr[i] * e;
@@ -443,7 +456,7 @@ struct RecRegs {
             if (i == next_close) {  // wave-uniform: the slice ends here
 #endif
                 const float v = fmaf(inv, acc1, cb * acc2);
-                *reinterpret_cast<float*>(lds + xn + row * 4) = v;
+                lds_st(xn + row * 4, v);
                 if (!(p.debug & 1)) tr[row] = v;
                 n += v;
                 s = fmaf(wr[i], v, s);
@@ -459,8 +472,8 @@ struct RecRegs {
         s = wave_sum_uniform(s);
 #endif
         if (lane == 0) {
-            *reinterpret_cast<float*>(lds + pn + wave * 4) = n;
-            *reinterpret_cast<float*>(lds + pn + 64 + wave * 4) = s;
+            lds_st(pn + wave * 4, n);
+            lds_st(pn + 64 + wave * 4, s);
         }
 #if !(defined(LFMMI_EXP) && (LFMMI_EXP & 2))
         __syncthreads();
@@ -513,14 +526,17 @@ struct RecRegs {
                          : kRegYZero);
             wr[i] = __uint_as_float(r.y);
             if (HAS_WB) wbr[i] = (on && !closing) ? wbp[(size_t)(first + i) * 64] : 0.f;
+            // opaque from here on: the three values stay in three registers for the
+            // whole time loop instead of being re-derived from the record each frame
+            asm volatile("" : "+v"(xa[i]), "+v"(ya[i]), "+v"(wr[i]));
         }
 
         // zero words of the Y buffers, partial slots
         if (tid == 0) {
-            *reinterpret_cast<float*>(lds + kRegY0 + kRegYZero) = 0.f;
-            *reinterpret_cast<float*>(lds + kRegY1 + kRegYZero) = 0.f;
+            lds_st(kRegY0 + kRegYZero, 0.f);
+            lds_st(kRegY1 + kRegYZero, 0.f);
         }
-        if (tid < 64) *reinterpret_cast<float*>(lds + kRegPart + tid * 4) = 0.f;
+        if (tid < 64) lds_st(kRegPart + tid * 4, 0.f);
         __syncthreads();
 
         // ---- step 0: v_0 = init into X0, partials into slot set 0
@@ -530,7 +546,7 @@ struct RecRegs {
             for (int sl = s0; sl < s1; ++sl) {
                 const int row = sl * 64 + lane;
                 const float v = p.g.vinit[od.vec_at + row];
-                *reinterpret_cast<float*>(lds + row * 4) = v;
+                lds_st(row * 4, v);
                 trel[(size_t)ti * rows + row] = v;
                 n += v;
                 s = fmaf(p.g.va[od.vec_at + row], v, s);
@@ -538,14 +554,14 @@ struct RecRegs {
             n = wave_sum_uniform(n);
             s = wave_sum_uniform(s);
             if (lane == 0) {
-                *reinterpret_cast<float*>(lds + kRegPart + wave * 4) = n;
-                *reinterpret_cast<float*>(lds + kRegPart + 64 + wave * 4) = s;
+                lds_st(kRegPart + wave * 4, n);
+                lds_st(kRegPart + 64 + wave * 4, s);
             }
             if (T > 0) {
                 const int fr = dir == 0 ? 0 : T - 1;
                 const float* e = p.emis + (erow0 + fr) * P;
                 for (int q = tid; q < ylen; q += nthreads)
-                    *reinterpret_cast<float*>(lds + kRegY0 + q * 4) = e[YREP ? q >> 5 : q];
+                    lds_st(kRegY0 + q * 4, e[YREP ? q >> 5 : q]);
             }
             if (T > 1) {
                 const int fr = dir == 0 ? 1 : T - 2;
@@ -575,7 +591,7 @@ struct RecRegs {
         {
             const uint32_t xc = (T & 1) ? kRegX1 : 0u;
             const uint32_t pc = kRegPart + ((T & 1) ? 128u : 0u);
-            float pv = *reinterpret_cast<const float*>(lds + pc + (lane & 31) * 4);
+            float pv = lds_ld(pc + (lane & 31) * 4);
             pv = row16_allsum(pv);
             const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
             const float Sd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16));
@@ -589,18 +605,18 @@ struct RecRegs {
             float z = 0.f;
             for (int sl = s0; sl < s1; ++sl) {
                 const int row = sl * 64 + lane;
-                const float v = fmaf(*reinterpret_cast<const float*>(lds + xc + row * 4), inv,
+                const float v = fmaf(lds_ld(xc + row * 4), inv,
                                      c * p.g.vb[od.vec_at + row]);
                 z = fmaf(p.g.vfin[od.vec_at + row], v, z);
             }
             z = wave_sum_uniform(z);
             __syncthreads();  // every wave has read the partials
-            if (lane == 0) *reinterpret_cast<float*>(lds + kRegPart + 256 + wave * 4) = z;
+            if (lane == 0) lds_st(kRegPart + 256 + wave * 4, z);
             __syncthreads();
             if (tid == 0) {
                 float Z = 0.f;
                 for (int w = 0; w < (nthreads >> 6); ++w)
-                    Z += *reinterpret_cast<const float*>(lds + kRegPart + 256 + w * 4);
+                    Z += lds_ld(kRegPart + 256 + w * 4);
                 static_cast<float*>(p.zfin)[(size_t)dir * p.B + b] = Z;
             }
         }
@@ -802,6 +818,8 @@ const RecVariant kRecVariants[] = {
     LFMMI_REC(float, 0, 16, 0, 1024), LFMMI_REC(float, 0, 24, 0, 1024),
     LFMMI_REC(float, 0, 28, 0, 1024),
     LFMMI_REC(float, 0, 16, 1, 1024),
+    // register-resident arcs, 12 waves (168 VGPRs per lane)
+    LFMMI_REC(float, 0, 32, 0, 768), LFMMI_REC(float, 0, 36, 0, 768),
     // register-resident arcs, 8 waves (256 VGPRs per lane)
     LFMMI_REC(float, 0, 32, 0, 512), LFMMI_REC(float, 0, 48, 0, 512),
     LFMMI_REC(float, 0, 32, 1, 512), LFMMI_REC(float, 0, 48, 1, 512),

@@ -120,6 +120,217 @@ inline void put(Ordering* o, int32_t position, int32_t nth, uint32_t x, uint32_t
     o->w[at] = w;
 }
 
+
+// ---- LDS bank conflicts -------------------------------------------------------
+// A wave's gather is served half-wave by half-wave (32 lanes); within a half,
+// lanes that hit the same one of the 32 four-byte banks at different addresses
+// are served one after the other. Two things are free at pack time: which lane
+// of its half-slice a state owns (its bank, as a gathered value), and the order
+// of a row's arcs over the slots.
+
+constexpr int kBanks = 32;
+constexpr int kHalf = 32;
+
+struct Lcg {
+    uint64_t s;
+    explicit Lcg(uint64_t seed) : s(seed * 2862933555777941757ULL + 3037000493ULL) {}
+    uint32_t next() { s = s * 6364136223846793005ULL + 1442695040888963407ULL; return (uint32_t)(s >> 33); }
+    uint32_t below(uint32_t n) { return (uint32_t)(((uint64_t)next() * n) >> 31) % n; }
+};
+
+// Re-deals the lanes inside every half-slice so that, for each half-slice of
+// rows, the states its arcs gather are spread evenly over the banks.
+// row_state[a] / x_state[a]: the state that owns the row of arc a / the state
+// whose value arc a gathers. pos: state -> slice * 64 + lane (updated).
+void balance_banks(const std::vector<int32_t>& row_state, const std::vector<int32_t>& x_state,
+                   std::vector<int32_t>* pos)
+{
+    const int64_t A = (int64_t)row_state.size();
+    const int32_t S = (int32_t)pos->size();
+    if (A < 256 || S < 2 * kHalf) return;
+    int32_t halves = 0;
+    for (int32_t s = 0; s < S; ++s) halves = std::max(halves, (*pos)[s] / kHalf + 1);
+    // arcs gathered from each state, as the half-slice of their row
+    std::vector<int32_t> first(S + 1, 0);
+    for (int64_t a = 0; a < A; ++a) ++first[x_state[a] + 1];
+    for (int32_t s = 0; s < S; ++s) first[s + 1] += first[s];
+    std::vector<int32_t> half_of(A), fill(first.begin(), first.end() - 1);
+    for (int64_t a = 0; a < A; ++a) half_of[fill[x_state[a]]++] = (*pos)[row_state[a]] / kHalf;
+    std::vector<int32_t> load((size_t)halves * kBanks, 0);
+    for (int32_t s = 0; s < S; ++s)
+        for (int32_t i = first[s]; i < first[s + 1]; ++i)
+            ++load[(size_t)half_of[i] * kBanks + (*pos)[s] % kBanks];
+    // members of each half-slice
+    std::vector<std::vector<int32_t>> members(halves);
+    for (int32_t s = 0; s < S; ++s) members[(*pos)[s] / kHalf].push_back(s);
+
+    Lcg rng(0x5eed0000u + (uint64_t)A);
+    const int64_t tries = std::min<int64_t>(60 * A, 6000000);
+    for (int64_t it = 0; it < tries; ++it) {
+        const int32_t u = (int32_t)rng.below((uint32_t)S);
+        const std::vector<int32_t>& m = members[(*pos)[u] / kHalf];
+        if (m.size() < 2) continue;
+        const int32_t v = m[rng.below((uint32_t)m.size())];
+        const int32_t bu = (*pos)[u] % kBanks, bv = (*pos)[v] % kBanks;
+        if (u == v || bu == bv) continue;
+        // change of sum of squares if u and v trade banks
+        int64_t delta = 0;
+        auto shift = [&](int32_t st, int32_t from, int32_t to, int sign) {
+            for (int32_t i = first[st]; i < first[st + 1]; ++i) {
+                int32_t* row = &load[(size_t)half_of[i] * kBanks];
+                delta += sign * (2 * (row[to] - row[from]) + 2);
+                --row[from];
+                ++row[to];
+            }
+        };
+        shift(u, bu, bv, 1);
+        shift(v, bv, bu, 1);
+        if (delta <= 0) {
+            std::swap((*pos)[u], (*pos)[v]);
+        } else {  // undo
+            shift(v, bu, bv, 1);
+            shift(u, bv, bu, 1);
+        }
+    }
+}
+
+// Chooses the slot (0 .. width - 1 inside its slice) of every arc. pos_row[a]:
+// position of the arc's row; bx[a], by[a]: banks of its two gathers, -1 for a
+// gather that cannot conflict. width[slice]: arc slots of the slice.
+void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>& bx,
+                 const std::vector<int16_t>& by, int32_t num_slices,
+                 const std::vector<int32_t>& width, std::vector<int32_t>* nth)
+{
+    const int64_t A = (int64_t)pos_row.size();
+    nth->assign(A, 0);
+    const int32_t halves = num_slices * 2;
+    std::vector<std::vector<int32_t>> arcs_of(halves);
+    for (int64_t a = 0; a < A; ++a) arcs_of[pos_row[a] / kHalf].push_back((int32_t)a);
+    Lcg rng(0xb0a7u + (uint64_t)A);
+    std::vector<int32_t> slot_of;      // per arc of the half-slice
+    std::vector<int32_t> table;        // [row][slot] -> local arc index or -1
+    std::vector<int32_t> lx, ly;       // [slot][bank]
+    for (int32_t h = 0; h < halves; ++h) {
+        const std::vector<int32_t>& arcs = arcs_of[h];
+        const int32_t W = width[h / 2];
+        const int32_t n = (int32_t)arcs.size();
+        if (n == 0 || W == 0) continue;
+        table.assign((size_t)kHalf * W, -1);
+        lx.assign((size_t)W * kBanks, 0);
+        ly.assign((size_t)W * kBanks, 0);
+        slot_of.assign(n, -1);
+        std::vector<std::vector<int32_t>> row_arcs(kHalf);
+        for (int32_t i = 0; i < n; ++i) row_arcs[pos_row[arcs[i]] % kHalf].push_back(i);
+        auto cost_at = [&](int32_t j, int32_t i) {
+            const int32_t a = arcs[i];
+            int32_t c = 0;
+            if (bx[a] >= 0) c += lx[(size_t)j * kBanks + bx[a]];
+            if (by[a] >= 0) c += ly[(size_t)j * kBanks + by[a]];
+            return c;
+        };
+        auto place = [&](int32_t r, int32_t j, int32_t i, int sign) {
+            const int32_t a = arcs[i];
+            if (bx[a] >= 0) lx[(size_t)j * kBanks + bx[a]] += sign;
+            if (by[a] >= 0) ly[(size_t)j * kBanks + by[a]] += sign;
+            table[(size_t)r * W + j] = sign > 0 ? i : -1;
+            slot_of[i] = sign > 0 ? j : -1;
+        };
+        // greedy: slot by slot, rows with the fewest arcs left choose first
+        std::vector<int32_t> order(kHalf);
+        std::vector<std::vector<int32_t>> left = row_arcs;
+        for (int32_t j = 0; j < W; ++j) {
+            std::iota(order.begin(), order.end(), 0);
+            std::stable_sort(order.begin(), order.end(), [&](int32_t p, int32_t q) {
+                return left[p].size() < left[q].size();
+            });
+            for (int32_t r : order) {
+                std::vector<int32_t>& cand = left[r];
+                if (cand.empty()) continue;
+                size_t best = 0;
+                int32_t best_cost = cost_at(j, cand[0]);
+                for (size_t c = 1; c < cand.size(); ++c) {
+                    const int32_t cc = cost_at(j, cand[c]);
+                    if (cc < best_cost) { best_cost = cc; best = c; }
+                }
+                place(r, j, cand[best], 1);
+                cand.erase(cand.begin() + best);
+            }
+        }
+        // hill climbing on the sum of squared bank loads: move an arc of a row to
+        // another slot of that row (swapping with what is there)
+        auto sq_delta_move = [&](int32_t i, int32_t from, int32_t to) {
+            // change of sum of squares when arc i leaves slot `from` for slot `to`
+            const int32_t a = arcs[i];
+            int64_t d = 0;
+            if (bx[a] >= 0) {
+                d += -2 * lx[(size_t)from * kBanks + bx[a]] + 1;
+                d += 2 * lx[(size_t)to * kBanks + bx[a]] + 1;
+            }
+            if (by[a] >= 0) {
+                d += -2 * ly[(size_t)from * kBanks + by[a]] + 1;
+                d += 2 * ly[(size_t)to * kBanks + by[a]] + 1;
+            }
+            return d;
+        };
+        const int64_t tries = 40LL * n;
+        for (int64_t it = 0; it < tries; ++it) {
+            const int32_t i = (int32_t)rng.below((uint32_t)n);
+            const int32_t r = pos_row[arcs[i]] % kHalf;
+            const int32_t j1 = slot_of[i];
+            const int32_t j2 = (int32_t)rng.below((uint32_t)W);
+            if (j1 == j2) continue;
+            const int32_t other = table[(size_t)r * W + j2];
+            // apply, measure, keep if not worse
+            int64_t d = sq_delta_move(i, j1, j2);
+            place(r, j1, i, -1);
+            if (other >= 0) {
+                d += sq_delta_move(other, j2, j1);
+                place(r, j2, other, -1);
+                // the two moves interact when they share a bank
+                const int32_t a = arcs[i], o = arcs[other];
+                if (bx[a] >= 0 && bx[a] == bx[o]) d -= 2;
+                if (by[a] >= 0 && by[a] == by[o]) d -= 2;
+            }
+            if (d <= 0) {
+                place(r, j2, i, 1);
+                if (other >= 0) place(r, j1, other, 1);
+            } else {
+                place(r, j1, i, 1);
+                if (other >= 0) place(r, j2, other, 1);
+            }
+        }
+        for (int32_t i = 0; i < n; ++i) (*nth)[arcs[i]] = slot_of[i];
+    }
+}
+
+// Modelled LDS cycles of the x gather (and the y gather when count_y) of one
+// ordering: per slot and half-wave, the largest number of distinct addresses
+// that fall into one bank (at least 1).
+int64_t gather_cycles(const Ordering& o, bool count_y)
+{
+    int64_t total = 0;
+    std::vector<uint32_t> seen;
+    for (int32_t sl = 0; sl < o.num_slices; ++sl)
+        for (int32_t j = o.slice_off[sl]; j < o.slice_off[sl + 1]; ++j)
+            for (int h = 0; h < 2; ++h)
+                for (int which = 0; which < (count_y ? 2 : 1); ++which) {
+                    int best = 1;
+                    for (int b = 0; b < kBanks; ++b) {
+                        seen.clear();
+                        for (int l = 0; l < kHalf; ++l) {
+                            const uint32_t key = o.key[(size_t)j * kLanes + h * kHalf + l];
+                            const uint32_t idx = which == 0 ? (key & 0xffffu) / 4 : (key >> 16) / 4;
+                            if ((int)(idx % kBanks) != b) continue;
+                            if (std::find(seen.begin(), seen.end(), idx) == seen.end())
+                                seen.push_back(idx);
+                        }
+                        best = std::max(best, (int)seen.size());
+                    }
+                    total += best;
+                }
+    return total;
+}
+
 }  // namespace
 
 int choose_waves(int64_t num_arcs, int32_t num_states)
@@ -140,7 +351,8 @@ bool uniform_init(const ArcList& g)
 }
 
 std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int occ_waves,
-                       bool per_arc_leak, PackedGraph* out, bool* bad_graph)
+                       bool per_arc_leak, const PackTuning& tune, PackedGraph* out,
+                       bool* bad_graph)
 {
     *bad_graph = false;
     const int32_t S = g.num_states;
@@ -174,9 +386,14 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     // ---- FWD (rows = to-states) and BWD (rows = from-states) arrangements
     std::vector<int32_t> indeg(S, 0), outdeg(S, 0);
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
-    const Arrangement af = arrange(indeg, rec_waves, 1);
-    const Arrangement ab = arrange(outdeg, rec_waves, 1);
+    Arrangement af = arrange(indeg, rec_waves, 1);
+    Arrangement ab = arrange(outdeg, rec_waves, 1);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
+    std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
+    if (tune.balance_banks) {
+        balance_banks(vdst, vsrc, &af.pos);  // alpha gathers from-states in FWD numbering
+        balance_banks(vsrc, vdst, &ab.pos);  // beta gathers to-states in BWD numbering
+    }
     start_ordering(af, S, &out->ord[0]);
     start_ordering(ab, S, &out->ord[1]);
     for (int32_t s = 0; s < S; ++s) {
@@ -185,12 +402,34 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     }
     std::vector<float> w(A);
     for (int64_t a = 0; a < A; ++a) w[a] = (float)std::exp((double)g.logw[a]);
+    // slot of every arc inside its row, per ordering
+    std::vector<int32_t> nth_f(A), nth_b(A);
     {
-        std::vector<int32_t> nf(S, 0), nb(S, 0);
+        std::vector<int32_t> prow_f(A), prow_b(A), wf(af.num_slices), wb_(ab.num_slices);
+        std::vector<int16_t> bxf(A), bxb(A), byy(A);
+        for (int64_t a = 0; a < A; ++a) {
+            prow_f[a] = af.pos[g.dst[a]];
+            prow_b[a] = ab.pos[g.src[a]];
+            bxf[a] = (int16_t)(af.pos[g.src[a]] % kBanks);
+            bxb[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);
+            byy[a] = tune.emission_conflicts ? (int16_t)(g.pdf[a] % kBanks) : (int16_t)-1;
+        }
+        for (int32_t sl = 0; sl < af.num_slices; ++sl) wf[sl] = af.slice_width[sl] - 1;
+        for (int32_t sl = 0; sl < ab.num_slices; ++sl) wb_[sl] = ab.slice_width[sl] - 1;
+        if (tune.order_slots) {
+            order_slots(prow_f, bxf, byy, af.num_slices, wf, &nth_f);
+            order_slots(prow_b, bxb, byy, ab.num_slices, wb_, &nth_b);
+        } else {
+            std::vector<int32_t> nf(S, 0), nb(S, 0);
+            for (int64_t a = 0; a < A; ++a) {
+                nth_f[a] = nf[g.dst[a]]++;
+                nth_b[a] = nb[g.src[a]]++;
+            }
+        }
         for (int64_t a = 0; a < A; ++a) {
             const int32_t i = g.src[a], j = g.dst[a];
-            put(&out->ord[0], af.pos[j], nf[j]++, (uint32_t)af.pos[i], (uint32_t)g.pdf[a], w[a]);
-            put(&out->ord[1], ab.pos[i], nb[i]++, (uint32_t)ab.pos[j], (uint32_t)g.pdf[a], w[a]);
+            put(&out->ord[0], af.pos[j], nth_f[a], (uint32_t)af.pos[i], (uint32_t)g.pdf[a], w[a]);
+            put(&out->ord[1], ab.pos[i], nth_b[a], (uint32_t)ab.pos[j], (uint32_t)g.pdf[a], w[a]);
         }
     }
 
@@ -243,13 +482,12 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             Ordering& ob = out->ord[1];
             of.wb.assign(of.w.size(), 0.f);
             ob.wb.assign(ob.w.size(), 0.f);
-            std::vector<int32_t> nf(S, 0), nb(S, 0);
             for (int64_t a = 0; a < A; ++a) {
                 const int32_t i = g.src[a], j = g.dst[a];
                 const int32_t pf = af.pos[j], pb = ab.pos[i];
-                of.wb[(size_t)(of.slice_off[pf / kLanes] + nf[j]++) * kLanes + pf % kLanes] =
+                of.wb[(size_t)(of.slice_off[pf / kLanes] + nth_f[a]) * kLanes + pf % kLanes] =
                     w[a] * g.init_prob[i];
-                ob.wb[(size_t)(ob.slice_off[pb / kLanes] + nb[i]++) * kLanes + pb % kLanes] = w[a];
+                ob.wb[(size_t)(ob.slice_off[pb / kLanes] + nth_b[a]) * kLanes + pb % kLanes] = w[a];
             }
         }
     }
@@ -281,15 +519,26 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             out->row_pdf4[ao.pos[r]] = pdf_of[r] * 4;
         }
         std::vector<int64_t> seen(num_pdfs, 0);
+        std::vector<int32_t> prow(A), nth(A), wo(ao.num_slices);
+        std::vector<int16_t> bx(A), by(A);
         for (int64_t a = 0; a < A; ++a) {
             const int32_t d = g.pdf[a];
             const int64_t r = first_row[d] + seen[d] / piece;
-            const int32_t nth = (int32_t)(seen[d] % piece);
+            nth[a] = (int32_t)(seen[d] % piece);
             ++seen[d];
-            put(&out->ord[2], ao.pos[r], nth, (uint32_t)af.pos[g.src[a]],
-                (uint32_t)ab.pos[g.dst[a]], w[a]);
+            prow[a] = ao.pos[r];
+            bx[a] = (int16_t)(af.pos[g.src[a]] % kBanks);
+            by[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);
         }
+        for (int32_t sl = 0; sl < ao.num_slices; ++sl) wo[sl] = ao.slice_width[sl];
+        if (tune.order_slots) order_slots(prow, bx, by, ao.num_slices, wo, &nth);
+        for (int64_t a = 0; a < A; ++a)
+            put(&out->ord[2], prow[a], nth[a], (uint32_t)af.pos[g.src[a]],
+                (uint32_t)ab.pos[g.dst[a]], w[a]);
     }
+    out->ord[0].gather_cycles = gather_cycles(out->ord[0], tune.emission_conflicts);
+    out->ord[1].gather_cycles = gather_cycles(out->ord[1], tune.emission_conflicts);
+    out->ord[2].gather_cycles = gather_cycles(out->ord[2], true);
     return std::string();
 }
 

@@ -39,6 +39,7 @@ struct Ordering {
     // wave_mask[w] has bit i set when slot i of wave w is such a closing slot
     // (0 when the wave owns more than 64 slots).
     std::vector<uint64_t> wave_mask;  // [num_waves]
+    int64_t gather_cycles = 0;        // modelled LDS cycles of the gathers of one frame
     float b_const = 0.f;              // leak target when it is one constant (BWD 1, FWD uniform pi)
     int32_t has_wb = 0;               // wb is filled
 };
@@ -70,10 +71,18 @@ int choose_waves(int64_t num_arcs, int32_t num_states);
 
 // Validates and packs one graph. Returns an empty string on success, else the
 // reason (bad_graph says whether the graph or an argument is at fault).
+// What the packer does about LDS bank conflicts of the fp32 kernels.
+struct PackTuning {
+    bool balance_banks = true;        // re-deal lanes inside half-slices (state -> bank)
+    bool order_slots = true;          // order each row's arcs over its slots
+    bool emission_conflicts = true;   // the emission gather can conflict (row not replicated)
+};
+
 // per_arc_leak: fill the per-arc leak factors (required when init_prob is not
 // uniform over the states).
 std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int occ_waves,
-                       bool per_arc_leak, PackedGraph* out, bool* bad_graph);
+                       bool per_arc_leak, const PackTuning& tune, PackedGraph* out,
+                       bool* bad_graph);
 // True when every state has the same initial probability.
 bool uniform_init(const ArcList& g);
 
