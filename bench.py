@@ -76,7 +76,7 @@ def main():
     dt = time.perf_counter() - t0
     kern = binding.lfmmi_profile_read(den)
     binding.lfmmi_profile_enable(den, False)
-    if int(status.abs().sum().item()) != 0 and not os.environ.get("LFMMI_DEBUG"):
+    if int(status.abs().sum().item()) != 0:
         print("bench.py: a sequence was flagged", file=sys.stderr)
         return 1
 

@@ -164,7 +164,9 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         // lane) before settling for streamed arcs.
         for (int attempt = 0; attempt < 2; ++attempt) {
             h->rec_waves = waves;
-            h->occ_waves = waves;
+            // the occupancy pass is throughput work: at most 8 waves, so that a lane
+            // has 256 registers for its arcs
+            h->occ_waves = std::min(waves, env_int("LFMMI_OCC_WAVES", 8));
             h->packed.assign(n, PackedGraph());
             h->max_rows_f = h->max_rows_b = 0;
             int max_slots = 0;
@@ -183,7 +185,6 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
                     max_slots = std::max(max_slots, h->packed[g].ord[o].max_wave_slots);
             }
             h->rec_nslot = rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
-            if (env_int("LFMMI_STREAM", 0) != 0) h->rec_nslot = 0;
             if (h->rec_nslot > 0 || h->wide || forced > 0 || waves <= 8 || attempt == 1) break;
             const int half = waves / 2;
             if (rec_register_slots(h->wide, h->has_wb, 2 * max_slots, half * kLanes) == 0) break;
@@ -536,7 +537,6 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     p.cfac = ws + at_cfac;
     p.zfin = ws + at_zfin;
     p.wide = h->wide ? 1 : 0;
-    p.debug = env_int("LFMMI_DEBUG", 0);
     p.status_ws = reinterpret_cast<int32_t*>(ws + at_status);
     p.status_out = status;
     p.objf = objf;

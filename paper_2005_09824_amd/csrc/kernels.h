@@ -68,7 +68,6 @@ struct FbParams {
     int32_t lds_rows_occ_a, lds_rows_occ_b;
     int32_t accumulate;
     int32_t wide;           // 1: state vectors, trellis and scales in fp64
-    int32_t debug;          // experiments only (LFMMI_DEBUG): bit 0 skips the trellis stores
     float leak, grad_scale;
 };
 

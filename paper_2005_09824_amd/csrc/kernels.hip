@@ -394,7 +394,7 @@ struct RecRegs {
                     lds_st(yn + q * 4, e[YREP ? q >> 5 : q]);
             }
         }
-        if (k + 1 < T && !(p.debug & 2)) {
+        if (k + 1 < T) {
             const int fr = dir == 0 ? k + 1 : T - k - 2;
             const float* e = p.emis + (erow0 + fr) * P;
 #pragma unroll
@@ -416,7 +416,7 @@ struct RecRegs {
         }
         const float c = eps * Sd * inv;
         const float cb = HAS_WB ? c : c * bconst;
-        if (tid == 0 && !(p.debug & 4)) {
+        if (tid == 0) {
             const int tp = dir == 0 ? k - 1 : T - k + 1;
             scalN[tp] = N;
             scalS[tp] = Sd;
@@ -438,11 +438,7 @@ struct RecRegs {
         for (int i = 0; i < NSLOT; ++i) {
             const float x = xv[i % kPrefetch];
             const float e = ev[i % kPrefetch];
-#if defined(LFMMI_EXP) && (LFMMI_EXP & 8)
-            if (false) {
-#else
             if (i + kPrefetch < NSLOT) {
-#endif
                 xv[i % kPrefetch] = lds_ld(xc + xa[i + kPrefetch]);
                 ev[i % kPrefetch] = lds_ld(yc + ya[i + kPrefetch]);
             }
@@ -450,14 +446,10 @@ struct RecRegs {
             const float t = wr[i] * e;
             acc1 = fmaf(t, x, acc1);
             acc2 = HAS_WB ? fmaf(wbr[i], e, acc2) : acc2 + t;
-#if defined(LFMMI_EXP) && (LFMMI_EXP & 1)
-            if (false) {
-#else
             if (i == next_close) {  // wave-uniform: the slice ends here
-#endif
                 const float v = fmaf(inv, acc1, cb * acc2);
                 lds_st(xn + row * 4, v);
-                if (!(p.debug & 1)) tr[row] = v;
+                tr[row] = v;
                 n += v;
                 s = fmaf(wr[i], v, s);
                 acc1 = 0.f;
@@ -467,17 +459,13 @@ struct RecRegs {
                 next_close = left ? __builtin_ctzll(left) : 64;
             }
         }
-#if !(defined(LFMMI_EXP) && (LFMMI_EXP & 4))
         n = wave_sum_uniform(n);
         s = wave_sum_uniform(s);
-#endif
         if (lane == 0) {
             lds_st(pn + wave * 4, n);
             lds_st(pn + 64 + wave * 4, s);
         }
-#if !(defined(LFMMI_EXP) && (LFMMI_EXP & 2))
         __syncthreads();
-#endif
     }
 
     __device__ __forceinline__ void run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
@@ -517,9 +505,6 @@ struct RecRegs {
             const bool closing = (mask >> i) & 1;
             const uint2 r = on ? recs[(size_t)(first + i) * 64] : make_uint2(0u, 0u);
             xa[i] = r.x & 0xffffu;
-#if defined(LFMMI_EXP) && (LFMMI_EXP & 16)
-            xa[i] = (uint32_t)((lane * 4 + i * 256) & 8191);  // conflict-free pattern (timing only)
-#endif
             ya[i] = kRegY0 +
                     ((on && !closing)
                          ? (YREP ? (r.x >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (r.x >> 16))
@@ -849,6 +834,7 @@ int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
 
 hipError_t configure_kernels()
 {
+
     for (const RecVariant& v : kRecVariants) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <numeric>
 
 namespace lfmmi {
@@ -120,6 +121,19 @@ inline void put(Ordering* o, int32_t position, int32_t nth, uint32_t x, uint32_t
     o->w[at] = w;
 }
 
+
+// wave_mask[w]: bit i set when slot i of wave w closes a slice.
+void fill_wave_mask(Ordering* o)
+{
+    o->wave_mask.assign(o->num_waves, 0);
+    for (int32_t wv = 0; wv < o->num_waves; ++wv) {
+        const int32_t first = o->slice_off[o->wave_first[wv]];
+        const int32_t count = o->slice_off[o->wave_first[wv + 1]] - first;
+        if (count > 64) continue;
+        for (int32_t sl = o->wave_first[wv]; sl < o->wave_first[wv + 1]; ++sl)
+            o->wave_mask[wv] |= (uint64_t)1 << (o->slice_off[sl + 1] - 1 - first);
+    }
+}
 
 // ---- LDS bank conflicts -------------------------------------------------------
 // A wave's gather is served half-wave by half-wave (32 lanes); within a half,
@@ -457,14 +471,7 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
                 o.key[at] = 0u;
                 o.w[at] = out->va[d][(size_t)sl * kLanes + l];
             }
-        o.wave_mask.assign(o.num_waves, 0);
-        for (int32_t wv = 0; wv < o.num_waves; ++wv) {
-            const int32_t first = o.slice_off[o.wave_first[wv]];
-            const int32_t count = o.slice_off[o.wave_first[wv + 1]] - first;
-            if (count > 64) continue;
-            for (int32_t sl = o.wave_first[wv]; sl < o.wave_first[wv + 1]; ++sl)
-                o.wave_mask[wv] |= (uint64_t)1 << (o.slice_off[sl + 1] - 1 - first);
-        }
+        fill_wave_mask(&o);
     }
     // leak target: BWD adds the same amount to every state; FWD adds pi, which
     // is one constant when pi is uniform. Otherwise (or when another graph of
@@ -494,11 +501,19 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
 
     // ---- OCC: arcs grouped by pdf, each pdf's list cut into pieces
     {
-        const int lanes_total = kLanes * std::max(1, occ_waves);
-        int64_t piece = (A + lanes_total - 1) / lanes_total;
-        piece = std::max<int64_t>(4, std::min<int64_t>(piece, 32));
         std::vector<int64_t> count(num_pdfs, 0);
         for (int64_t a = 0; a < A; ++a) ++count[g.pdf[a]];
+        // piece length: the one whose slices deal out most evenly over the waves
+        // (a wave's load is about slices-per-wave * piece)
+        const int waves_o = std::max(1, occ_waves);
+        int64_t piece = 4, best_load = -1;
+        for (int64_t len = 4; len <= 64; ++len) {
+            int64_t rows = 0;
+            for (int32_t d = 0; d < num_pdfs; ++d) rows += (count[d] + len - 1) / len;
+            const int64_t slices = (rows + kLanes - 1) / kLanes;
+            const int64_t load = (slices + waves_o - 1) / waves_o * len;
+            if (best_load < 0 || load <= best_load) { best_load = load; piece = len; }
+        }
         std::vector<int64_t> first_row(num_pdfs + 1, 0);
         for (int32_t d = 0; d < num_pdfs; ++d)
             first_row[d + 1] = first_row[d] + (count[d] + piece - 1) / piece;
