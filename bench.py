@@ -23,6 +23,9 @@ sys.path.insert(0, ROOT)
 # MI355X: 256 CUs x 128 B/clk LDS x 2.4 GHz
 LDS_PEAK_GBPS = 256 * 128 * 2.4
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the recursion kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
+# a plain copy of known size (profiles/hbm_traffic_wsj_mono_2k.txt); other workloads: not measured
+REC_TRAFFIC_BYTES = {"wsj_mono_2k": 357.8e6}
 
 
 def main():
@@ -32,6 +35,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 is the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="only run plain device-to-device copies of BYTES (to calibrate the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; sequences are independent, so "
@@ -46,6 +52,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_probe > 0:
+        n = args.copy_probe // 4
+        a = torch.ones(n, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": n * 4, "copies": 4}))
+        return 0
     wl = workloads.make_workload(args.config)
     lengths, leak = wl["lengths"], wl["leak"]
     frames = int(lengths.sum())
@@ -108,8 +124,12 @@ def main():
                    "numerators": num is not None},
         "roofline": {"bound": "lds", "kernel": "k_rec", "achieved": achieved,
                      "peak": LDS_PEAK_GBPS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBPS,
-                     "traffic": None,
-                     "workgroups": 2 * B, "compute_units": 256},
+                     "traffic": REC_TRAFFIC_BYTES.get(wl["name"]),
+                     "kernel_ms": kern["rec"],
+                     "workgroups": 2 * B, "compute_units": 256,
+                     # the same against the LDS peak of the compute units a workgroup holds
+                     "frac_of_occupied_cus": achieved / (LDS_PEAK_GBPS * min(2 * B, 256) / 256.0),
+                     "hbm_frac": (REC_TRAFFIC_BYTES.get(wl["name"], 0.0) / rec_s / 1e9) / HBM_PEAK_GBPS},
         "kernels_ms": {k: kern[k] for k in ("emit", "rec", "scan", "occ")},
         "arc_updates_per_s": 2.0 * A * fps,
         "workspace_bytes": info["workspace_bytes"],
