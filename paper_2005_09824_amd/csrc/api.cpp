@@ -559,6 +559,13 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     shape.rec_has_wb = h->has_wb ? 1 : 0;
     shape.occ_threads = h->occ_waves * kLanes;
     shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
+    // the plane-layout occupancy kernel (several frames per arc record) when it fits
+    shape.occ_multi = h->wide ? 0 : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b), P);
+    {
+        const int forced = env_int("LFMMI_OCC_MULTI", -1);
+        if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;
+    }
+    shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", 1));
 
     hipEvent_t* ev = nullptr;
     if (h->profile) {

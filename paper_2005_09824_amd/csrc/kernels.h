@@ -77,7 +77,9 @@ struct LaunchShape {
     int rec_yrep;      // emission row replicated across LDS banks
     int rec_has_wb;    // arcs carry a per-arc leak factor
     int occ_threads;   // workgroup size of the occupancy kernel
-    int occ_frames;    // frames per occupancy workgroup
+    int occ_frames;    // frames per occupancy workgroup (frame-at-a-time kernel)
+    int occ_multi;     // frames per record of the plane-layout occupancy kernel (0: not used)
+    int occ_groups;    // groups of occ_multi frames per workgroup
 };
 
 // Each returns the first HIP error met (hipSuccess otherwise). ev, if non-null,
@@ -90,5 +92,7 @@ size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
 // Register-resident slot count the recursion kernel offers for this shape (0: none).
 int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
 size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide);
+int occ_plane_frames(int rows, int P);
+size_t occ_plane_lds_bytes(int P, int frames);
 
 }  // namespace lfmmi

@@ -784,6 +784,194 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Occupancy, F frames at a time (fp32). The arc records are the bulk of what
+// the frame-at-a-time kernel pulls out of L2 (8 bytes per arc and frame), and
+// every chunk of them costs an exposed L2 latency; here one record serves F
+// consecutive frames. LDS holds one plane per frame and side at a fixed stride,
+//   XA[f] at f * STRIDE, XB[f] at (F + f) * STRIDE, bins[f][pdf] after them,
+// so a gather is a 4-byte read at the record's state offset plus an immediate,
+// with the bank pattern the packer ordered the slots for.
+// ---------------------------------------------------------------------------
+template <int F, int STRIDE>
+__global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_wg)
+{
+    static_assert(2 * F * STRIDE <= 65536, "plane offsets must fit the ds immediate");
+    constexpr uint32_t kBins = 2u * F * STRIDE;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nthreads = blockDim.x;
+    const int b = blockIdx.y;
+    const SeqDesc sd = p.seqs[b];
+    const int T = sd.T;
+    const int P = p.P;
+    const int Ppad = (P + 63) & ~63;
+    const OrdDesc od = p.g.ords[sd.graph * 3 + 2];
+    const OrdDesc odf = p.g.ords[sd.graph * 3 + 0];
+    const OrdDesc odb = p.g.ords[sd.graph * 3 + 1];
+    const int rows_f = odf.num_slices * 64, rows_b = odb.num_slices * 64;
+
+    const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+    const int32_t* so = p.g.slice_off + od.slice_off_at;
+    const int32_t* row_pdf4 = p.g.row_pdf4 + od.vec_at;
+    const float* scal = static_cast<const float*>(p.scal) + sd.scal_at;
+    const float* cfac = static_cast<const float*>(p.cfac) + sd.scal_at;
+    const float* vb_f = p.g.vb + odf.vec_at;
+    const float* vb_b = p.g.vb + odb.vec_at;
+    const float* alpha = static_cast<const float*>(p.alpha) + sd.alpha_at;
+    const float* beta = static_cast<const float*>(p.beta) + sd.beta_at;
+    const float eps = p.leak;
+    int s0 = 0, s1 = 0;
+    if (wave < od.num_waves) {
+        s0 = p.g.wave_first[od.wave_first_at + wave];
+        s1 = p.g.wave_first[od.wave_first_at + wave + 1];
+    }
+
+    const int t_begin = blockIdx.x * groups_per_wg * F + 1;
+    const int t_end = min(t_begin + groups_per_wg * F - 1, p.T);
+    for (int t0 = t_begin; t0 <= t_end; t0 += F) {
+        if (t0 > T) {  // nothing but padding rows from here on
+            if (!p.accumulate)
+                for (int t = t0; t <= t_end; ++t) {
+                    float* g = p.grad + ((size_t)b * p.T + (t - 1)) * P;
+                    for (int d = tid; d < P; d += nthreads) g[d] = 0.f;
+                }
+            break;
+        }
+        // per-frame scalars: the trellis holds raw vectors, vhat' = v / n + (eps s / n) b
+        float inva[F], ca[F], invb[F], cb[F], cf[F];
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+            const int t = t0 + f;
+            const bool live = t <= T;
+            cf[f] = live ? cfac[t] : 0.f;
+            const float na = live ? scal[t - 1] : 1.f, sa = live ? scal[p.scal_total + t - 1] : 0.f;
+            const float nb = live ? scal[2 * p.scal_total + t] : 1.f;
+            const float sb = live ? scal[3 * p.scal_total + t] : 0.f;
+            const bool ok = live && cf[f] != 0.f;  // dead sequences stage zeros
+            inva[f] = ok ? 1.f / na : 0.f;
+            ca[f] = eps * sa * inva[f];
+            invb[f] = ok ? 1.f / nb : 0.f;
+            cb[f] = eps * sb * invb[f];
+        }
+        __syncthreads();  // the previous group's gathers and bin reads are done
+        // staging: two rows per thread and side in flight, all loads (alpha and beta)
+        // issued before any is used
+        const int rows_max = max(rows_f, rows_b);
+        for (int r0 = 0; r0 < rows_max; r0 += 2 * nthreads) {
+            float va[2][F], vbt[2][F], ba[2], bbt[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int r = r0 + u * nthreads + tid;
+                ba[u] = r < rows_f ? vb_f[r] : 0.f;
+                bbt[u] = r < rows_b ? vb_b[r] : 0.f;
+#pragma unroll
+                for (int f = 0; f < F; ++f) {
+                    const bool live = t0 + f <= T;
+                    va[u][f] = (r < rows_f && live) ? alpha[(size_t)(t0 - 1 + f) * rows_f + r] : 0.f;
+                    vbt[u][f] = (r < rows_b && live) ? beta[(size_t)(t0 + f) * rows_b + r] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int r = r0 + u * nthreads + tid;
+#pragma unroll
+                for (int f = 0; f < F; ++f) {
+                    if (r < rows_f)
+                        lds_st((uint32_t)(f * STRIDE) + (uint32_t)r * 4u,
+                               fmaf(va[u][f], inva[f], ca[f] * ba[u]));
+                    if (r < rows_b)
+                        lds_st((uint32_t)((F + f) * STRIDE) + (uint32_t)r * 4u,
+                               fmaf(vbt[u][f], invb[f], cb[f] * bbt[u]));
+                }
+            }
+        }
+        for (int d = tid; d < F * Ppad; d += nthreads) lds_st(kBins + (uint32_t)d * 4u, 0.f);
+        __syncthreads();
+
+        auto one_slot = [&](const uint2 r, float* acc) {
+            const uint32_t xa = r.x & 0xffffu, xb = r.x >> 16;
+            const float w = __uint_as_float(r.y);
+#pragma unroll
+            for (int f = 0; f < F; ++f) {
+                const float a = lds_ld(xa + (uint32_t)(f * STRIDE));
+                const float bt = lds_ld(xb + (uint32_t)((F + f) * STRIDE));
+                acc[f] = fmaf(w * bt, a, acc[f]);
+            }
+        };
+        // emission values of this thread's gradient entries, in flight during the gathers
+        float ev[F];
+#pragma unroll
+        for (int f = 0; f < F; ++f)
+            ev[f] = (tid < P && t0 + f <= T) ? p.emis[((size_t)b * p.T + (t0 + f - 1)) * P + tid] : 0.f;
+
+        for (int sl = s0; sl < s1; ++sl) {
+            const int o0 = so[sl], o1 = so[sl + 1];
+            const uint2* rp = recs + (size_t)o0 * 64;
+            float acc[F];
+#pragma unroll
+            for (int f = 0; f < F; ++f) acc[f] = 0.f;
+            // chunks of 8 records, the next chunk loading while this one is used
+            uint2 cur[8], nxt[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) cur[u] = o0 + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
+            for (int i = o0; i < o1; i += 8) {
+                rp += 512;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    nxt[u] = i + 8 + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
+                if (i + 8 <= o1) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) one_slot(cur[u], acc);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (i + u < o1) one_slot(cur[u], acc);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
+            }
+            const int pd = row_pdf4[sl * 64 + lane];
+            if (pd >= 0) {
+#pragma unroll
+                for (int f = 0; f < F; ++f)
+                    __hip_atomic_fetch_add(
+                        reinterpret_cast<lds_float_t*>(static_cast<uintptr_t>(
+                            kBins + (uint32_t)(f * Ppad) * 4u + (uint32_t)pd)),
+                        acc[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+            const int t = t0 + f;
+            if (t > p.T) break;
+            const size_t at = ((size_t)b * p.T + (t - 1)) * P;
+            float* g = p.grad + at;
+            if (t > T) {
+                if (!p.accumulate)
+                    for (int d = tid; d < P; d += nthreads) g[d] = 0.f;
+                continue;
+            }
+            const float scale = p.grad_scale * cf[f];
+            const float* e = p.emis + at;
+            if (tid < P) {
+                const float v = cf[f] == 0.f
+                                    ? 0.f
+                                    : scale * ev[f] * lds_ld(kBins + (uint32_t)(f * Ppad + tid) * 4u);
+                g[tid] = p.accumulate ? g[tid] + v : v;
+            }
+            for (int d = tid + nthreads; d < P; d += nthreads) {
+                const float v = cf[f] == 0.f
+                                    ? 0.f
+                                    : scale * e[d] * lds_ld(kBins + (uint32_t)(f * Ppad + d) * 4u);
+                g[d] = p.accumulate ? g[d] + v : v;
+            }
+        }
+    }
+}
+
 // ---- kernel variants ---------------------------------------------------------
 using RecKernel = void (*)(FbParams);
 
@@ -841,7 +1029,10 @@ hipError_t configure_kernels()
         if (e != hipSuccess) return e;
     }
     const void* fns[] = {reinterpret_cast<const void*>(k_occ<float>),
-                         reinterpret_cast<const void*>(k_occ<double>)};
+                         reinterpret_cast<const void*>(k_occ<double>),
+                         reinterpret_cast<const void*>(k_occ_planes<4, 8192>),
+                         reinterpret_cast<const void*>(k_occ_planes<2, 16384>),
+                         reinterpret_cast<const void*>(k_occ_planes<1, 32768>)};
     for (const void* f : fns) {
         hipError_t e =
             hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -861,6 +1052,22 @@ size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide)
 {
     const size_t Ppad = (size_t)((P + 63) & ~63);
     return ((size_t)rows_a + rows_b + 2 * Ppad) * (wide ? 8 : 4);
+}
+
+// Frames per record of the plane-layout occupancy kernel for this many rows
+// (0: rows or pdfs do not fit its fixed LDS map).
+int occ_plane_frames(int rows, int P)
+{
+    const size_t Ppad = (size_t)((P + 63) & ~63);
+    for (int f : {4, 2, 1})
+        if (rows * 4 <= 32768 / f && 65536 + (size_t)f * Ppad * 4 <= 160 * 1024) return f;
+    return 0;
+}
+
+size_t occ_plane_lds_bytes(int P, int frames)
+{
+    const size_t Ppad = (size_t)((P + 63) & ~63);
+    return 65536 + (size_t)frames * Ppad * 4;
 }
 
 template <typename Real>
@@ -892,10 +1099,21 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     if ((e = hipGetLastError()) != hipSuccess) return e;
     LFMMI_EV(3)
     if (p.T > 0) {
-        dim3 grid((p.T + shape.occ_frames - 1) / shape.occ_frames, p.B);
-        hipLaunchKernelGGL(k_occ<Real>, grid, dim3(shape.occ_threads),
-                           occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b, p.P, wide), stream,
-                           p, shape.occ_frames);
+        if (!wide && shape.occ_multi > 0) {
+            const int F = shape.occ_multi;
+            const int per_wg = F * shape.occ_groups;
+            dim3 grid((p.T + per_wg - 1) / per_wg, p.B);
+            void (*fn)(FbParams, int) = F == 4   ? k_occ_planes<4, 8192>
+                                        : F == 2 ? k_occ_planes<2, 16384>
+                                                 : k_occ_planes<1, 32768>;
+            hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads), occ_plane_lds_bytes(p.P, F),
+                               stream, p, shape.occ_groups);
+        } else {
+            dim3 grid((p.T + shape.occ_frames - 1) / shape.occ_frames, p.B);
+            hipLaunchKernelGGL(k_occ<Real>, grid, dim3(shape.occ_threads),
+                               occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b, p.P, wide),
+                               stream, p, shape.occ_frames);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     LFMMI_EV(4)
