@@ -152,7 +152,8 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
  *   slice_off  [slices + 1] first slot of each slice
  *   wave_first [waves + 1]  first slice of each wave
  *   key, w     [total slots * 64] arc records, lane-minor; key = x-index * 4 in
- *              the low 16 bits, y-index * 4 in the high 16 bits; padding has w 0.
+ *              the low 16 bits, y-index * 4 in the high 16 bits; padding has w 0 (its
+ *              key points wherever no bank conflict arises).
  *              In FWD and BWD the last slot of every slice holds no arc: its
  *              key is 0 and its w is the row's leak-dot weight (FWD: 1 on real
  *              rows; BWD: init_prob of the row's state)

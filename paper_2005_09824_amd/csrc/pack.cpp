@@ -208,6 +208,78 @@ void balance_banks(const std::vector<int32_t>& row_state, const std::vector<int3
     }
 }
 
+// Single-gather slot order by bipartite edge colouring. Rows and banks of one
+// half-slice form a bipartite multigraph (one edge per arc); a proper colouring
+// with W colours puts at most one arc of every row and of every bank node into
+// each slot. A bank that gathers more than W arcs is split into several nodes of
+// at most W arcs, so it shows up that many times in some slots and once in the
+// others. slot_of[i] receives the colour of arc i (rows[i] in 0..31, banks[i]
+// in 0..31).
+void colour_half_slice(const std::vector<int32_t>& rows, const std::vector<int32_t>& banks,
+                       int32_t W, std::vector<int32_t>* slot_of)
+{
+    const int32_t n = (int32_t)rows.size();
+    slot_of->assign(n, -1);
+    if (n == 0 || W == 0) return;
+    // bank nodes: bank b, copy k -> node id; arcs of a bank fill copy 0 first
+    std::vector<int32_t> node_of(n), seen(kBanks, 0), first_node(kBanks + 1, 0);
+    std::vector<int32_t> demand(kBanks, 0);
+    for (int32_t i = 0; i < n; ++i) ++demand[banks[i]];
+    for (int b = 0; b < kBanks; ++b)
+        first_node[b + 1] = first_node[b] + std::max(1, (demand[b] + W - 1) / W);
+    for (int32_t i = 0; i < n; ++i) node_of[i] = first_node[banks[i]] + seen[banks[i]]++ / W;
+    const int32_t nodes = first_node[kBanks];
+    std::vector<int32_t> at_row((size_t)kHalf * W, -1), at_node((size_t)nodes * W, -1);
+    auto free_colour = [&](const std::vector<int32_t>& tab, int32_t who) {
+        for (int32_t c = 0; c < W; ++c)
+            if (tab[(size_t)who * W + c] < 0) return c;
+        return (int32_t)-1;
+    };
+    // Arcs of the extra nodes of overloaded banks go first: with every colour
+    // still free they all land in the lowest colours, so that the slots in which
+    // some bank shows up twice are shared between the overloaded banks.
+    std::vector<int32_t> order;
+    order.reserve(n);
+    for (int32_t e = 0; e < n; ++e)
+        if (node_of[e] != first_node[banks[e]]) order.push_back(e);
+    for (int32_t e = 0; e < n; ++e)
+        if (node_of[e] == first_node[banks[e]]) order.push_back(e);
+    for (int32_t e : order) {
+        const int32_t u = rows[e], v = node_of[e];
+        const int32_t a = free_colour(at_row, u);   // free at the row
+        const int32_t b = free_colour(at_node, v);  // free at the bank node
+        if (a < 0 || b < 0) continue;               // cannot happen: degrees are <= W
+        if (at_node[(size_t)v * W + a] >= 0) {
+            // a is taken at v: flip the a/b alternating path that starts at v
+            std::vector<int32_t> path;
+            int32_t cur_is_node = 1, who = v, want = a;
+            while (true) {
+                const int32_t f = cur_is_node ? at_node[(size_t)who * W + want]
+                                              : at_row[(size_t)who * W + want];
+                if (f < 0) break;
+                path.push_back(f);
+                who = cur_is_node ? rows[f] : node_of[f];
+                cur_is_node ^= 1;
+                want = want == a ? b : a;
+            }
+            for (int32_t f : path) {
+                const int32_t c = (*slot_of)[f];
+                at_row[(size_t)rows[f] * W + c] = -1;
+                at_node[(size_t)node_of[f] * W + c] = -1;
+            }
+            for (int32_t f : path) {
+                const int32_t c = (*slot_of)[f] == a ? b : a;
+                (*slot_of)[f] = c;
+                at_row[(size_t)rows[f] * W + c] = f;
+                at_node[(size_t)node_of[f] * W + c] = f;
+            }
+        }
+        (*slot_of)[e] = a;
+        at_row[(size_t)u * W + a] = e;
+        at_node[(size_t)v * W + a] = e;
+    }
+}
+
 // Chooses the slot (0 .. width - 1 inside its slice) of every arc. pos_row[a]:
 // position of the arc's row; bx[a], by[a]: banks of its two gathers, -1 for a
 // gather that cannot conflict. width[slice]: arc slots of the slice.
@@ -249,6 +321,21 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
             table[(size_t)r * W + j] = sign > 0 ? i : -1;
             slot_of[i] = sign > 0 ? j : -1;
         };
+        if (by[arcs[0]] < 0 && bx[arcs[0]] >= 0) {
+            // one gather only: an edge colouring is (nearly) conflict-free by construction
+            std::vector<int32_t> rws(n), bks(n), col;
+            for (int32_t i = 0; i < n; ++i) {
+                rws[i] = pos_row[arcs[i]] % kHalf;
+                bks[i] = bx[arcs[i]];
+            }
+            colour_half_slice(rws, bks, W, &col);
+            bool ok = true;
+            for (int32_t i = 0; i < n; ++i) ok = ok && col[i] >= 0;
+            if (ok) {
+                for (int32_t i = 0; i < n; ++i) (*nth)[arcs[i]] = col[i];
+                continue;
+            }
+        }
         // greedy: slot by slot, rows with the fewest arcs left choose first
         std::vector<int32_t> order(kHalf);
         std::vector<std::vector<int32_t>> left = row_arcs;
@@ -314,6 +401,50 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
             }
         }
         for (int32_t i = 0; i < n; ++i) (*nth)[arcs[i]] = slot_of[i];
+    }
+}
+
+// Padding slots (w == 0) still gather: point each at a bank its half-wave does
+// not use in that slot (or, failing that, at an address another lane reads
+// anyway), so that padding never adds a bank conflict. fix_y: do the same for
+// the second gather. skip_last: leave the closing slot of every slice alone.
+void retarget_padding(Ordering* o, bool fix_y, bool skip_last, int32_t x_rows, int32_t y_rows)
+{
+    for (int32_t sl = 0; sl < o->num_slices; ++sl) {
+        const int32_t j1 = o->slice_off[sl + 1] - (skip_last ? 1 : 0);
+        for (int32_t j = o->slice_off[sl]; j < j1; ++j)
+            for (int h = 0; h < 2; ++h)
+                for (int which = 0; which < (fix_y ? 2 : 1); ++which) {
+                    const int32_t limit = which == 0 ? x_rows : y_rows;
+                    bool used[kBanks] = {false};
+                    int32_t any = -1;
+                    for (int l = 0; l < kHalf; ++l) {
+                        const size_t at = (size_t)j * kLanes + h * kHalf + l;
+                        if (o->w[at] == 0.f) continue;
+                        const uint32_t idx =
+                            which == 0 ? (o->key[at] & 0xffffu) / 4 : (o->key[at] >> 16) / 4;
+                        used[idx % kBanks] = true;
+                        any = (int32_t)idx;
+                    }
+                    int next_free = 0;
+                    for (int l = 0; l < kHalf; ++l) {
+                        const size_t at = (size_t)j * kLanes + h * kHalf + l;
+                        if (o->w[at] != 0.f) continue;
+                        while (next_free < kBanks && (used[next_free] || next_free >= limit))
+                            ++next_free;
+                        uint32_t idx = 0;
+                        if (next_free < kBanks) {
+                            idx = (uint32_t)next_free;  // bank next_free, nobody else there
+                            used[next_free] = true;
+                        } else if (any >= 0) {
+                            idx = (uint32_t)any;        // same address as a real arc: broadcast
+                        }
+                        if (which == 0)
+                            o->key[at] = (o->key[at] & 0xffff0000u) | (idx * 4u);
+                        else
+                            o->key[at] = (o->key[at] & 0x0000ffffu) | ((idx * 4u) << 16);
+                    }
+                }
     }
 }
 
@@ -550,6 +681,12 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         for (int64_t a = 0; a < A; ++a)
             put(&out->ord[2], prow[a], nth[a], (uint32_t)af.pos[g.src[a]],
                 (uint32_t)ab.pos[g.dst[a]], w[a]);
+    }
+    if (tune.order_slots) {
+        const int32_t rf = af.num_slices * kLanes, rb = ab.num_slices * kLanes;
+        retarget_padding(&out->ord[0], tune.emission_conflicts, true, rf, num_pdfs);
+        retarget_padding(&out->ord[1], tune.emission_conflicts, true, rb, num_pdfs);
+        retarget_padding(&out->ord[2], true, false, rf, rb);
     }
     out->ord[0].gather_cycles = gather_cycles(out->ord[0], tune.emission_conflicts);
     out->ord[1].gather_cycles = gather_cycles(out->ord[1], tune.emission_conflicts);

@@ -55,9 +55,8 @@ def _unpack(graph_handle, g, graph):
                 row = s * 64 + lane
                 for i in range(o0, o1):
                     k, w = int(d["key"][i * 64 + lane]), float(d["w"][i * 64 + lane])
-                    if w == 0.0:      # padding: anywhere in the row (slots are ordered
-                        assert k == 0  # to spread LDS banks), always key 0
-                        continue
+                    if w == 0.0:      # padding: anywhere in the row (slots are ordered to
+                        continue      # spread LDS banks); its key points at an unused bank
                     assert d["row_id"][row] >= 0
                     x, y = (k & 0xFFFF) // 4, (k >> 16) // 4
                     if o == 0:
