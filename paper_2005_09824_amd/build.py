@@ -14,7 +14,8 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # scalar fp32 only: no packed-fp32 instructions from the auto-vectoriser
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-munsafe-fp-atomics",  # native LDS float add for the occupancy bins
+    # private arrays stay out of LDS: kernels here address LDS by absolute offsets
+    "-mllvm", "-disable-promote-alloca-to-lds",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -52,7 +52,7 @@ struct lfmmi_graph {
     int rec_waves = 1, occ_waves = 1;
     std::vector<PackedGraph> packed;
     std::vector<OrdDesc> ords;  // [num_graphs * 3]
-    int32_t max_rows_f = 0, max_rows_b = 0;
+    int32_t max_rows_f = 0, max_rows_b = 0, max_rows_occ = 0;
     bool wide = false;  // fp64 state vectors (some state is not final)
     int rec_nslot = 0;  // register-resident arc slots of the recursion kernel (0: streamed)
     bool rec_yrep = false;
@@ -168,7 +168,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             // has 256 registers for its arcs
             h->occ_waves = std::min(waves, env_int("LFMMI_OCC_WAVES", 8));
             h->packed.assign(n, PackedGraph());
-            h->max_rows_f = h->max_rows_b = 0;
+            h->max_rows_f = h->max_rows_b = h->max_rows_occ = 0;
             int max_slots = 0;
             for (int32_t g = 0; g < n; ++g) {
                 bool bad = false;
@@ -181,6 +181,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
                 }
                 h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
                 h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
+                h->max_rows_occ = std::max(h->max_rows_occ, h->packed[g].ord[2].num_slices * kLanes);
                 for (int o = 0; o < 2; ++o)
                     max_slots = std::max(max_slots, h->packed[g].ord[o].max_wave_slots);
             }
@@ -192,7 +193,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         }
         const int rows = std::max(h->max_rows_f, h->max_rows_b);
         if (rec_lds_bytes(rows, num_pdfs, h->wide, false) > kLdsBytes ||
-            occ_lds_bytes(h->max_rows_f, h->max_rows_b, num_pdfs, h->wide) > kLdsBytes) {
+            occ_lds_bytes(h->max_rows_f, h->max_rows_b, h->max_rows_occ, h->wide) > kLdsBytes) {
             delete h;
             return fail(LFMMI_ERR_UNSUPPORTED,
                         "states and pdfs do not fit the 160 KB of LDS of one compute unit");
@@ -225,7 +226,7 @@ lfmmi_status upload(lfmmi_graph* h)
     if ((e = configure_kernels()) != hipSuccess) return fail_hip(e, "hipFuncSetAttribute");
 
     // concatenate every graph's orderings
-    size_t n_slots = 0, n_soff = 0, n_wf = 0, n_vec = 0, n_rowpdf = 0, n_mask = 0;
+    size_t n_slots = 0, n_soff = 0, n_wf = 0, n_vec = 0, n_rowpdf = 0, n_mask = 0, n_pfirst = 0;
     h->ords.assign((size_t)h->num_graphs * 3, OrdDesc{});
     for (int32_t g = 0; g < h->num_graphs; ++g)
         for (int o = 0; o < 3; ++o) {
@@ -252,6 +253,8 @@ lfmmi_status upload(lfmmi_graph* h)
             } else {
                 d.vec_at = (int32_t)n_rowpdf;
                 n_rowpdf += (size_t)od.num_slices * kLanes;
+                d.pdf_first_at = (int32_t)n_pfirst;
+                n_pfirst += h->packed[g].pdf_first.size();
             }
         }
     if (n_slots > (size_t)1 << 30) return fail(LFMMI_ERR_UNSUPPORTED, "packed graph too large");
@@ -267,6 +270,7 @@ lfmmi_status upload(lfmmi_graph* h)
     const size_t at_vb = reserve<float>(&total, n_vec);
     const size_t at_vfin = reserve<float>(&total, n_vec);
     const size_t at_rowpdf = reserve<int32_t>(&total, n_rowpdf);
+    const size_t at_pfirst = reserve<int32_t>(&total, n_pfirst);
     const size_t at_ords = reserve<OrdDesc>(&total, h->ords.size());
     total = std::max<size_t>(total, kAlign);
 
@@ -304,8 +308,11 @@ lfmmi_status upload(lfmmi_graph* h)
                 std::memcpy(host.data() + at_vb + (size_t)d.vec_at * 4, pg.vb[o].data(), nrow * 4);
                 std::memcpy(host.data() + at_vfin + (size_t)d.vec_at * 4, pg.vfin[o].data(), nrow * 4);
             } else {
-                std::memcpy(host.data() + at_rowpdf + (size_t)d.vec_at * 4,
-                            h->packed[g].row_pdf4.data(), nrow * 4);
+                const PackedGraph& pg = h->packed[g];
+                std::memcpy(host.data() + at_rowpdf + (size_t)d.vec_at * 4, pg.pdf_rows.data(),
+                            nrow * 4);
+                std::memcpy(host.data() + at_pfirst + (size_t)d.pdf_first_at * 4,
+                            pg.pdf_first.data(), pg.pdf_first.size() * 4);
             }
         }
     std::memcpy(host.data() + at_ords, h->ords.data(), h->ords.size() * sizeof(OrdDesc));
@@ -329,7 +336,8 @@ lfmmi_status upload(lfmmi_graph* h)
     h->dg.va = reinterpret_cast<const float*>(base + at_va);
     h->dg.vb = reinterpret_cast<const float*>(base + at_vb);
     h->dg.vfin = reinterpret_cast<const float*>(base + at_vfin);
-    h->dg.row_pdf4 = reinterpret_cast<const int32_t*>(base + at_rowpdf);
+    h->dg.pdf_rows = reinterpret_cast<const int32_t*>(base + at_rowpdf);
+    h->dg.pdf_first = reinterpret_cast<const int32_t*>(base + at_pfirst);
     h->dg.ords = reinterpret_cast<const OrdDesc*>(base + at_ords);
     h->uploaded = true;
     return LFMMI_OK;
@@ -548,6 +556,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     p.lds_rows = std::max(h->max_rows_f, h->max_rows_b);
     p.lds_rows_occ_a = h->max_rows_f;
     p.lds_rows_occ_b = h->max_rows_b;
+    p.lds_rows_occ = h->max_rows_occ;
     p.accumulate = accumulate ? 1 : 0;
     p.leak = leak;
     p.grad_scale = grad_scale;
@@ -560,7 +569,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     shape.occ_threads = h->occ_waves * kLanes;
     shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
     // the plane-layout occupancy kernel (several frames per arc record) when it fits
-    shape.occ_multi = h->wide ? 0 : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b), P);
+    shape.occ_multi = h->wide ? 0 : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b), h->max_rows_occ);
     {
         const int forced = env_int("LFMMI_OCC_MULTI", -1);
         if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;

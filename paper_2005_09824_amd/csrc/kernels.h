@@ -13,13 +13,13 @@ struct OrdDesc {
     int32_t rec_at;         // first slot (units of 64 records) in recs
     int32_t slice_off_at;   // first entry in slice_off (num_slices + 1 entries)
     int32_t wave_first_at;  // first entry in wave_first (num_waves + 1 entries)
-    int32_t vec_at;         // FWD/BWD: first row in vinit/va/vb/vfin; OCC: in row_pdf4
+    int32_t vec_at;         // FWD/BWD: first row in vinit/va/vb/vfin; OCC: in pdf_rows
     int32_t max_wave_slots;
     int32_t total_slots;
     int32_t mask_at;        // FWD/BWD: first entry in wave_mask (num_waves entries)
     int32_t has_wb;         // FWD: the leak target differs per state
     float b_const;          // the leak target when it is one constant
-    int32_t pad;
+    int32_t pdf_first_at;   // OCC: first entry in pdf_first (num_pdfs + 1 entries)
 };
 
 struct DeviceGraph {
@@ -32,7 +32,8 @@ struct DeviceGraph {
     const float* va;
     const float* vb;
     const float* vfin;
-    const int32_t* row_pdf4;
+    const int32_t* pdf_first;   // OCC rows of pdf d: pdf_rows[pdf_first[d] .. pdf_first[d + 1])
+    const int32_t* pdf_rows;    // row positions (slice * 64 + lane)
     const OrdDesc* ords;        // [num_graphs * 3]
 };
 
@@ -66,6 +67,7 @@ struct FbParams {
     int32_t B, T, P;
     int32_t lds_rows;       // largest padded row count over the handle's graphs
     int32_t lds_rows_occ_a, lds_rows_occ_b;
+    int32_t lds_rows_occ;   // largest padded OCC row count over the handle's graphs
     int32_t accumulate;
     int32_t wide;           // 1: state vectors, trellis and scales in fp64
     float leak, grad_scale;
@@ -91,8 +93,8 @@ hipError_t configure_kernels();
 size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
 // Register-resident slot count the recursion kernel offers for this shape (0: none).
 int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
-size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide);
-int occ_plane_frames(int rows, int P);
-size_t occ_plane_lds_bytes(int P, int frames);
+size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide);
+int occ_plane_frames(int rows, int occ_rows);
+size_t occ_plane_lds_bytes(int occ_rows, int frames);
 
 }  // namespace lfmmi

@@ -686,7 +686,10 @@ __global__ void __launch_bounds__(256) k_scan(FbParams p)
 
 // ---------------------------------------------------------------------------
 // Occupancy and gradient, frames in parallel. Rows of the OCC ordering are
-// pieces of one pdf's arc list; a row's sum goes to its pdf's LDS bin.
+// pieces of one pdf's arc list; a row's sum is stored to LDS and one thread per
+// pdf then adds that pdf's rows in table order, so the result does not depend
+// on timing. (An LDS float atomic add takes about 190 clocks per wave
+// instruction on this chip whatever its addresses, against 2 to 4 for a store.)
 //   gamma_t[d] = c_t * e_t[d] * sum_{a: pdf_a = d} w_a * ahat_{t-1}[src_a] * bhat_t[dst_a]
 // ---------------------------------------------------------------------------
 template <typename Real>
@@ -707,19 +710,18 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     const SeqDesc sd = p.seqs[b];
     const int T = sd.T;
     const int P = p.P;
-    const int Ppad = (P + 63) & ~63;
     const OrdDesc od = p.g.ords[sd.graph * 3 + 2];
     const int rows_f = p.g.ords[sd.graph * 3 + 0].num_slices * 64;
     const int rows_b = p.g.ords[sd.graph * 3 + 1].num_slices * 64;
 
     Real* XA = reinterpret_cast<Real*>(lds_raw);
     Real* XB = XA + p.lds_rows_occ_a;
-    Real* bins0 = XB + p.lds_rows_occ_b;
-    Real* bins1 = bins0 + Ppad;
+    Real* rowsum = XB + p.lds_rows_occ_b;
 
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
-    const int32_t* row_pdf4 = p.g.row_pdf4 + od.vec_at;
+    const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
+    const int32_t* pdf_rows = p.g.pdf_rows + od.vec_at;
     const Real* cfac = static_cast<const Real*>(p.cfac) + sd.scal_at;
     const Real* scal = static_cast<const Real*>(p.scal) + sd.scal_at;
     const float* vb_f = p.g.vb + p.g.ords[sd.graph * 3 + 0].vec_at;
@@ -742,7 +744,6 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
                 for (int d = tid; d < P; d += nthreads) g[d] = 0.f;
             continue;
         }
-        Real* bins = (t & 1) ? bins1 : bins0;
         // the trellis holds raw vectors: vhat' = v / n + (eps * s / n) * b
         const Real na = scal[t - 1], sa = scal[p.scal_total + t - 1];
         const Real nb = scal[2 * p.scal_total + t], sb = scal[3 * p.scal_total + t];
@@ -752,7 +753,6 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
         const Real* br = static_cast<const Real*>(p.beta) + sd.beta_at + (size_t)t * rows_b;
         for (int r = tid; r < rows_f; r += nthreads) XA[r] = ar[r] * inva + ca * (Real)vb_f[r];
         for (int r = tid; r < rows_b; r += nthreads) XB[r] = br[r] * invb + cb * (Real)vb_b[r];
-        for (int d = tid; d < P; d += nthreads) bins[d] = 0;
         __syncthreads();
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
@@ -771,16 +771,19 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
                 acc += occ_term(rp[0], XA, XB);
                 rp += 64;
             }
-            const int pd = row_pdf4[sl * 64 + lane];
-            if (pd >= 0) atomicAdd(bins + (pd >> 2), acc);
+            rowsum[sl * 64 + lane] = acc;
         }
         __syncthreads();
         const Real scale = (Real)p.grad_scale * c;
         const float* e = p.emis + at;
         for (int d = tid; d < P; d += nthreads) {
-            const float v = (float)(scale * (Real)e[d] * bins[d]);
+            Real sum = 0;
+            for (int r = pdf_first[d], r1 = pdf_first[d + 1]; r < r1; ++r) sum += rowsum[pdf_rows[r]];
+            const float v = (float)(scale * (Real)e[d] * sum);
             g[d] = p.accumulate ? g[d] + v : v;
         }
+        // the next frame's row sums are stored after its staging barrier, which
+        // every thread reaches only once it is done here
     }
 }
 
@@ -789,15 +792,18 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 // the frame-at-a-time kernel pulls out of L2 (8 bytes per arc and frame), and
 // every chunk of them costs an exposed L2 latency; here one record serves F
 // consecutive frames. LDS holds one plane per frame and side at a fixed stride,
-//   XA[f] at f * STRIDE, XB[f] at (F + f) * STRIDE, bins[f][pdf] after them,
+//   XA[f] at f * STRIDE, XB[f] at (F + f) * STRIDE, row sums [f][row] after them,
 // so a gather is a 4-byte read at the record's state offset plus an immediate,
-// with the bank pattern the packer ordered the slots for.
+// with the bank pattern the packer ordered the slots for. Thread f * P + d then
+// adds the row sums of pdf d in frame f and writes that gradient entry: the F
+// gradient rows of a group are contiguous, so the write is coalesced.
 // ---------------------------------------------------------------------------
 template <int F, int STRIDE>
 __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_wg)
 {
     static_assert(2 * F * STRIDE <= 65536, "plane offsets must fit the ds immediate");
-    constexpr uint32_t kBins = 2u * F * STRIDE;
+    constexpr uint32_t kRowSum = 2u * F * STRIDE;
+    constexpr int kPre = 8;  // row positions a thread fetches ahead of the gathers
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -806,15 +812,16 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
     const SeqDesc sd = p.seqs[b];
     const int T = sd.T;
     const int P = p.P;
-    const int Ppad = (P + 63) & ~63;
     const OrdDesc od = p.g.ords[sd.graph * 3 + 2];
     const OrdDesc odf = p.g.ords[sd.graph * 3 + 0];
     const OrdDesc odb = p.g.ords[sd.graph * 3 + 1];
     const int rows_f = odf.num_slices * 64, rows_b = odb.num_slices * 64;
+    const int occ_rows = od.num_slices * 64;
 
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
-    const int32_t* row_pdf4 = p.g.row_pdf4 + od.vec_at;
+    const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
+    const int32_t* pdf_rows = p.g.pdf_rows + od.vec_at;
     const float* scal = static_cast<const float*>(p.scal) + sd.scal_at;
     const float* cfac = static_cast<const float*>(p.cfac) + sd.scal_at;
     const float* vb_f = p.g.vb + odf.vec_at;
@@ -827,6 +834,20 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
         s0 = p.g.wave_first[od.wave_first_at + wave];
         s1 = p.g.wave_first[od.wave_first_at + wave + 1];
     }
+    // this thread's first gradient entry of a group: frame my_f, pdf my_d; the
+    // LDS addresses of the first kPre of that pdf's row sums stay in registers
+    const int my_f = tid / P, my_d = tid - my_f * P;
+    int my_r0 = 0, my_r1 = 0;
+    uint32_t my_at[kPre];
+    if (my_f < F) {
+        my_r0 = pdf_first[my_d];
+        my_r1 = pdf_first[my_d + 1];
+    }
+#pragma unroll
+    for (int k = 0; k < kPre; ++k)
+        my_at[k] = my_r0 + k < my_r1
+                       ? kRowSum + (uint32_t)(my_f * occ_rows + pdf_rows[my_r0 + k]) * 4u
+                       : 0u;
 
     const int t_begin = blockIdx.x * groups_per_wg * F + 1;
     const int t_end = min(t_begin + groups_per_wg * F - 1, p.T);
@@ -855,7 +876,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             invb[f] = ok ? 1.f / nb : 0.f;
             cb[f] = eps * sb * invb[f];
         }
-        __syncthreads();  // the previous group's gathers and bin reads are done
+        __syncthreads();  // the previous group's gathers and row-sum reads are done
         // staging: two rows per thread and side in flight, all loads (alpha and beta)
         // issued before any is used
         const int rows_max = max(rows_f, rows_b);
@@ -887,7 +908,6 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 }
             }
         }
-        for (int d = tid; d < F * Ppad; d += nthreads) lds_st(kBins + (uint32_t)d * 4u, 0.f);
         __syncthreads();
 
         auto one_slot = [&](const uint2 r, float* acc) {
@@ -900,11 +920,10 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 acc[f] = fmaf(w * bt, a, acc[f]);
             }
         };
-        // emission values of this thread's gradient entries, in flight during the gathers
-        float ev[F];
-#pragma unroll
-        for (int f = 0; f < F; ++f)
-            ev[f] = (tid < P && t0 + f <= T) ? p.emis[((size_t)b * p.T + (t0 + f - 1)) * P + tid] : 0.f;
+        // emission value of this thread's gradient entry, in flight during the gathers
+        const size_t group_at = ((size_t)b * p.T + (t0 - 1)) * P;
+        const bool my_live = my_f < F && t0 + my_f <= T;
+        const float my_e = my_live ? p.emis[group_at + tid] : 0.f;
 
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
@@ -932,42 +951,39 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
 #pragma unroll
                 for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
             }
-            const int pd = row_pdf4[sl * 64 + lane];
-            if (pd >= 0) {
 #pragma unroll
-                for (int f = 0; f < F; ++f)
-                    __hip_atomic_fetch_add(
-                        reinterpret_cast<lds_float_t*>(static_cast<uintptr_t>(
-                            kBins + (uint32_t)(f * Ppad) * 4u + (uint32_t)pd)),
-                        acc[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
+            for (int f = 0; f < F; ++f)
+                lds_st(kRowSum + (uint32_t)(f * occ_rows + sl * 64 + lane) * 4u, acc[f]);
         }
         __syncthreads();
-#pragma unroll
-        for (int f = 0; f < F; ++f) {
+        for (int idx = tid; idx < F * P; idx += nthreads) {
+            const int f = idx / P, d = idx - f * P;
             const int t = t0 + f;
             if (t > p.T) break;
-            const size_t at = ((size_t)b * p.T + (t - 1)) * P;
-            float* g = p.grad + at;
+            float* g = p.grad + group_at + idx;
             if (t > T) {
-                if (!p.accumulate)
-                    for (int d = tid; d < P; d += nthreads) g[d] = 0.f;
+                if (!p.accumulate) *g = 0.f;
                 continue;
             }
-            const float scale = p.grad_scale * cf[f];
-            const float* e = p.emis + at;
-            if (tid < P) {
-                const float v = cf[f] == 0.f
-                                    ? 0.f
-                                    : scale * ev[f] * lds_ld(kBins + (uint32_t)(f * Ppad + tid) * 4u);
-                g[tid] = p.accumulate ? g[tid] + v : v;
+            float sum = 0.f, e;
+            int r, r1;
+            if (idx == tid) {
+#pragma unroll
+                for (int k = 0; k < kPre; ++k)
+                    if (my_r0 + k < my_r1) sum += lds_ld(my_at[k]);
+                r = my_r0 + kPre;
+                r1 = my_r1;
+                e = my_e;
+            } else {
+                r = pdf_first[d];
+                r1 = pdf_first[d + 1];
+                e = p.emis[group_at + idx];
             }
-            for (int d = tid + nthreads; d < P; d += nthreads) {
-                const float v = cf[f] == 0.f
-                                    ? 0.f
-                                    : scale * e[d] * lds_ld(kBins + (uint32_t)(f * Ppad + d) * 4u);
-                g[d] = p.accumulate ? g[d] + v : v;
-            }
+            for (; r < r1; ++r)
+                sum += lds_ld(kRowSum + (uint32_t)(f * occ_rows + pdf_rows[r]) * 4u);
+            const float c = cfac[t];
+            const float v = c == 0.f ? 0.f : p.grad_scale * c * e * sum;
+            *g = p.accumulate ? *g + v : v;
         }
     }
 }
@@ -1022,11 +1038,21 @@ int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
 
 hipError_t configure_kernels()
 {
-
+    // Kernels that address LDS by absolute offsets take the dynamic allocation to
+    // start at 0: a static allocation (say a private array the compiler moved to
+    // LDS) would sit there instead and be overwritten.
+    auto no_static_lds = [](const void* f) {
+        hipFuncAttributes attr;
+        const hipError_t e = hipFuncGetAttributes(&attr, f);
+        if (e != hipSuccess) return e;
+        return attr.sharedSizeBytes == 0 ? hipSuccess : hipErrorInvalidConfiguration;
+    };
     for (const RecVariant& v : kRecVariants) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        if (v.nslot > 0 && (e = no_static_lds(reinterpret_cast<const void*>(v.fn))) != hipSuccess)
+            return e;
     }
     const void* fns[] = {reinterpret_cast<const void*>(k_occ<float>),
                          reinterpret_cast<const void*>(k_occ<double>),
@@ -1037,6 +1063,7 @@ hipError_t configure_kernels()
         hipError_t e =
             hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        if (f != fns[0] && f != fns[1] && (e = no_static_lds(f)) != hipSuccess) return e;
     }
     return hipSuccess;
 }
@@ -1048,26 +1075,23 @@ size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep)
     return (2 * (size_t)lds_rows + 64) * (wide ? 8 : 4) + 2 * ypad * 4;
 }
 
-size_t occ_lds_bytes(int rows_a, int rows_b, int P, bool wide)
+size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide)
 {
-    const size_t Ppad = (size_t)((P + 63) & ~63);
-    return ((size_t)rows_a + rows_b + 2 * Ppad) * (wide ? 8 : 4);
+    return ((size_t)rows_a + rows_b + occ_rows) * (wide ? 8 : 4);
 }
 
-// Frames per record of the plane-layout occupancy kernel for this many rows
-// (0: rows or pdfs do not fit its fixed LDS map).
-int occ_plane_frames(int rows, int P)
+// Frames per record of the plane-layout occupancy kernel for this many state
+// rows and OCC rows (0: they do not fit its LDS map).
+int occ_plane_frames(int rows, int occ_rows)
 {
-    const size_t Ppad = (size_t)((P + 63) & ~63);
     for (int f : {4, 2, 1})
-        if (rows * 4 <= 32768 / f && 65536 + (size_t)f * Ppad * 4 <= 160 * 1024) return f;
+        if (rows * 4 <= 32768 / f && occ_plane_lds_bytes(occ_rows, f) <= 160 * 1024) return f;
     return 0;
 }
 
-size_t occ_plane_lds_bytes(int P, int frames)
+size_t occ_plane_lds_bytes(int occ_rows, int frames)
 {
-    const size_t Ppad = (size_t)((P + 63) & ~63);
-    return 65536 + (size_t)frames * Ppad * 4;
+    return 65536 + (size_t)frames * occ_rows * 4;
 }
 
 template <typename Real>
@@ -1106,12 +1130,12 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
             void (*fn)(FbParams, int) = F == 4   ? k_occ_planes<4, 8192>
                                         : F == 2 ? k_occ_planes<2, 16384>
                                                  : k_occ_planes<1, 32768>;
-            hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads), occ_plane_lds_bytes(p.P, F),
+            hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads), occ_plane_lds_bytes(p.lds_rows_occ, F),
                                stream, p, shape.occ_groups);
         } else {
             dim3 grid((p.T + shape.occ_frames - 1) / shape.occ_frames, p.B);
             hipLaunchKernelGGL(k_occ<Real>, grid, dim3(shape.occ_threads),
-                               occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b, p.P, wide),
+                               occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b, p.lds_rows_occ, wide),
                                stream, p, shape.occ_frames);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <numeric>
+#include <queue>
 
 namespace lfmmi {
 namespace {
@@ -634,44 +635,90 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     {
         std::vector<int64_t> count(num_pdfs, 0);
         for (int64_t a = 0; a < A; ++a) ++count[g.pdf[a]];
-        // piece length: the one whose slices deal out most evenly over the waves
-        // (a wave's load is about slices-per-wave * piece)
+        // Every row's sum takes an LDS word per frame in flight, so rows are kept
+        // few: k slices per wave, i.e. waves * 64 * k rows, handed to the pdfs one
+        // at a time, always to the pdf whose pieces are longest at that moment. A
+        // pdf's pieces then differ by at most one arc, and sorting rows by length
+        // leaves little padding. k: the smallest whose fullest wave is within 3 %
+        // of the best over all k tried.
         const int waves_o = std::max(1, occ_waves);
-        int64_t piece = 4, best_load = -1;
-        for (int64_t len = 4; len <= 64; ++len) {
-            int64_t rows = 0;
-            for (int32_t d = 0; d < num_pdfs; ++d) rows += (count[d] + len - 1) / len;
-            const int64_t slices = (rows + kLanes - 1) / kLanes;
-            const int64_t load = (slices + waves_o - 1) / waves_o * len;
-            if (best_load < 0 || load <= best_load) { best_load = load; piece = len; }
+        int64_t nonempty = 0;
+        for (int32_t d = 0; d < num_pdfs; ++d) nonempty += count[d] > 0;
+        auto allot = [&](int64_t target, std::vector<int64_t>* pieces) {
+            pieces->assign(num_pdfs, 0);
+            using Item = std::pair<double, int32_t>;  // (arcs per piece, pdf)
+            std::priority_queue<Item> longest;
+            int64_t left = target;
+            for (int32_t d = 0; d < num_pdfs; ++d)
+                if (count[d] > 0) {
+                    (*pieces)[d] = 1;
+                    --left;
+                    longest.push(Item((double)count[d], d));
+                }
+            while (left > 0 && !longest.empty()) {
+                const int32_t d = longest.top().second;
+                longest.pop();
+                if ((*pieces)[d] >= count[d]) continue;  // one arc per piece already
+                ++(*pieces)[d];
+                --left;
+                longest.push(Item((double)count[d] / (double)(*pieces)[d], d));
+            }
+        };
+        auto lengths_of = [&](const std::vector<int64_t>& pieces, std::vector<int32_t>* len,
+                              std::vector<int32_t>* pdf_of) {
+            len->clear();
+            pdf_of->clear();
+            for (int32_t d = 0; d < num_pdfs; ++d)
+                for (int64_t i = 0; i < pieces[d]; ++i) {
+                    const int64_t base = count[d] / pieces[d], extra = count[d] % pieces[d];
+                    len->push_back((int32_t)(base + (i < extra ? 1 : 0)));
+                    pdf_of->push_back(d);
+                }
+        };
+        std::vector<int64_t> pieces, try_pieces;
+        std::vector<int32_t> len, pdf_of;
+        {
+            const int64_t per_k = (int64_t)waves_o * kLanes;
+            const int64_t k_min = std::max<int64_t>(1, (nonempty + per_k - 1) / per_k);
+            std::vector<std::pair<int64_t, int32_t>> tried;  // (k, fullest wave)
+            int32_t best = -1;
+            for (int64_t k = k_min; k < k_min + 12; ++k) {
+                allot(k * per_k, &try_pieces);
+                lengths_of(try_pieces, &len, &pdf_of);
+                const Arrangement t = arrange(len, occ_waves, 0);
+                tried.emplace_back(k, t.max_wave_slots);
+                if (best < 0 || t.max_wave_slots < best) best = t.max_wave_slots;
+                if (k * per_k >= A) break;  // one arc per piece
+            }
+            int64_t k_pick = k_min;
+            for (const auto& t : tried)
+                if ((double)t.second <= 1.03 * (double)best) { k_pick = t.first; break; }
+            allot(k_pick * per_k, &pieces);
+            lengths_of(pieces, &len, &pdf_of);
         }
         std::vector<int64_t> first_row(num_pdfs + 1, 0);
-        for (int32_t d = 0; d < num_pdfs; ++d)
-            first_row[d + 1] = first_row[d] + (count[d] + piece - 1) / piece;
+        for (int32_t d = 0; d < num_pdfs; ++d) first_row[d + 1] = first_row[d] + pieces[d];
         const int64_t R = first_row[num_pdfs];
         if (R > (int64_t)1 << 28) return "too many occupancy rows";
-        std::vector<int32_t> len((size_t)R, 0), pdf_of((size_t)R, 0);
-        for (int32_t d = 0; d < num_pdfs; ++d)
-            for (int64_t r = first_row[d], left = count[d]; r < first_row[d + 1]; ++r) {
-                len[r] = (int32_t)std::min<int64_t>(piece, left);
-                left -= len[r];
-                pdf_of[r] = d;
-            }
         const Arrangement ao = arrange(len, occ_waves, 0);
         start_ordering(ao, (int32_t)R, &out->ord[2]);
-        out->row_pdf4.assign((size_t)ao.num_slices * kLanes, -1);
+        out->pdf_first.assign((size_t)num_pdfs + 1, 0);
+        out->pdf_rows.assign((size_t)ao.num_slices * kLanes, 0);
+        for (int32_t d = 0; d <= num_pdfs; ++d) out->pdf_first[d] = (int32_t)first_row[d];
         for (int64_t r = 0; r < R; ++r) {
             out->ord[2].row_id[ao.pos[r]] = pdf_of[r];
-            out->row_pdf4[ao.pos[r]] = pdf_of[r] * 4;
+            out->pdf_rows[r] = ao.pos[r];
         }
         std::vector<int64_t> seen(num_pdfs, 0);
         std::vector<int32_t> prow(A), nth(A), wo(ao.num_slices);
         std::vector<int16_t> bx(A), by(A);
         for (int64_t a = 0; a < A; ++a) {
             const int32_t d = g.pdf[a];
-            const int64_t r = first_row[d] + seen[d] / piece;
-            nth[a] = (int32_t)(seen[d] % piece);
-            ++seen[d];
+            // the first `extra` pieces of a pdf hold base + 1 arcs, the others base
+            const int64_t base = count[d] / pieces[d], extra = count[d] % pieces[d];
+            const int64_t n = seen[d]++, head = extra * (base + 1);
+            const int64_t r = first_row[d] + (n < head ? n / (base + 1) : extra + (n - head) / base);
+            nth[a] = (int32_t)(n < head ? n % (base + 1) : (n - head) % base);
             prow[a] = ao.pos[r];
             bx[a] = (int16_t)(af.pos[g.src[a]] % kBanks);
             by[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);

@@ -52,7 +52,10 @@ struct PackedGraph {
     //   init: start vector (FWD pi, BWD final)      fin: closing dot (FWD final, BWD pi)
     //   a:    leak dot weights (FWD 1, BWD pi)      b:   leak target (FWD pi, BWD 1)
     std::vector<float> vinit[2], va[2], vb[2], vfin[2];
-    std::vector<int32_t> row_pdf4;  // OCC: pdf * 4 of each row, -1 = padding row
+    // OCC: the rows of pdf d are pdf_rows[pdf_first[d] .. pdf_first[d + 1]), each
+    // a position slice * 64 + lane; their sums are added in this order
+    std::vector<int32_t> pdf_first;  // [num_pdfs + 1]
+    std::vector<int32_t> pdf_rows;   // [OCC num_slices * 64], the tail unused
 };
 
 struct ArcList {
