@@ -456,7 +456,8 @@ struct RecRegs {
                 acc2 = 0.f;
                 row += 64;
                 left &= left - 1;
-                next_close = left ? __builtin_ctzll(left) : 64;
+                if (!left) break;  // the wave's last slice: only padding slots follow
+                next_close = __builtin_ctzll(left);
             }
         }
         n = wave_sum_uniform(n);
