@@ -161,35 +161,59 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         if (forced > 0) waves = std::min(forced, kMaxWaves);
         // Pack for `waves` waves; when the arcs of a wave then fit no register-resident
         // variant of the recursion kernel, try half the waves (twice the registers per
-        // lane) before settling for streamed arcs.
-        for (int attempt = 0; attempt < 2; ++attempt) {
-            h->rec_waves = waves;
-            // the occupancy pass is throughput work: at most 8 waves, so that a lane
-            // has 256 registers for its arcs
-            h->occ_waves = std::min(waves, env_int("LFMMI_OCC_WAVES", 8));
+        // lane) before settling for streamed arcs. Slices are padded to even widths
+        // for the register-resident kernel only: `registers_possible` rules it out
+        // beforehand where it can, else streamed arcs are packed once more without.
+        auto registers_possible = [&](int wv) {
+            if (h->wide) return false;
+            if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return false;  // staging limits
+            for (int32_t g = 0; g < n; ++g) {
+                if (state_off[g + 1] - state_off[g] > 8192) return false;  // fixed LDS map
+                if ((double)(arc_off[g + 1] - arc_off[g]) / (64.0 * wv) > 48.0) return false;
+            }
+            return true;
+        };
+        auto pack_with = [&](int wv, bool even, int* max_slots) -> lfmmi_status {
+            tune.even_slices = even;
+            h->rec_waves = wv;
+            // the occupancy pass is throughput work: at most 8 waves
+            h->occ_waves = std::min(wv, env_int("LFMMI_OCC_WAVES", 8));
             h->packed.assign(n, PackedGraph());
             h->max_rows_f = h->max_rows_b = h->max_rows_occ = 0;
-            int max_slots = 0;
+            *max_slots = 0;
             for (int32_t g = 0; g < n; ++g) {
                 bool bad = false;
                 std::string err = pack_graph(arcs_of(g), num_pdfs, h->rec_waves, h->occ_waves,
                                              h->has_wb, tune, &h->packed[g], &bad);
-                if (!err.empty()) {
-                    delete h;
+                if (!err.empty())
                     return fail(bad ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
                                 (n > 1 ? "graph " + std::to_string(g) + ": " : std::string()) + err);
-                }
                 h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
                 h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
                 h->max_rows_occ = std::max(h->max_rows_occ, h->packed[g].ord[2].num_slices * kLanes);
                 for (int o = 0; o < 2; ++o)
-                    max_slots = std::max(max_slots, h->packed[g].ord[o].max_wave_slots);
+                    *max_slots = std::max(*max_slots, h->packed[g].ord[o].max_wave_slots);
             }
-            h->rec_nslot = rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
-            if (h->rec_nslot > 0 || h->wide || forced > 0 || waves <= 8 || attempt == 1) break;
-            const int half = waves / 2;
-            if (rec_register_slots(h->wide, h->has_wb, 2 * max_slots, half * kLanes) == 0) break;
-            waves = half;
+            return LFMMI_OK;
+        };
+        {
+            int max_slots = 0;
+            bool even = registers_possible(waves);
+            lfmmi_status st = pack_with(waves, even, &max_slots);
+            h->rec_nslot = even ? rec_register_slots(false, h->has_wb, max_slots, waves * kLanes) : 0;
+            if (st == LFMMI_OK && h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
+                registers_possible(waves / 2) &&
+                rec_register_slots(false, h->has_wb, 2 * max_slots, waves / 2 * kLanes) != 0) {
+                waves /= 2;
+                even = true;
+                st = pack_with(waves, true, &max_slots);
+                h->rec_nslot = rec_register_slots(false, h->has_wb, max_slots, waves * kLanes);
+            }
+            if (st == LFMMI_OK && h->rec_nslot == 0 && even) st = pack_with(waves, false, &max_slots);
+            if (st != LFMMI_OK) {
+                delete h;
+                return st;
+            }
         }
         const int rows = std::max(h->max_rows_f, h->max_rows_b);
         if (rec_lds_bytes(rows, num_pdfs, h->wide, false) > kLdsBytes ||
@@ -198,10 +222,6 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             return fail(LFMMI_ERR_UNSUPPORTED,
                         "states and pdfs do not fit the 160 KB of LDS of one compute unit");
         }
-        // the register-resident kernel has a fixed LDS map: 32 KB per buffer
-        if (h->rec_nslot > 0 &&
-            (rows > 8192 || (h->rec_yrep ? (size_t)num_pdfs * 128 : (size_t)num_pdfs * 4) > 32764))
-            h->rec_nslot = 0;
     } catch (const std::bad_alloc&) {
         delete h;
         return fail(LFMMI_ERR_OOM, "host allocation failed");

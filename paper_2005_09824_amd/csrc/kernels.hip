@@ -17,6 +17,8 @@
 // added back into log Z.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace lfmmi {
 namespace {
 
@@ -353,56 +355,79 @@ __device__ __forceinline__ void lds_st(uint32_t addr, float v)
     *reinterpret_cast<lds_float_t*>(static_cast<uintptr_t>(addr)) = v;
 }
 
+// Emission staging passes of the variant for workgroups of up to NT threads.
+__host__ __device__ constexpr int stage_passes(bool yrep, int nt)
+{
+    return yrep ? (nt >= 1024 ? 2 : (nt >= 768 ? 3 : 4)) : (nt >= 1024 ? 3 : (nt >= 768 ? 4 : 6));
+}
+
 template <bool YREP, bool HAS_WB, int NSLOT, int NT>
 struct RecRegs {
-    static constexpr int kYRegs = NT >= 1024 ? 3 : (NT >= 768 ? 4 : 6);
+    // Emission staging. Replicated rows (YREP): a thread writes four of the 32
+    // copies of one value with one 16-byte store, kYPass passes of NT threads
+    // cover 8 * P <= kYPass * NT quads. Plain rows: one value per thread and pass.
+    static constexpr int kYPass = stage_passes(YREP, NT);
     static constexpr int kPrefetch = NT >= 1024 ? 4 : 6;
+    static constexpr int kTailSlots = NSLOT / 2;
 
     uint32_t xa[NSLOT];  // byte address of the state value inside X0
     uint32_t ya[NSLOT];  // LDS byte address of the emission value in Y0 (absolute)
     float wr[NSLOT];     // arc weight; closing slots: the row's leak-dot weight
     float wbr[HAS_WB ? NSLOT : 1];
-    float yreg[kYRegs];
+    float yreg[kYPass];
+    uint32_t ysrc[kYPass];  // byte offset of this thread's value inside an emission row
+    uint32_t ydst[kYPass];  // byte offset inside a Y buffer it is stored to
+    int ypasses;            // passes that hold any of the row
+
+    // per-step pointers, moved by one frame after every step
+    const float* e2;  // emission row loaded during this step (used two steps on)
+    float* trow;      // trellis row written by this step
+    float* sN;        // where the scalars of the previous step go
+    float* sS;
+    ptrdiff_t estep, tstep, sstep;
+
+    __device__ __forceinline__ void load_y()
+    {
+        const char* base = reinterpret_cast<const char*>(e2);
+#pragma unroll
+        for (int i = 0; i < kYPass; ++i)
+            if (i == 0 || i < ypasses) yreg[i] = *reinterpret_cast<const float*>(base + ysrc[i]);
+    }
+
+    __device__ __forceinline__ void store_y(const uint32_t ybuf)
+    {
+#pragma unroll
+        for (int i = 0; i < kYPass; ++i)
+            if (i == 0 || i < ypasses) {
+                if constexpr (YREP) {  // four adjacent words: one 16-byte store
+                    const float y = yreg[i];
+                    const uint32_t at = ybuf + ydst[i];
+                    lds_st(at, y);
+                    lds_st(at + 4, y);
+                    lds_st(at + 8, y);
+                    lds_st(at + 12, y);
+                } else {
+                    lds_st(ybuf + ydst[i], yreg[i]);
+                }
+            }
+    }
 
     template <int PAR>
-    __device__ __forceinline__ void step(const FbParams& p, unsigned char* lds, const int k,
-                                         const int T, const int dir, const int tid, const int lane,
-                                         const int wave, const int nthreads, const int ylen,
-                                         const size_t erow0, const float eps, const float bconst,
-                                         const uint64_t mask, const int row0, float* trel,
-                                         const int rows, float* scalN, float* scalS)
+    __device__ __forceinline__ void step(const int k, const int T, const int tid, const int lane,
+                                         const int wave, const float eps, const float bconst,
+                                         const uint64_t mask, const uint32_t row4_first,
+                                         const int nsl)
     {
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
         // Y addresses in ya[] are absolute addresses inside Y0; Y1 is 32 KB further
         constexpr uint32_t yc = PAR ? 0u : (kRegY1 - kRegY0), yn = PAR ? kRegY1 : kRegY0;
         constexpr uint32_t pc = kRegPart + (PAR ? 0u : 128u), pn = kRegPart + (PAR ? 128u : 0u);
-        const int P = p.P;
 
         // emission row of step k + 1 (loaded one step ago) into the other Y buffer,
-        // then the loads for step k + 2
-        if (k < T) {
-#pragma unroll
-            for (int i = 0; i < kYRegs; ++i) {
-                const int q = tid + i * nthreads;
-                if (q < ylen) lds_st(yn + q * 4, yreg[i]);
-            }
-            if (ylen > kYRegs * nthreads) {
-                const int fr = dir == 0 ? k : T - k - 1;
-                const float* e = p.emis + (erow0 + fr) * P;
-                for (int q = tid + kYRegs * nthreads; q < ylen; q += nthreads)
-                    lds_st(yn + q * 4, e[YREP ? q >> 5 : q]);
-            }
-        }
-        if (k + 1 < T) {
-            const int fr = dir == 0 ? k + 1 : T - k - 2;
-            const float* e = p.emis + (erow0 + fr) * P;
-#pragma unroll
-            for (int i = 0; i < kYRegs; ++i) {
-                const int q = tid + i * nthreads;
-                if (q < ylen) yreg[i] = e[YREP ? q >> 5 : q];
-            }
-        }
+        // then the loads for step k + 2; past the end both repeat the last row
+        store_y(yn);
+        load_y();
 
         // scalars of step k - 1: lanes 0-15 fetch the n partials, 16-31 the s partials
         float pv = lds_ld(pc + (lane & 31) * 4);
@@ -417,12 +442,9 @@ struct RecRegs {
         const float c = eps * Sd * inv;
         const float cb = HAS_WB ? c : c * bconst;
         if (tid == 0) {
-            const int tp = dir == 0 ? k - 1 : T - k + 1;
-            scalN[tp] = N;
-            scalS[tp] = Sd;
+            *sN = N;
+            *sS = Sd;
         }
-        const int ti = dir == 0 ? k : T - k;
-        float* tr = trel + (size_t)ti * rows;
 
         float xv[kPrefetch], ev[kPrefetch];
 #pragma unroll
@@ -433,9 +455,18 @@ struct RecRegs {
         float acc1 = 0.f, acc2 = 0.f, n = 0.f, s = 0.f;
         uint64_t left = mask;
         int next_close = left ? __builtin_ctzll(left) : 64;
-        int row = row0 + lane;
+        uint32_t row4 = row4_first;  // byte offset of this lane's row in a state vector
+        char* const tr = reinterpret_cast<char*>(trow);
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
+            // a wave with fewer slots than the variant holds leaves at its last one;
+            // slices are an even number of slots wide, so that this, and the test
+            // for the end of a slice, are needed at every other slot only
+            if ((i & 1) == 0 && i >= NSLOT - kTailSlots) {
+                int count = nsl;
+                asm volatile("" : "+s"(count));  // compare here, in a scalar register
+                if (i >= count) break;
+            }
             const float x = xv[i % kPrefetch];
             const float e = ev[i % kPrefetch];
             if (i + kPrefetch < NSLOT) {
@@ -446,18 +477,17 @@ struct RecRegs {
             const float t = wr[i] * e;
             acc1 = fmaf(t, x, acc1);
             acc2 = HAS_WB ? fmaf(wbr[i], e, acc2) : acc2 + t;
-            if (i == next_close) {  // wave-uniform: the slice ends here
+            if ((i & 1) == 1 && __builtin_expect(i == next_close, 0)) {  // wave-uniform: a slice ends
                 const float v = fmaf(inv, acc1, cb * acc2);
-                lds_st(xn + row * 4, v);
-                tr[row] = v;
+                lds_st(xn + row4, v);
+                *reinterpret_cast<float*>(tr + row4) = v;
                 n += v;
                 s = fmaf(wr[i], v, s);
                 acc1 = 0.f;
                 acc2 = 0.f;
-                row += 64;
+                row4 += 256;
                 left &= left - 1;
-                if (!left) break;  // the wave's last slice: only padding slots follow
-                next_close = __builtin_ctzll(left);
+                next_close = left ? __builtin_ctzll(left) : 64;
             }
         }
         n = wave_sum_uniform(n);
@@ -466,6 +496,10 @@ struct RecRegs {
             lds_st(pn + wave * 4, n);
             lds_st(pn + 64 + wave * 4, s);
         }
+        if (k + 2 < T) e2 += estep;
+        trow += tstep;
+        sN += sstep;
+        sS += sstep;
         __syncthreads();
     }
 
@@ -479,7 +513,6 @@ struct RecRegs {
         const int T = sd.T;
         const int P = p.P;
         const int rows = od.num_slices * 64;
-        const int ylen = YREP ? P * 32 : P;
         float* trel = static_cast<float*>(dir == 0 ? p.alpha : p.beta) +
                       (dir == 0 ? sd.alpha_at : sd.beta_at);
         float* scalN = static_cast<float*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
@@ -489,7 +522,7 @@ struct RecRegs {
         const int32_t* so = p.g.slice_off + od.slice_off_at;
         const float eps = p.leak;
         const float bconst = od.b_const;
-        const size_t erow0 = (size_t)b * p.T;
+        const float* erows = p.emis + (size_t)b * p.T * P;  // this sequence's emission rows
 
         int s0 = 0, s1 = 0;
         uint64_t mask = 0;
@@ -515,6 +548,19 @@ struct RecRegs {
             // opaque from here on: the three values stay in three registers for the
             // whole time loop instead of being re-derived from the record each frame
             asm volatile("" : "+v"(xa[i]), "+v"(ya[i]), "+v"(wr[i]));
+        }
+        // emission staging: which value of a row this thread fetches in pass i, and
+        // where in a Y buffer it goes
+        {
+            const int units = YREP ? P * 8 : P;  // 16-byte quads, or single values
+            ypasses = (units + nthreads - 1) / nthreads;
+#pragma unroll
+            for (int i = 0; i < kYPass; ++i) {
+                // threads past the row repeat the work of an earlier thread
+                const int q = (tid + i * nthreads) % units;
+                ysrc[i] = (uint32_t)(YREP ? q >> 3 : q) * 4u;
+                ydst[i] = (uint32_t)q * (YREP ? 16u : 4u);
+            }
         }
 
         // zero words of the Y buffers, partial slots
@@ -543,35 +589,36 @@ struct RecRegs {
                 lds_st(kRegPart + wave * 4, n);
                 lds_st(kRegPart + 64 + wave * 4, s);
             }
+            // rows of steps 1 (into Y0 now) and 2 (into registers); frame of step k:
+            // FWD k - 1, BWD T - k, kept inside the sequence when T is short
+            auto frame_of = [&](int k) {
+                const int fr = dir == 0 ? k - 1 : T - k;
+                return max(0, min(fr, T - 1));
+            };
             if (T > 0) {
-                const int fr = dir == 0 ? 0 : T - 1;
-                const float* e = p.emis + (erow0 + fr) * P;
-                for (int q = tid; q < ylen; q += nthreads)
-                    lds_st(kRegY0 + q * 4, e[YREP ? q >> 5 : q]);
-            }
-            if (T > 1) {
-                const int fr = dir == 0 ? 1 : T - 2;
-                const float* e = p.emis + (erow0 + fr) * P;
-#pragma unroll
-                for (int i = 0; i < kYRegs; ++i) {
-                    const int q = tid + i * nthreads;
-                    yreg[i] = q < ylen ? e[YREP ? q >> 5 : q] : 0.f;
-                }
+                e2 = erows + (size_t)frame_of(1) * P;
+                load_y();
+                store_y(kRegY0);
+                e2 = erows + (size_t)frame_of(2) * P;
+                load_y();
+                e2 = erows + (size_t)frame_of(3) * P;
             }
             __syncthreads();
         }
+        estep = dir == 0 ? (ptrdiff_t)P : -(ptrdiff_t)P;
+        tstep = dir == 0 ? (ptrdiff_t)rows : -(ptrdiff_t)rows;
+        sstep = dir == 0 ? 1 : -1;
+        trow = trel + (size_t)(dir == 0 ? 1 : T - 1) * rows;  // step 1 writes row 1 / T - 1
+        sN = scalN + (dir == 0 ? 0 : T);                      // and the scalars of step 0
+        sS = scalS + (dir == 0 ? 0 : T);
 
-        const int row0 = s0 * 64;
+        const uint32_t row4_first = (uint32_t)(s0 * 64 + lane) * 4u;
         int k = 1;
         for (; k + 1 <= T; k += 2) {
-            step<1>(p, lds, k, T, dir, tid, lane, wave, nthreads, ylen, erow0, eps, bconst, mask,
-                    row0, trel, rows, scalN, scalS);
-            step<0>(p, lds, k + 1, T, dir, tid, lane, wave, nthreads, ylen, erow0, eps, bconst,
-                    mask, row0, trel, rows, scalN, scalS);
+            step<1>(k, T, tid, lane, wave, eps, bconst, mask, row4_first, nsl);
+            step<0>(k + 1, T, tid, lane, wave, eps, bconst, mask, row4_first, nsl);
         }
-        if (k <= T)
-            step<1>(p, lds, k, T, dir, tid, lane, wave, nthreads, ylen, erow0, eps, bconst, mask,
-                    row0, trel, rows, scalN, scalS);
+        if (k <= T) step<1>(k, T, tid, lane, wave, eps, bconst, mask, row4_first, nsl);
 
         // ---- last scalars and the closing dot product
         {
@@ -1005,7 +1052,8 @@ const RecVariant kRecVariants[] = {
     LFMMI_REC(float, 0, 0, 0, 1024), LFMMI_REC(float, 0, 0, 1, 1024),
     LFMMI_REC(double, 1, 0, 0, 1024), LFMMI_REC(double, 1, 0, 1, 1024),
     // register-resident arcs, 16 waves (128 VGPRs per lane)
-    LFMMI_REC(float, 0, 16, 0, 1024), LFMMI_REC(float, 0, 24, 0, 1024),
+    LFMMI_REC(float, 0, 16, 0, 1024), LFMMI_REC(float, 0, 20, 0, 1024),
+    LFMMI_REC(float, 0, 24, 0, 1024), LFMMI_REC(float, 0, 26, 0, 1024),
     LFMMI_REC(float, 0, 28, 0, 1024),
     LFMMI_REC(float, 0, 16, 1, 1024),
     // register-resident arcs, 12 waves (168 VGPRs per lane)
@@ -1113,7 +1161,17 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     LFMMI_EV(1)
-    hipLaunchKernelGGL(rv->fn, dim3(2 * p.B), dim3(shape.rec_threads),
+    int rec_threads = shape.rec_threads;
+    if (shape.rec_nslot > 0) {
+        // enough threads to stage one emission row in the variant's passes; waves
+        // beyond the graph's own hold no arcs
+        const int units = shape.rec_yrep ? p.P * 8 : p.P;
+        const int passes = stage_passes(shape.rec_yrep != 0, rv->max_threads);
+        const int need = ((units + passes - 1) / passes + 63) / 64 * 64;
+        rec_threads = std::max(rec_threads, need);
+        if (rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
+    }
+    hipLaunchKernelGGL(rv->fn, dim3(2 * p.B), dim3(rec_threads),
                        shape.rec_nslot > 0
                            ? reg_lds_bytes()
                            : rec_lds_bytes(p.lds_rows, p.P, wide, shape.rec_yrep != 0),

@@ -20,7 +20,8 @@ struct Arrangement {
     int32_t num_slices = 0, num_waves = 0, max_wave_slots = 0;
 };
 
-Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots)
+Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
+                    bool even_widths = false)
 {
     Arrangement ar;
     const int32_t R = (int32_t)len.size();
@@ -33,6 +34,10 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots)
     std::vector<int32_t> sorted_width(ar.num_slices);
     for (int32_t s = 0; s < ar.num_slices; ++s)
         sorted_width[s] = len[idx[(size_t)s * kLanes]] + extra_slots;
+    // even_widths: one more padding slot where needed (the register-resident
+    // recursion kernel looks for the end of a slice at every other slot only)
+    if (even_widths)
+        for (int32_t& wd : sorted_width) wd += wd & 1;
 
     std::vector<std::vector<int32_t>> owned(ar.num_waves);
     std::vector<int64_t> load(ar.num_waves, 0);
@@ -532,8 +537,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     // ---- FWD (rows = to-states) and BWD (rows = from-states) arrangements
     std::vector<int32_t> indeg(S, 0), outdeg(S, 0);
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
-    Arrangement af = arrange(indeg, rec_waves, 1);
-    Arrangement ab = arrange(outdeg, rec_waves, 1);
+    Arrangement af = arrange(indeg, rec_waves, 1, tune.even_slices);
+    Arrangement ab = arrange(outdeg, rec_waves, 1, tune.even_slices);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {

@@ -79,6 +79,7 @@ struct PackTuning {
     bool balance_banks = true;        // re-deal lanes inside half-slices (state -> bank)
     bool order_slots = true;          // order each row's arcs over its slots
     bool emission_conflicts = true;   // the emission gather can conflict (row not replicated)
+    bool even_slices = true;          // FWD / BWD slices an even number of slots wide
 };
 
 // per_arc_leak: fill the per-arc leak factors (required when init_prob is not

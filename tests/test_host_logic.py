@@ -136,7 +136,7 @@ def test_graph_with_no_arcs_and_isolated_states():
          "pdf": np.zeros(0, np.int32), "logw": np.zeros(0, np.float32),
          "init_prob": np.ones(3, np.float32), "final_prob": np.ones(3, np.float32)}
     h = binding.lfmmi_graph_pack(g)
-    assert binding.lfmmi_graph_ordering_info(h, 0, 0)["total_slots"] == 1  # closing slot only
+    assert binding.lfmmi_graph_ordering_info(h, 0, 0)["total_slots"] == 2  # one padding slot, then the closing slot
     assert binding.lfmmi_graph_ordering_info(h, 0, 2)["total_slots"] == 0  # no rows at all
     h.close()
 
