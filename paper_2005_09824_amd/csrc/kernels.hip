@@ -329,6 +329,20 @@ __device__ __forceinline__ float wave_sum_uniform(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Wave sums of a and b at once: a 32-lane swap puts a[l] + a[l + 32] in the lower
+// half-wave and b[l] + b[l + 32] in the upper one, five DPP steps finish both.
+__device__ __forceinline__ float2 half_wave_sums(float a, float b)
+{
+    // lanes 0-31 of .x keep a, lanes 32-63 of .x take b's lanes 0-31; .y the rest
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b),
+                                                     false, false);
+    float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    v = row16_allsum(v);
+    v = dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    return make_float2(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31)),
+                       __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63)));
+}
+
 // ---------------------------------------------------------------------------
 // The recursion with the wave's arc records in registers (fp32 graphs whose
 // waves own at most NSLOT slots). Fixed LDS map, so that the buffer of the
@@ -368,7 +382,8 @@ struct RecRegs {
     // cover 8 * P <= kYPass * NT quads. Plain rows: one value per thread and pass.
     static constexpr int kYPass = stage_passes(YREP, NT);
     static constexpr int kPrefetch = NT >= 1024 ? 4 : 6;
-    static constexpr int kTailSlots = NSLOT / 2;
+    static constexpr int kTailSlots = 4;
+    static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
 
     uint32_t xa[NSLOT];  // byte address of the state value inside X0
     uint32_t ya[NSLOT];  // LDS byte address of the emission value in Y0 (absolute)
@@ -399,13 +414,15 @@ struct RecRegs {
 #pragma unroll
         for (int i = 0; i < kYPass; ++i)
             if (i == 0 || i < ypasses) {
-                if constexpr (YREP) {  // four adjacent words: one 16-byte store
-                    const float y = yreg[i];
+                if constexpr (YREP) {
+                    // four adjacent words from one register: two 2-word stores (the
+                    // compiler would spend a register and an instruction per word)
                     const uint32_t at = ybuf + ydst[i];
-                    lds_st(at, y);
-                    lds_st(at + 4, y);
-                    lds_st(at + 8, y);
-                    lds_st(at + 12, y);
+                    asm volatile("ds_write2_b32 %0, %1, %1 offset1:1\n\t"
+                                 "ds_write2_b32 %0, %1, %1 offset0:2 offset1:3"
+                                 :
+                                 : "v"(at), "v"(yreg[i])
+                                 : "memory");
                 } else {
                     lds_st(ybuf + ydst[i], yreg[i]);
                 }
@@ -457,32 +474,41 @@ struct RecRegs {
         int next_close = left ? __builtin_ctzll(left) : 64;
         uint32_t row4 = row4_first;  // byte offset of this lane's row in a state vector
         char* const tr = reinterpret_cast<char*>(trow);
+        // Slots go in pairs: slices are an even number of slots wide, so a slice can
+        // only end on the second slot of a pair.
 #pragma unroll
-        for (int i = 0; i < NSLOT; ++i) {
-            // a wave with fewer slots than the variant holds leaves at its last one;
-            // slices are an even number of slots wide, so that this, and the test
-            // for the end of a slice, are needed at every other slot only
-            if ((i & 1) == 0 && i >= NSLOT - kTailSlots) {
+        for (int i = 0; i < NSLOT; i += 2) {
+            // a wave with fewer slots than the variant holds leaves at its last one
+            // (tested near the end only, where the counts of one graph differ)
+            if (i > 0 && i >= NSLOT - kTailSlots) {
                 int count = nsl;
                 asm volatile("" : "+s"(count));  // compare here, in a scalar register
                 if (i >= count) break;
             }
-            const float x = xv[i % kPrefetch];
-            const float e = ev[i % kPrefetch];
+            float x0 = xv[i % kPrefetch], e0 = ev[i % kPrefetch];
+            const float x1 = xv[(i + 1) % kPrefetch], e1 = ev[(i + 1) % kPrefetch];
             if (i + kPrefetch < NSLOT) {
                 xv[i % kPrefetch] = lds_ld(xc + xa[i + kPrefetch]);
                 ev[i % kPrefetch] = lds_ld(yc + ya[i + kPrefetch]);
+                xv[(i + 1) % kPrefetch] = lds_ld(xc + xa[i + 1 + kPrefetch]);
+                ev[(i + 1) % kPrefetch] = lds_ld(yc + ya[i + 1 + kPrefetch]);
             }
-            // an arc slot; closing and padding slots see e == 0 or w == 0 and add nothing
-            const float t = wr[i] * e;
-            acc1 = fmaf(t, x, acc1);
-            acc2 = HAS_WB ? fmaf(wbr[i], e, acc2) : acc2 + t;
-            if ((i & 1) == 1 && __builtin_expect(i == next_close, 0)) {  // wave-uniform: a slice ends
+            // one wait for the pair: this names the value loaded last, so the first
+            // use of any of the four comes after all of them have arrived
+            asm volatile("" : "+v"(x0), "+v"(e0) : "v"(x1), "v"(e1));
+            // arc slots; closing and padding slots see e == 0 or w == 0 and add nothing
+            const float t0 = wr[i] * e0;
+            const float t1 = wr[i + 1] * e1;
+            acc1 = fmaf(t0, x0, acc1);
+            acc2 = HAS_WB ? fmaf(wbr[i], e0, acc2) : acc2 + t0;
+            acc1 = fmaf(t1, x1, acc1);
+            acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i + 1 : 0], e1, acc2) : acc2 + t1;
+            if (__builtin_expect(i + 1 == next_close, 0)) {  // wave-uniform: a slice ends
                 const float v = fmaf(inv, acc1, cb * acc2);
                 lds_st(xn + row4, v);
                 *reinterpret_cast<float*>(tr + row4) = v;
                 n += v;
-                s = fmaf(wr[i], v, s);
+                s = fmaf(wr[i + 1], v, s);
                 acc1 = 0.f;
                 acc2 = 0.f;
                 row4 += 256;
@@ -490,11 +516,13 @@ struct RecRegs {
                 next_close = left ? __builtin_ctzll(left) : 64;
             }
         }
-        n = wave_sum_uniform(n);
-        s = wave_sum_uniform(s);
-        if (lane == 0) {
-            lds_st(pn + wave * 4, n);
-            lds_st(pn + 64 + wave * 4, s);
+        // both wave sums in one reduction: n in the lower half-wave, s in the upper
+        {
+            const float2 ns = half_wave_sums(n, s);
+            if (lane == 0) {
+                lds_st(pn + wave * 4, ns.x);
+                lds_st(pn + 64 + wave * 4, ns.y);
+            }
         }
         if (k + 2 < T) e2 += estep;
         trow += tstep;
