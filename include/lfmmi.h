@@ -145,7 +145,8 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
  * [6] 1 if the emission row is replicated per LDS bank, [7] 1 if the arcs carry
  * a per-arc leak factor (non-uniform init_prob), [8] modelled LDS cycles of the
  * gathers of one frame (per slot and half-wave, the largest number of distinct
- * addresses in one of the 32 banks), [9..11] 0. */
+ * addresses in one of the 32 banks), [9] 1 if every FWD / BWD slice ends in a
+ * closing slot (packed so when init_prob is not uniform), [10..11] 0. */
 lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
                                        int32_t ord, int64_t info[12]);
 /* Copies the packed ordering out (any pointer may be NULL):
@@ -154,9 +155,9 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
  *   key, w     [total slots * 64] arc records, lane-minor; key = x-index * 4 in
  *              the low 16 bits, y-index * 4 in the high 16 bits; padding has w 0 (its
  *              key points wherever no bank conflict arises).
- *              In FWD and BWD the last slot of every slice holds no arc: its
- *              key is 0 and its w is the row's leak-dot weight (FWD: 1 on real
- *              rows; BWD: init_prob of the row's state)
+ *              With closing slots (info[9]) the last slot of every FWD / BWD
+ *              slice holds no arc: its key is 0 and its w is the row's leak-dot
+ *              weight (FWD: 1 on real rows; BWD: init_prob of the row's state)
  *   row_id     [slices * 64] the state (FWD: to-state, BWD: from-state) or
  *              pdf-id (OCC) a row stands for, -1 for padding rows
  *   x-index / y-index: FWD (from-state in FWD numbering, pdf), BWD (to-state in

@@ -262,6 +262,8 @@ lfmmi_status upload(lfmmi_graph* h)
             d.mask_at = (int32_t)n_mask;
             d.has_wb = od.has_wb;
             d.b_const = od.b_const;
+            d.closing = od.closing_slots;
+            d.a_const = od.a_const;
             n_mask += od.wave_mask.size();
             n_slots += od.total_slots;
             n_soff += od.slice_off.size();
@@ -643,7 +645,8 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t 
     info[6] = ord < 2 && h->rec_yrep ? 1 : 0;
     info[7] = o.has_wb;
     info[8] = o.gather_cycles;
-    info[9] = info[10] = info[11] = 0;
+    info[9] = ord < 2 ? o.closing_slots : 0;
+    info[10] = info[11] = 0;
     return LFMMI_OK;
 }
 

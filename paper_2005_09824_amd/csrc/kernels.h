@@ -20,6 +20,8 @@ struct OrdDesc {
     int32_t has_wb;         // FWD: the leak target differs per state
     float b_const;          // the leak target when it is one constant
     int32_t pdf_first_at;   // OCC: first entry in pdf_first (num_pdfs + 1 entries)
+    int32_t closing;        // FWD/BWD: slices end in a slot that holds the row's leak-dot weight
+    float a_const;          // that weight when it is one constant (no closing slots)
 };
 
 struct DeviceGraph {

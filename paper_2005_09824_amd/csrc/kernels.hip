@@ -211,7 +211,7 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
         Real n = 0, s = 0;
         {
             for (int sl = s0; sl < s1; ++sl) {
-                const int o0 = so[sl], o1 = so[sl + 1] - 1;  // o1: the closing slot
+                const int o0 = so[sl], o1 = so[sl + 1] - od.closing;  // without the closing slot
                 const uint2* rp = recs + (size_t)o0 * 64;
                 const float* wp = wbp + (size_t)o0 * 64;
                 Real acc1 = 0, acc2 = 0;
@@ -245,9 +245,9 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
                     rp += 64;
                     wp += 64;
                 }
-                const Real arow = (Real)__uint_as_float(rp[0].y);
-                const Real v = inv * acc1 + cb * acc2;
                 const int row = sl * 64 + lane;
+                const Real arow = (Real)p.g.va[od.vec_at + row];
+                const Real v = inv * acc1 + cb * acc2;
                 Xn[row] = v;
                 tr[row] = v;
                 n += v;
@@ -331,16 +331,23 @@ __device__ __forceinline__ float wave_sum_uniform(float v)
 
 // Wave sums of a and b at once: a 32-lane swap puts a[l] + a[l + 32] in the lower
 // half-wave and b[l] + b[l + 32] in the upper one, five DPP steps finish both.
-__device__ __forceinline__ float2 half_wave_sums(float a, float b)
+// Lane 31 returns the sum of a, lane 63 the sum of b (other lanes: partial sums).
+__device__ __forceinline__ float half_wave_sums(float a, float b)
 {
-    // lanes 0-31 of .x keep a, lanes 32-63 of .x take b's lanes 0-31; .y the rest
+    // lanes 0-31 of [0] keep a, lanes 32-63 of [0] take b's lanes 0-31; [1] the rest
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b),
                                                      false, false);
     float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     v = row16_allsum(v);
-    v = dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
-    return make_float2(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31)),
-                       __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63)));
+    return dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+}
+
+// Lane 63 returns the sum over the wave (other lanes: partial sums).
+__device__ __forceinline__ float wave_sum_lane63(float v)
+{
+    v = row16_allsum(v);
+    v = dpp_add<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
+    return dpp_add<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
 }
 
 // ---------------------------------------------------------------------------
@@ -431,9 +438,9 @@ struct RecRegs {
 
     template <int PAR>
     __device__ __forceinline__ void step(const int k, const int T, const int tid, const int lane,
-                                         const int wave, const float eps, const float bconst,
+                                         const float eps, const float aconst, const float bconst,
                                          const uint64_t mask, const uint32_t row4_first,
-                                         const int nsl)
+                                         const uint32_t part_at, const int nsl)
     {
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
@@ -446,11 +453,13 @@ struct RecRegs {
         store_y(yn);
         load_y();
 
-        // scalars of step k - 1: lanes 0-15 fetch the n partials, 16-31 the s partials
-        float pv = lds_ld(pc + (lane & 31) * 4);
+        // scalars of step k - 1: lanes 0-15 fetch the n partials, 16-31 the s partials.
+        // Without per-row leak-dot weights s is a_const * n.
+        float pv = lds_ld(pc + (lane & (HAS_WB ? 31 : 15)) * 4);
         pv = row16_allsum(pv);
         const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
-        const float Sd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16));
+        const float Sd = HAS_WB ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16))
+                                : aconst * N;
         float inv = 0.f;
         if (N > 0.f) {
             inv = __builtin_amdgcn_rcpf(N);
@@ -508,7 +517,7 @@ struct RecRegs {
                 lds_st(xn + row4, v);
                 *reinterpret_cast<float*>(tr + row4) = v;
                 n += v;
-                s = fmaf(wr[i + 1], v, s);
+                if (HAS_WB) s = fmaf(wr[i + 1], v, s);  // the closing slot's w is a[row]
                 acc1 = 0.f;
                 acc2 = 0.f;
                 row4 += 256;
@@ -516,13 +525,13 @@ struct RecRegs {
                 next_close = left ? __builtin_ctzll(left) : 64;
             }
         }
-        // both wave sums in one reduction: n in the lower half-wave, s in the upper
-        {
-            const float2 ns = half_wave_sums(n, s);
-            if (lane == 0) {
-                lds_st(pn + wave * 4, ns.x);
-                lds_st(pn + 64 + wave * 4, ns.y);
-            }
+        if constexpr (HAS_WB) {
+            // both wave sums in one reduction: lane 31 ends up with n, lane 63 with s
+            const float ns = half_wave_sums(n, s);
+            if ((lane & 31) == 31) lds_st(pn + part_at, ns);
+        } else {
+            const float ns = wave_sum_lane63(n);
+            if (lane == 63) lds_st(pn + part_at, ns);
         }
         if (k + 2 < T) e2 += estep;
         trow += tstep;
@@ -549,6 +558,7 @@ struct RecRegs {
         const float* wbp = p.g.wb + (size_t)od.rec_at * 64 + lane;
         const int32_t* so = p.g.slice_off + od.slice_off_at;
         const float eps = p.leak;
+        const float aconst = od.a_const;
         const float bconst = od.b_const;
         const float* erows = p.emis + (size_t)b * p.T * P;  // this sequence's emission rows
 
@@ -564,7 +574,7 @@ struct RecRegs {
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
             const bool on = i < nsl;
-            const bool closing = (mask >> i) & 1;
+            const bool closing = HAS_WB && ((mask >> i) & 1);  // holds a[row], no arc
             const uint2 r = on ? recs[(size_t)(first + i) * 64] : make_uint2(0u, 0u);
             xa[i] = r.x & 0xffffu;
             ya[i] = kRegY0 +
@@ -641,21 +651,24 @@ struct RecRegs {
         sS = scalS + (dir == 0 ? 0 : T);
 
         const uint32_t row4_first = (uint32_t)(s0 * 64 + lane) * 4u;
+        // where this lane's end-of-step sum goes: n of wave w at word w, s at 16 + w
+        const uint32_t part_at = (uint32_t)wave * 4u + (HAS_WB && lane >= 32 ? 64u : 0u);
         int k = 1;
         for (; k + 1 <= T; k += 2) {
-            step<1>(k, T, tid, lane, wave, eps, bconst, mask, row4_first, nsl);
-            step<0>(k + 1, T, tid, lane, wave, eps, bconst, mask, row4_first, nsl);
+            step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
+            step<0>(k + 1, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
         }
-        if (k <= T) step<1>(k, T, tid, lane, wave, eps, bconst, mask, row4_first, nsl);
+        if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
 
         // ---- last scalars and the closing dot product
         {
             const uint32_t xc = (T & 1) ? kRegX1 : 0u;
             const uint32_t pc = kRegPart + ((T & 1) ? 128u : 0u);
-            float pv = lds_ld(pc + (lane & 31) * 4);
+            float pv = lds_ld(pc + (lane & (HAS_WB ? 31 : 15)) * 4);
             pv = row16_allsum(pv);
             const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
-            const float Sd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16));
+            const float Sd =
+                HAS_WB ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16)) : aconst * N;
             const float inv = N > 0.f ? 1.f / N : 0.f;
             const float c = eps * Sd * inv;
             if (tid == 0) {

@@ -33,7 +33,7 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
                      [&](int32_t a, int32_t b) { return len[a] > len[b]; });
     std::vector<int32_t> sorted_width(ar.num_slices);
     for (int32_t s = 0; s < ar.num_slices; ++s)
-        sorted_width[s] = len[idx[(size_t)s * kLanes]] + extra_slots;
+        sorted_width[s] = std::max(len[idx[(size_t)s * kLanes]] + extra_slots, 1);
     // even_widths: one more padding slot where needed (the register-resident
     // recursion kernel looks for the end of a slice at every other slot only)
     if (even_widths)
@@ -537,8 +537,10 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     // ---- FWD (rows = to-states) and BWD (rows = from-states) arrangements
     std::vector<int32_t> indeg(S, 0), outdeg(S, 0);
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
-    Arrangement af = arrange(indeg, rec_waves, 1, tune.even_slices);
-    Arrangement ab = arrange(outdeg, rec_waves, 1, tune.even_slices);
+    // with a uniform pi the leak-dot weights are constants and need no slot
+    const int closing = per_arc_leak ? 1 : 0;
+    Arrangement af = arrange(indeg, rec_waves, closing, tune.even_slices);
+    Arrangement ab = arrange(outdeg, rec_waves, closing, tune.even_slices);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {
@@ -565,8 +567,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             bxb[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);
             byy[a] = tune.emission_conflicts ? (int16_t)(g.pdf[a] % kBanks) : (int16_t)-1;
         }
-        for (int32_t sl = 0; sl < af.num_slices; ++sl) wf[sl] = af.slice_width[sl] - 1;
-        for (int32_t sl = 0; sl < ab.num_slices; ++sl) wb_[sl] = ab.slice_width[sl] - 1;
+        for (int32_t sl = 0; sl < af.num_slices; ++sl) wf[sl] = af.slice_width[sl] - closing;
+        for (int32_t sl = 0; sl < ab.num_slices; ++sl) wb_[sl] = ab.slice_width[sl] - closing;
         if (tune.order_slots) {
             order_slots(prow_f, bxf, byy, af.num_slices, wf, &nth_f);
             order_slots(prow_b, bxb, byy, ab.num_slices, wb_, &nth_b);
@@ -602,12 +604,15 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         }
         // closing slot of every slice: the row's leak-dot weight
         Ordering& o = out->ord[d];
-        for (int32_t sl = 0; sl < o.num_slices; ++sl)
-            for (int l = 0; l < kLanes; ++l) {
-                const size_t at = (size_t)(o.slice_off[sl + 1] - 1) * kLanes + l;
-                o.key[at] = 0u;
-                o.w[at] = out->va[d][(size_t)sl * kLanes + l];
-            }
+        o.closing_slots = closing;
+        o.a_const = d == 0 ? 1.f : g.init_prob[0];
+        if (closing)
+            for (int32_t sl = 0; sl < o.num_slices; ++sl)
+                for (int l = 0; l < kLanes; ++l) {
+                    const size_t at = (size_t)(o.slice_off[sl + 1] - 1) * kLanes + l;
+                    o.key[at] = 0u;
+                    o.w[at] = out->va[d][(size_t)sl * kLanes + l];
+                }
         fill_wave_mask(&o);
     }
     // leak target: BWD adds the same amount to every state; FWD adds pi, which
@@ -736,8 +741,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     }
     if (tune.order_slots) {
         const int32_t rf = af.num_slices * kLanes, rb = ab.num_slices * kLanes;
-        retarget_padding(&out->ord[0], tune.emission_conflicts, true, rf, num_pdfs);
-        retarget_padding(&out->ord[1], tune.emission_conflicts, true, rb, num_pdfs);
+        retarget_padding(&out->ord[0], tune.emission_conflicts, closing != 0, rf, num_pdfs);
+        retarget_padding(&out->ord[1], tune.emission_conflicts, closing != 0, rb, num_pdfs);
         retarget_padding(&out->ord[2], true, false, rf, rb);
     }
     out->ord[0].gather_cycles = gather_cycles(out->ord[0], tune.emission_conflicts);

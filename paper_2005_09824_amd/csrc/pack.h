@@ -34,10 +34,14 @@ struct Ordering {
     std::vector<float> w;             // [total_slots * 64]
     std::vector<float> wb;            // non-uniform pi only: FWD w * pi[from-state], BWD w
     std::vector<int32_t> row_id;      // [num_slices * 64], -1 = padding row
-    // FWD / BWD only: every slice ends in one extra slot that holds no arc but
-    // the row's leak-dot weight (FWD 1, BWD pi[row], 0 on padding rows).
-    // wave_mask[w] has bit i set when slot i of wave w is such a closing slot
+    // FWD / BWD only. closing_slots: every slice ends in one extra slot that holds
+    // no arc but the row's leak-dot weight a[row] (FWD 1, BWD pi[row], 0 on padding
+    // rows); packed so when pi is not uniform. Otherwise a[row] is the constant
+    // a_const on every real row and slices hold arcs (and padding) only.
+    // wave_mask[w] has bit i set when slot i of wave w is the last of a slice
     // (0 when the wave owns more than 64 slots).
+    int32_t closing_slots = 0;
+    float a_const = 0.f;
     std::vector<uint64_t> wave_mask;  // [num_waves]
     int64_t gather_cycles = 0;        // modelled LDS cycles of the gathers of one frame
     float b_const = 0.f;              // leak target when it is one constant (BWD 1, FWD uniform pi)

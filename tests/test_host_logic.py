@@ -43,7 +43,7 @@ def _unpack(graph_handle, g, graph):
         assert max(per_wave) == d["max_wave_slots"]
         for s in range(d["slices"]):
             o0, o1 = d["slice_off"][s], d["slice_off"][s + 1]
-            if o < 2:   # the closing slot of the slice carries the row's leak-dot weight
+            if o < 2 and d["closing_slots"]:   # it carries the row's leak-dot weight
                 o1 -= 1
                 for lane in range(64):
                     row = s * 64 + lane
@@ -136,7 +136,7 @@ def test_graph_with_no_arcs_and_isolated_states():
          "pdf": np.zeros(0, np.int32), "logw": np.zeros(0, np.float32),
          "init_prob": np.ones(3, np.float32), "final_prob": np.ones(3, np.float32)}
     h = binding.lfmmi_graph_pack(g)
-    assert binding.lfmmi_graph_ordering_info(h, 0, 0)["total_slots"] == 2  # one padding slot, then the closing slot
+    assert binding.lfmmi_graph_ordering_info(h, 0, 0)["total_slots"] == 2  # uniform pi: no closing slot, two padding slots
     assert binding.lfmmi_graph_ordering_info(h, 0, 2)["total_slots"] == 0  # no rows at all
     h.close()
 
