@@ -390,6 +390,8 @@ struct RecRegs {
     static constexpr int kYPass = stage_passes(YREP, NT);
     static constexpr int kPrefetch = NT >= 1024 ? 4 : 6;
     static constexpr int kTailSlots = 4;
+    static constexpr int kStageAt = 4;  // slot before which a step does its global memory work
+    static_assert(kStageAt % 2 == 0 && kStageAt < NSLOT - kTailSlots, "every wave reaches it");
     static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
 
     uint32_t xa[NSLOT];  // byte address of the state value inside X0
@@ -448,14 +450,18 @@ struct RecRegs {
         constexpr uint32_t yc = PAR ? 0u : (kRegY1 - kRegY0), yn = PAR ? kRegY1 : kRegY0;
         constexpr uint32_t pc = kRegPart + (PAR ? 0u : 128u), pn = kRegPart + (PAR ? 128u : 0u);
 
-        // emission row of step k + 1 (loaded one step ago) into the other Y buffer,
-        // then the loads for step k + 2; past the end both repeat the last row
-        store_y(yn);
-        load_y();
-
-        // scalars of step k - 1: lanes 0-15 fetch the n partials, 16-31 the s partials.
-        // Without per-row leak-dot weights s is a_const * n.
+        // First the LDS reads this wave waits for: the partial sums of step k - 1
+        // (lanes 0-15 fetch the n partials, 16-31 the s partials) and the first
+        // gathers. The scalar chain below then runs while the gathers are in flight.
         float pv = lds_ld(pc + (lane & (HAS_WB ? 31 : 15)) * 4);
+        float xv[kPrefetch], ev[kPrefetch];
+#pragma unroll
+        for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
+            xv[i] = lds_ld(xc + xa[i]);
+            ev[i] = lds_ld(yc + ya[i]);
+        }
+        asm volatile("" ::: "memory");  // nothing else moves ahead of these reads
+        // Without per-row leak-dot weights s is a_const * n.
         pv = row16_allsum(pv);
         const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
         const float Sd = HAS_WB ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16))
@@ -467,17 +473,7 @@ struct RecRegs {
         }
         const float c = eps * Sd * inv;
         const float cb = HAS_WB ? c : c * bconst;
-        if (tid == 0) {
-            *sN = N;
-            *sS = Sd;
-        }
 
-        float xv[kPrefetch], ev[kPrefetch];
-#pragma unroll
-        for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
-            xv[i] = lds_ld(xc + xa[i]);
-            ev[i] = lds_ld(yc + ya[i]);
-        }
         float acc1 = 0.f, acc2 = 0.f, n = 0.f, s = 0.f;
         uint64_t left = mask;
         int next_close = left ? __builtin_ctzll(left) : 64;
@@ -493,6 +489,24 @@ struct RecRegs {
                 int count = nsl;
                 asm volatile("" : "+s"(count));  // compare here, in a scalar register
                 if (i >= count) break;
+            }
+            // issue priority falls as the wave advances, so that the waves of a SIMD
+            // (served oldest first at equal priority) move through the slots together
+            if (i == 0) __builtin_amdgcn_s_setprio(2);
+            else if (i == (NSLOT / 6) * 2) __builtin_amdgcn_s_setprio(1);
+            else if (i == (NSLOT / 3) * 2) __builtin_amdgcn_s_setprio(0);
+            if (i == kStageAt) {
+                // Global memory work sits here, a few slots in: the loads it waits for
+                // were issued a step ago and the last stores long enough ago to be
+                // done, so the wait costs nothing. Emission row of step k + 1 (loaded
+                // one step ago) into the other Y buffer, then the loads for step k + 2
+                // (past the end both repeat the last row), and the scalars of step k - 1.
+                store_y(yn);
+                load_y();
+                if (tid == 0) {
+                    *sN = N;
+                    *sS = Sd;
+                }
             }
             float x0 = xv[i % kPrefetch], e0 = ev[i % kPrefetch];
             const float x1 = xv[(i + 1) % kPrefetch], e1 = ev[(i + 1) % kPrefetch];
@@ -525,6 +539,7 @@ struct RecRegs {
                 next_close = left ? __builtin_ctzll(left) : 64;
             }
         }
+        __builtin_amdgcn_s_setprio(3);  // the serial end of this step and start of the next
         if constexpr (HAS_WB) {
             // both wave sums in one reduction: lane 31 ends up with n, lane 63 with s
             const float ns = half_wave_sums(n, s);
