@@ -3,8 +3,6 @@
 
 #include <algorithm>
 #include <cmath>
-#include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <numeric>
 #include <queue>
@@ -23,7 +21,7 @@ struct Arrangement {
 };
 
 Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
-                    bool even_widths = false, const double* wave_share = nullptr)
+                    bool even_widths = false)
 {
     Arrangement ar;
     const int32_t R = (int32_t)len.size();
@@ -43,17 +41,12 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
 
     std::vector<std::vector<int32_t>> owned(ar.num_waves);
     std::vector<int64_t> load(ar.num_waves, 0);
-    // share[w]: the part of the work wave w should get, relative to the others
-    std::vector<double> share(ar.num_waves, 1.0);
-    if (wave_share)
-        for (int w = 0; w < ar.num_waves; ++w) share[w] = wave_share[w];
-    auto rel = [&](int w, int64_t l) { return (double)l / share[w]; };
     for (int32_t s = 0; s < ar.num_slices; ++s) {
         int best = 0;
         for (int w = 1; w < ar.num_waves; ++w) {
-            const double lw = rel(w, load[w] + sorted_width[s]);
-            const double lb = rel(best, load[best] + sorted_width[s]);
-            if (lw < lb || (lw == lb && owned[w].size() < owned[best].size())) best = w;
+            if (load[w] < load[best] ||
+                (load[w] == load[best] && owned[w].size() < owned[best].size()))
+                best = w;
         }
         owned[best].push_back(s);
         load[best] += sorted_width[s];
@@ -62,13 +55,13 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
     for (int round = 0; round < 256; ++round) {
         int top = 0;
         for (int w = 1; w < ar.num_waves; ++w)
-            if (rel(w, load[w]) > rel(top, load[top])) top = w;
+            if (load[w] > load[top]) top = w;
         bool improved = false;
         for (size_t a = 0; a < owned[top].size() && !improved; ++a) {
             const int64_t wa = sorted_width[owned[top][a]];
             for (int w = 0; w < ar.num_waves && !improved; ++w) {
                 if (w == top) continue;
-                if (rel(w, load[w] + wa) < rel(top, load[top])) {  // move
+                if (load[w] + wa < load[top]) {  // move
                     owned[w].push_back(owned[top][a]);
                     owned[top].erase(owned[top].begin() + a);
                     load[w] += wa;
@@ -78,7 +71,7 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
                 }
                 for (size_t c = 0; c < owned[w].size(); ++c) {  // swap
                     const int64_t wc = sorted_width[owned[w][c]];
-                    if (wc < wa && rel(w, load[w] - wc + wa) < rel(top, load[top])) {
+                    if (wc < wa && load[w] - wc + wa < load[top]) {
                         std::swap(owned[top][a], owned[w][c]);
                         load[top] += wc - wa;
                         load[w] += wa - wc;
@@ -547,14 +540,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
     // with a uniform pi the leak-dot weights are constants and need no slot
     const int closing = per_arc_leak ? 1 : 0;
-    std::vector<double> share(std::max(rec_waves, 1), 1.0);
-    if (const char* sk = std::getenv("LFMMI_SKEW")) {
-        double g[4] = {1, 1, 1, 1};
-        std::sscanf(sk, "%lf,%lf,%lf,%lf", &g[0], &g[1], &g[2], &g[3]);
-        for (int w = 0; w < rec_waves; ++w) share[w] = g[std::min(3, w * 4 / rec_waves)];
-    }
-    Arrangement af = arrange(indeg, rec_waves, closing, tune.even_slices, share.data());
-    Arrangement ab = arrange(outdeg, rec_waves, closing, tune.even_slices, share.data());
+    Arrangement af = arrange(indeg, rec_waves, closing, tune.even_slices);
+    Arrangement ab = arrange(outdeg, rec_waves, closing, tune.even_slices);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {
