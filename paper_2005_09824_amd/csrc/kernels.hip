@@ -1024,10 +1024,12 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 acc[f] = fmaf(w * bt, a, acc[f]);
             }
         };
-        // emission value of this thread's gradient entry, in flight during the gathers
+        // emission value and frame scale of this thread's gradient entry, in flight
+        // during the gathers
         const size_t group_at = ((size_t)b * p.T + (t0 - 1)) * P;
         const bool my_live = my_f < F && t0 + my_f <= T;
         const float my_e = my_live ? p.emis[group_at + tid] : 0.f;
+        const float my_c = my_live ? cfac[t0 + my_f] : 0.f;
 
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
@@ -1069,7 +1071,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 if (!p.accumulate) *g = 0.f;
                 continue;
             }
-            float sum = 0.f, e;
+            float sum = 0.f, e, c;
             int r, r1;
             if (idx == tid) {
 #pragma unroll
@@ -1078,14 +1080,15 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 r = my_r0 + kPre;
                 r1 = my_r1;
                 e = my_e;
+                c = my_c;
             } else {
                 r = pdf_first[d];
                 r1 = pdf_first[d + 1];
                 e = p.emis[group_at + idx];
+                c = cfac[t];
             }
             for (; r < r1; ++r)
                 sum += lds_ld(kRowSum + (uint32_t)(f * occ_rows + pdf_rows[r]) * 4u);
-            const float c = cfac[t];
             const float v = c == 0.f ? 0.f : p.grad_scale * c * e * sum;
             *g = p.accumulate ? *g + v : v;
         }
