@@ -388,7 +388,7 @@ struct RecRegs {
     // copies of one value with one 16-byte store, kYPass passes of NT threads
     // cover 8 * P <= kYPass * NT quads. Plain rows: one value per thread and pass.
     static constexpr int kYPass = stage_passes(YREP, NT);
-    static constexpr int kPrefetch = NT >= 1024 ? 4 : 6;
+    static constexpr int kPrefetch = NT >= 1024 ? 2 : (NT >= 768 ? 4 : 6);
     static constexpr int kTailSlots = 4;
     static constexpr int kStageAt = 4;  // slot before which a step does its global memory work
     static_assert(kStageAt % 2 == 0 && kStageAt < NSLOT - kTailSlots, "every wave reaches it");
@@ -454,7 +454,7 @@ struct RecRegs {
         // (lanes 0-15 fetch the n partials, 16-31 the s partials) and the first
         // gathers. The scalar chain below then runs while the gathers are in flight.
         float pv = lds_ld(pc + (lane & (HAS_WB ? 31 : 15)) * 4);
-        float xv[kPrefetch], ev[kPrefetch];
+        float xv[kPrefetch ? kPrefetch : 1], ev[kPrefetch ? kPrefetch : 1];
 #pragma unroll
         for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
             xv[i] = lds_ld(xc + xa[i]);
@@ -508,13 +508,20 @@ struct RecRegs {
                     *sS = Sd;
                 }
             }
-            float x0 = xv[i % kPrefetch], e0 = ev[i % kPrefetch];
-            const float x1 = xv[(i + 1) % kPrefetch], e1 = ev[(i + 1) % kPrefetch];
-            if (i + kPrefetch < NSLOT) {
-                xv[i % kPrefetch] = lds_ld(xc + xa[i + kPrefetch]);
-                ev[i % kPrefetch] = lds_ld(yc + ya[i + kPrefetch]);
-                xv[(i + 1) % kPrefetch] = lds_ld(xc + xa[i + 1 + kPrefetch]);
-                ev[(i + 1) % kPrefetch] = lds_ld(yc + ya[i + 1 + kPrefetch]);
+            float x0, e0, x1, e1;
+            if constexpr (kPrefetch == 0) {
+                x0 = lds_ld(xc + xa[i]); e0 = lds_ld(yc + ya[i]);
+                x1 = lds_ld(xc + xa[i + 1]); e1 = lds_ld(yc + ya[i + 1]);
+            } else {
+                x0 = xv[i % (kPrefetch ? kPrefetch : 1)]; e0 = ev[i % (kPrefetch ? kPrefetch : 1)];
+                x1 = xv[(i + 1) % (kPrefetch ? kPrefetch : 1)]; e1 = ev[(i + 1) % (kPrefetch ? kPrefetch : 1)];
+            }
+            if (kPrefetch > 0 && i + kPrefetch < NSLOT) {
+                constexpr int kp = kPrefetch ? kPrefetch : 1;
+                xv[i % kp] = lds_ld(xc + xa[(i + kp) % NSLOT]);
+                ev[i % kp] = lds_ld(yc + ya[(i + kp) % NSLOT]);
+                xv[(i + 1) % kp] = lds_ld(xc + xa[(i + 1 + kp) % NSLOT]);
+                ev[(i + 1) % kp] = lds_ld(yc + ya[(i + 1 + kp) % NSLOT]);
             }
             // one wait for the pair: this names the value loaded last, so the first
             // use of any of the four comes after all of them have arrived

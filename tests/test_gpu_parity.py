@@ -80,6 +80,24 @@ def test_scaled_configs_every_element(config, scale):
     h.close()
 
 
+def test_nonuniform_start_distribution_on_the_register_path():
+    # a start distribution that is not uniform: every arc carries its leak factor
+    # and slices end in closing slots; all final weights positive keeps it in fp32
+    wl = workloads.make_workload(2, scale={"S": 1500, "B": 4, "Tlo": 20, "Thi": 45}, pad_value=np.nan)
+    g = wl["den"]
+    rng = np.random.default_rng(7)
+    pi = rng.uniform(0.05, 1.0, g["num_states"])
+    g["init_prob"] = (pi / pi.sum()).astype(np.float32)
+    g["final_prob"] = rng.uniform(0.2, 1.0, g["num_states"]).astype(np.float32)
+    h = binding.lfmmi_graph_create(g)
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    assert info["per_arc_leak"] == 1 and info["closing_slots"] == 1 and info["register_slots"] > 0
+    assert binding.lfmmi_graph_info(h)["fp64"] == 0
+    lz, gamma = oracle.forward_backward(g, wl["logits"], wl["lengths"], wl["leak"])
+    check(*run_gpu(h, wl["logits"], wl["lengths"], wl["leak"]), lz, gamma, "non-uniform pi")
+    h.close()
+
+
 def test_config5_scaled_full_loss():
     wl = workloads.make_workload(5, scale={"S": 400, "B": 6, "nlo": 5, "nhi": 25})
     den = binding.lfmmi_graph_create(wl["den"])
