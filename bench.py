@@ -23,8 +23,9 @@ sys.path.insert(0, ROOT)
 # MI355X: 256 CUs x 128 B/clk LDS x 2.4 GHz
 LDS_PEAK_GBPS = 256 * 128 * 2.4
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the recursion kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
-# a plain copy of known size (profiles/hbm_traffic_wsj_mono_2k.txt); other workloads: not measured
+# HBM bytes of the recursion kernel per step (all its launches), from rocprofv3 FETCH_SIZE /
+# WRITE_SIZE scaled by a plain copy of known size (profiles/hbm_traffic_wsj_mono_2k.txt); other
+# workloads: not measured
 REC_TRAFFIC_BYTES = {"wsj_mono_2k": 357.8e6}
 
 
@@ -102,7 +103,10 @@ def main():
     # dominant kernel: the alpha/beta recursion. Algorithmic LDS bytes per frame:
     # per arc and direction two 4-byte gathers (state vector, emission), per state
     # and direction 12 bytes (write, re-read for the rescale, write back).
-    rec_bytes = frames * (16.0 * A + 24.0 * S)
+    # A call cuts its sequences into buckets that run concurrently, each with a
+    # recursion launch of its own: bytes and duration below are per launch (means).
+    launches_per_call = kern["launches"] / max(kern["calls"], 1)
+    rec_bytes = frames * (16.0 * A + 24.0 * S) / launches_per_call
     rec_s = kern["rec"] * 1e-3
     achieved = rec_bytes / rec_s / 1e9
     info = binding.lfmmi_graph_info(den)
@@ -124,12 +128,14 @@ def main():
                    "numerators": num is not None},
         "roofline": {"bound": "lds", "kernel": "k_rec", "achieved": achieved,
                      "peak": LDS_PEAK_GBPS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBPS,
-                     "traffic": REC_TRAFFIC_BYTES.get(wl["name"]),
-                     "kernel_ms": kern["rec"],
+                     "traffic": (REC_TRAFFIC_BYTES[wl["name"]] / launches_per_call
+                                 if wl["name"] in REC_TRAFFIC_BYTES else None),
+                     "kernel_ms": kern["rec"], "launches_per_step": launches_per_call,
                      "workgroups": 2 * B, "compute_units": 256,
                      # the same against the LDS peak of the compute units a workgroup holds
                      "frac_of_occupied_cus": achieved / (LDS_PEAK_GBPS * min(2 * B, 256) / 256.0),
-                     "hbm_frac": (REC_TRAFFIC_BYTES.get(wl["name"], 0.0) / rec_s / 1e9) / HBM_PEAK_GBPS},
+                     "hbm_frac": (REC_TRAFFIC_BYTES.get(wl["name"], 0.0) / launches_per_call
+                                  / rec_s / 1e9) / HBM_PEAK_GBPS},
         "kernels_ms": {k: kern[k] for k in ("emit", "rec", "scan", "occ")},
         "arc_updates_per_s": 2.0 * A * fps,
         "workspace_bytes": info["workspace_bytes"],

@@ -117,6 +117,11 @@ void lfmmi_graph_destroy(lfmmi_graph *graph);
  *   hip_stream  hipStream_t (NULL = default stream). The call only enqueues
  *            work; it does not synchronise. It may allocate (and so
  *            synchronise) when the handle's cached workspace has to grow.
+ *            Internally the sequences are cut by length into up to four buckets
+ *            whose kernels run on streams of the handle's own (default
+ *            priority) between an event recorded on hip_stream and events
+ *            hip_stream then waits for: all of the call's work is ordered on
+ *            hip_stream as if it ran there.
  * B == 0 or T == 0 with all lengths 0 are valid. Calls on one handle must be
  * ordered on one stream (they share the handle's workspace).
  */
@@ -167,14 +172,18 @@ lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph *graph, int32_t g, int3
                                        int32_t *slice_off, int32_t *wave_first,
                                        uint32_t *key, float *w, int32_t *row_id);
 
-/* Per-kernel timing with HIP events on the caller's stream. While enabled,
- * every lfmmi_forward_backward on this handle records events around its four
- * kernels. lfmmi_profile_read waits for the last such call, returns the mean
- * duration per call in milliseconds - ms[0] emission, [1] recursion (alpha and
- * beta), [2] scales, [3] occupancy + gradient - and the number of calls averaged
- * in *calls (may be NULL), then forgets them. */
+/* Per-kernel timing with HIP events. While enabled, every lfmmi_forward_backward
+ * on this handle records events around its kernels, on the streams they run on:
+ * one emission launch per call, then one recursion, scale and occupancy launch
+ * per bucket of sequences (see lfmmi_forward_backward). lfmmi_profile_read waits
+ * for them and returns mean durations in milliseconds - ms[0] emission per call;
+ * [1] recursion (alpha and beta), [2] scales, [3] occupancy + gradient, each per
+ * launch - with the number of calls in *calls and of launches of each of the
+ * three in *launches (either may be NULL), then forgets them. Launches of one
+ * call overlap: the per-launch means do not add up to the time of a call. */
 lfmmi_status lfmmi_profile_enable(lfmmi_graph *graph, int enable);
-lfmmi_status lfmmi_profile_read(lfmmi_graph *graph, float ms[4], int32_t *calls);
+lfmmi_status lfmmi_profile_read(lfmmi_graph *graph, float ms[4], int32_t *calls,
+                                int32_t *launches);
 
 #ifdef __cplusplus
 }

@@ -62,7 +62,7 @@ def load_library():
     lib.lfmmi_graph_ordering_info.argtypes = [vp, i32, i32, vp]
     lib.lfmmi_graph_ordering_copy.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     lib.lfmmi_profile_enable.argtypes = [vp, ctypes.c_int]
-    lib.lfmmi_profile_read.argtypes = [vp, vp, vp]
+    lib.lfmmi_profile_read.argtypes = [vp, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("lfmmi_graph_destroy", "lfmmi_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -252,7 +252,9 @@ def lfmmi_profile_enable(graph, enable=True):
 def lfmmi_profile_read(graph):
     ms = np.zeros(4, dtype=np.float32)
     calls = np.zeros(1, dtype=np.int32)
-    _check(load_library().lfmmi_profile_read(graph.handle, _hp(ms), _hp(calls)))
+    launches = np.zeros(1, dtype=np.int32)
+    _check(load_library().lfmmi_profile_read(graph.handle, _hp(ms), _hp(calls), _hp(launches)))
     out = dict(zip(("emit", "rec", "scan", "occ"), (float(v) for v in ms)))
     out["calls"] = int(calls[0])
+    out["launches"] = int(launches[0])
     return out

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -73,9 +74,15 @@ struct lfmmi_graph {
     hipEvent_t stage_done = nullptr;
     bool stage_pending = false;
 
-    // profiling: one set of 5 events per call made while enabled
+    // streams and events of the concurrent buckets of a call, made on first use
+    hipStream_t aux[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
+    hipEvent_t fork = nullptr;
+    hipEvent_t join[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
+
+    // profiling: per call made while enabled 2 + 4 * (its bucket count) events
     bool profile = false;
     std::vector<hipEvent_t> ev;
+    std::vector<int32_t> ev_buckets;  // bucket count of each profiled call
 };
 
 namespace {
@@ -434,6 +441,11 @@ void lfmmi_graph_destroy(lfmmi_graph* h)
         if (h->stage) (void)hipHostFree(h->stage);
         if (h->stage_done) (void)hipEventDestroy(h->stage_done);
         for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
+        for (int q = 1; q < Buckets::kMax; ++q) {
+            if (h->aux[q]) (void)hipStreamDestroy(h->aux[q]);
+            if (h->join[q]) (void)hipEventDestroy(h->join[q]);
+        }
+        if (h->fork) (void)hipEventDestroy(h->fork);
     }
     delete h;
 }
@@ -598,19 +610,59 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     }
     shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", 1));
 
+    // ---- buckets of sequences that run concurrently (longest sequences first):
+    // an eighth, a quarter, a quarter and the rest, so that the bucket that ends
+    // last has little occupancy work left to do on its own
+    Buckets bk;
+    {
+        int want = std::min(env_int("LFMMI_BUCKETS", Buckets::kMax), (int)Buckets::kMax);
+        want = std::max(1, std::min(want, B / 2));
+        if (T == 0) want = 1;
+        static const double upto[Buckets::kMax][Buckets::kMax] = {
+            {1.0, 1.0, 1.0, 1.0}, {0.25, 1.0, 1.0, 1.0}, {0.15, 0.5, 1.0, 1.0}, {0.125, 0.375, 0.625, 1.0}};
+        bk.n = want;
+        int at = 0;
+        for (int q = 0; q < want; ++q) {
+            int end = q == want - 1 ? B : (int)std::lround(upto[want - 1][q] * B);
+            end = std::max(at + 1, std::min(end, B - (want - 1 - q)));
+            bk.first[q] = at;
+            bk.count[q] = end - at;
+            for (int i = at; i < end; ++i) bk.tmax[q] = std::max(bk.tmax[q], lengths[by_len[i]]);
+            at = end;
+        }
+        if (want > 1) {
+            if (!h->fork &&
+                (e = hipEventCreateWithFlags(&h->fork, hipEventDisableTiming)) != hipSuccess)
+                return fail_hip(e, "hipEventCreate");
+            for (int q = 1; q < want; ++q) {
+                // plain streams (default priority) that do not synchronise with stream 0
+                if (!h->aux[q] &&
+                    (e = hipStreamCreateWithFlags(&h->aux[q], hipStreamNonBlocking)) != hipSuccess)
+                    return fail_hip(e, "hipStreamCreate");
+                if (!h->join[q] &&
+                    (e = hipEventCreateWithFlags(&h->join[q], hipEventDisableTiming)) != hipSuccess)
+                    return fail_hip(e, "hipEventCreate");
+                bk.streams[q] = h->aux[q];
+                bk.join[q] = h->join[q];
+            }
+            bk.fork = h->fork;
+        }
+    }
+
     hipEvent_t* ev = nullptr;
     if (h->profile) {
-        const size_t first = h->ev.size();
-        h->ev.resize(first + 5, nullptr);
-        for (size_t i = first; i < first + 5; ++i)
+        const size_t first = h->ev.size(), count = 2 + 4 * (size_t)bk.n;
+        h->ev.resize(first + count, nullptr);
+        for (size_t i = first; i < first + count; ++i)
             if ((e = hipEventCreate(&h->ev[i])) != hipSuccess) {
                 for (size_t j = first; j < i; ++j) (void)hipEventDestroy(h->ev[j]);
                 h->ev.resize(first);
                 return fail_hip(e, "hipEventCreate");
             }
+        h->ev_buckets.push_back(bk.n);
         ev = h->ev.data() + first;
     }
-    if ((e = launch_forward_backward(p, shape, stream, ev)) != hipSuccess)
+    if ((e = launch_forward_backward(p, shape, stream, ev, bk)) != hipSuccess)
         return fail_hip(e, "kernel launch");
     return LFMMI_OK;
 }
@@ -673,30 +725,45 @@ lfmmi_status lfmmi_profile_enable(lfmmi_graph* h, int enable)
     return LFMMI_OK;
 }
 
-lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4], int32_t* calls)
+lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4], int32_t* calls, int32_t* launches)
 {
     if (!h || !ms) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
-    const size_t n = h->ev.size() / 5;
+    const size_t n = h->ev_buckets.size();
     if (calls) *calls = (int32_t)n;
+    if (launches) *launches = 0;
     for (int i = 0; i < 4; ++i) ms[i] = 0.f;
     if (n == 0) return fail(LFMMI_ERR_INVALID_ARG, "no profiled call to read");
-    hipError_t e = hipEventSynchronize(h->ev.back());
     lfmmi_status st = LFMMI_OK;
-    if (e != hipSuccess) st = fail_hip(e, "hipEventSynchronize");
+    hipError_t e;
     double sum[4] = {0, 0, 0, 0};
-    for (size_t c = 0; c < n && st == LFMMI_OK; ++c)
-        for (int i = 0; i < 4; ++i) {
-            float t = 0.f;
-            if ((e = hipEventElapsedTime(&t, h->ev[c * 5 + i], h->ev[c * 5 + i + 1])) != hipSuccess) {
-                st = fail_hip(e, "hipEventElapsedTime");
-                break;
-            }
-            sum[i] += t;
+    int64_t runs = 0;
+    auto elapsed = [&](size_t from, size_t to, double* acc) {
+        float t = 0.f;
+        if ((e = hipEventSynchronize(h->ev[to])) != hipSuccess ||
+            (e = hipEventElapsedTime(&t, h->ev[from], h->ev[to])) != hipSuccess) {
+            st = fail_hip(e, "hipEventElapsedTime");
+            return;
         }
+        *acc += t;
+    };
+    size_t at = 0;
+    for (size_t c = 0; c < n && st == LFMMI_OK; ++c) {
+        elapsed(at, at + 1, &sum[0]);
+        for (int q = 0; q < h->ev_buckets[c] && st == LFMMI_OK; ++q) {
+            const size_t b0 = at + 2 + 4 * (size_t)q;
+            for (int i = 0; i < 3 && st == LFMMI_OK; ++i) elapsed(b0 + i, b0 + i + 1, &sum[1 + i]);
+            ++runs;
+        }
+        at += 2 + 4 * (size_t)h->ev_buckets[c];
+    }
     for (hipEvent_t x : h->ev) (void)hipEventDestroy(x);
     h->ev.clear();
-    if (st == LFMMI_OK)
-        for (int i = 0; i < 4; ++i) ms[i] = (float)(sum[i] / (double)n);
+    h->ev_buckets.clear();
+    if (st == LFMMI_OK) {
+        ms[0] = (float)(sum[0] / (double)n);
+        for (int i = 1; i < 4; ++i) ms[i] = (float)(sum[i] / (double)runs);
+        if (launches) *launches = (int32_t)runs;
+    }
     return st;
 }
 

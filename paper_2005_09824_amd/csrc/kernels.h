@@ -52,6 +52,7 @@ struct FbParams {
     DeviceGraph g;
     const SeqDesc* seqs;    // [B]
     const int32_t* order;   // [2B] (b << 1 | direction), longest sequences first
+    int32_t seq_first;      // this launch covers order entries from 2 * seq_first on
     const float* logits;    // [B, T, P]
     float* emis;            // [B, T, P] exp(logit - row max)
     float* rowmax;          // [B, T]
@@ -86,10 +87,27 @@ struct LaunchShape {
     int occ_groups;    // groups of occ_multi frames per workgroup
 };
 
-// Each returns the first HIP error met (hipSuccess otherwise). ev, if non-null,
-// holds 5 events recorded before, between and after the four kernels.
+// Sequences in launch order are cut into `n` consecutive buckets (longest
+// first). Bucket 0 runs on the caller's stream, the others on streams[1..n-1]
+// after the emission kernel, and the caller's stream waits for them at the end:
+// short sequences finish the recursion early and their occupancy pass then
+// overlaps the recursion of the long ones, which leaves compute units idle.
+struct Buckets {
+    static constexpr int kMax = 4;
+    int n = 1;
+    int first[kMax] = {0, 0, 0, 0};  // first sequence (index into the launch order)
+    int count[kMax] = {0, 0, 0, 0};
+    int tmax[kMax] = {0, 0, 0, 0};   // longest sequence of the bucket
+    hipStream_t streams[kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
+    hipEvent_t fork = nullptr;                                        // n > 1 only
+    hipEvent_t join[kMax] = {nullptr, nullptr, nullptr, nullptr};      // [0] unused
+};
+
+// Returns the first HIP error met (hipSuccess otherwise). ev, if non-null, holds
+// 2 + 4 * n events: around the emission kernel, then per bucket before, between
+// and after its three kernels.
 hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
-                                   hipStream_t stream, hipEvent_t* ev);
+                                   hipStream_t stream, hipEvent_t* ev, const Buckets& bk);
 hipError_t configure_kernels();
 // Dynamic LDS the recursion / occupancy kernels need.
 size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);

@@ -54,8 +54,13 @@ __global__ void __launch_bounds__(256) k_emit(FbParams p)
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int b = blockIdx.y;
-    if (t >= p.seqs[b].T) return;
+    if (t >= p.T) return;
     const size_t at = ((size_t)b * p.T + t) * p.P;
+    if (t >= p.seqs[b].T) {  // a padding frame: its gradient row is zero
+        if (!p.accumulate)
+            for (int d = lane; d < p.P; d += 64) p.grad[at + d] = 0.f;
+        return;
+    }
     const float* x = p.logits + at;
     float* e = p.emis + at;
     float m = -INFINITY;
@@ -723,7 +728,7 @@ template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT>
 __global__ void __launch_bounds__(NT) k_rec(FbParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int code = p.order[blockIdx.x];
+    const int code = p.order[2 * p.seq_first + blockIdx.x];
     const int b = code >> 1, dir = code & 1;
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
@@ -746,7 +751,7 @@ __global__ void __launch_bounds__(256) k_scan(FbParams p)
     __shared__ double sa[256], sb[256], sm[256];
     __shared__ double tot[3];
     const int tid = threadIdx.x;
-    const int b = blockIdx.x;
+    const int b = p.order[2 * (p.seq_first + blockIdx.x)] >> 1;
     const SeqDesc sd = p.seqs[b];
     const int T = sd.T;
     const int n = T + 1;
@@ -817,7 +822,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = blockDim.x;
-    const int b = blockIdx.y;
+    const int b = p.order[2 * (p.seq_first + blockIdx.y)] >> 1;
     const SeqDesc sd = p.seqs[b];
     const int T = sd.T;
     const int P = p.P;
@@ -919,7 +924,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = blockDim.x;
-    const int b = blockIdx.y;
+    const int b = p.order[2 * (p.seq_first + blockIdx.y)] >> 1;
     const SeqDesc sd = p.seqs[b];
     const int T = sd.T;
     const int P = p.P;
@@ -1211,22 +1216,24 @@ size_t occ_plane_lds_bytes(int occ_rows, int frames)
 
 template <typename Real>
 static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipStream_t stream,
-                               hipEvent_t* ev)
+                               hipEvent_t* ev, const Buckets& bk)
 {
     hipError_t e;
     const bool wide = sizeof(Real) == 8;
     const RecVariant* rv =
         find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0);
     if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
-#define LFMMI_EV(i)                                                   \
-    if (ev) { e = hipEventRecord(ev[i], stream); if (e != hipSuccess) return e; }
-    LFMMI_EV(0)
+#define LFMMI_EV(i, on)                                               \
+    if (ev) { e = hipEventRecord(ev[i], on); if (e != hipSuccess) return e; }
+    LFMMI_EV(0, stream)
     if (p.T > 0) {
         dim3 grid((p.T + 3) / 4, p.B);
         hipLaunchKernelGGL(k_emit, grid, dim3(256), 0, stream, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    LFMMI_EV(1)
+    LFMMI_EV(1, stream)
+    if (bk.n > 1 && (e = hipEventRecord(bk.fork, stream)) != hipSuccess) return e;
+
     int rec_threads = shape.rec_threads;
     if (shape.rec_nslot > 0) {
         // enough threads to stage one emission row in the variant's passes; waves
@@ -1237,44 +1244,65 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         rec_threads = std::max(rec_threads, need);
         if (rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
     }
-    hipLaunchKernelGGL(rv->fn, dim3(2 * p.B), dim3(rec_threads),
-                       shape.rec_nslot > 0
-                           ? reg_lds_bytes()
-                           : rec_lds_bytes(p.lds_rows, p.P, wide, shape.rec_yrep != 0),
-                       stream, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    LFMMI_EV(2)
-    hipLaunchKernelGGL(k_scan<Real>, dim3(p.B), dim3(256), 0, stream, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    LFMMI_EV(3)
-    if (p.T > 0) {
-        if (!wide && shape.occ_multi > 0) {
-            const int F = shape.occ_multi;
-            const int per_wg = F * shape.occ_groups;
-            dim3 grid((p.T + per_wg - 1) / per_wg, p.B);
-            void (*fn)(FbParams, int) = F == 4   ? k_occ_planes<4, 8192>
-                                        : F == 2 ? k_occ_planes<2, 16384>
-                                                 : k_occ_planes<1, 32768>;
-            hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads), occ_plane_lds_bytes(p.lds_rows_occ, F),
-                               stream, p, shape.occ_groups);
-        } else {
-            dim3 grid((p.T + shape.occ_frames - 1) / shape.occ_frames, p.B);
-            hipLaunchKernelGGL(k_occ<Real>, grid, dim3(shape.occ_threads),
-                               occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b, p.lds_rows_occ, wide),
-                               stream, p, shape.occ_frames);
-        }
+    // bucket 0 (the longest sequences) first, on the caller's stream
+    for (int q = 0; q < bk.n; ++q) {
+        if (bk.count[q] <= 0) continue;
+        hipStream_t on = q == 0 ? stream : bk.streams[q];
+        if (q > 0 && (e = hipStreamWaitEvent(on, bk.fork, 0)) != hipSuccess) return e;
+        FbParams pq = p;
+        pq.seq_first = bk.first[q];
+        const int nb = bk.count[q];
+        hipEvent_t* evq = ev ? ev + 2 + 4 * q : nullptr;
+#define LFMMI_EVQ(i) \
+    if (evq) { e = hipEventRecord(evq[i], on); if (e != hipSuccess) return e; }
+        LFMMI_EVQ(0)
+        hipLaunchKernelGGL(rv->fn, dim3(2 * nb), dim3(rec_threads),
+                           shape.rec_nslot > 0
+                               ? reg_lds_bytes()
+                               : rec_lds_bytes(p.lds_rows, p.P, wide, shape.rec_yrep != 0),
+                           on, pq);
         if ((e = hipGetLastError()) != hipSuccess) return e;
+        LFMMI_EVQ(1)
+        hipLaunchKernelGGL(k_scan<Real>, dim3(nb), dim3(256), 0, on, pq);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        LFMMI_EVQ(2)
+        const int tq = std::min(bk.tmax[q], p.T);
+        if (tq > 0) {
+            if (!wide && shape.occ_multi > 0) {
+                const int F = shape.occ_multi;
+                const int per_wg = F * shape.occ_groups;
+                dim3 grid((tq + per_wg - 1) / per_wg, nb);
+                void (*fn)(FbParams, int) = F == 4   ? k_occ_planes<4, 8192>
+                                            : F == 2 ? k_occ_planes<2, 16384>
+                                                     : k_occ_planes<1, 32768>;
+                hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads),
+                                   occ_plane_lds_bytes(p.lds_rows_occ, F), on, pq,
+                                   shape.occ_groups);
+            } else {
+                dim3 grid((tq + shape.occ_frames - 1) / shape.occ_frames, nb);
+                hipLaunchKernelGGL(k_occ<Real>, grid, dim3(shape.occ_threads),
+                                   occ_lds_bytes(p.lds_rows_occ_a, p.lds_rows_occ_b,
+                                                 p.lds_rows_occ, wide),
+                                   on, pq, shape.occ_frames);
+            }
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        LFMMI_EVQ(3)
+#undef LFMMI_EVQ
+        if (q > 0 && (e = hipEventRecord(bk.join[q], on)) != hipSuccess) return e;
     }
-    LFMMI_EV(4)
+    for (int q = 1; q < bk.n; ++q)
+        if (bk.count[q] > 0 && (e = hipStreamWaitEvent(stream, bk.join[q], 0)) != hipSuccess)
+            return e;
 #undef LFMMI_EV
     return hipSuccess;
 }
 
 hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
-                                   hipStream_t stream, hipEvent_t* ev)
+                                   hipStream_t stream, hipEvent_t* ev, const Buckets& bk)
 {
-    return p.wide ? launch_typed<double>(p, shape, stream, ev)
-                  : launch_typed<float>(p, shape, stream, ev);
+    return p.wide ? launch_typed<double>(p, shape, stream, ev, bk)
+                  : launch_typed<float>(p, shape, stream, ev, bk);
 }
 
 }  // namespace lfmmi
