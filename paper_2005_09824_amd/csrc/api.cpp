@@ -68,6 +68,9 @@ struct lfmmi_graph {
     // workspace, grown on demand
     void* ws = nullptr;
     size_t ws_bytes = 0;
+    // lengths and T of the call whose descriptors the workspace holds (empty: none)
+    std::vector<int32_t> desc_lengths;
+    int32_t desc_T = -1;
     // pinned staging for per-call descriptors
     void* stage = nullptr;
     size_t stage_bytes = 0;
@@ -79,7 +82,7 @@ struct lfmmi_graph {
     hipEvent_t fork = nullptr;
     hipEvent_t join[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
 
-    // profiling: per call made while enabled 2 + 4 * (its bucket count) events
+    // profiling: per call made while enabled 4 * (its bucket count) events
     bool profile = false;
     std::vector<hipEvent_t> ev;
     std::vector<int32_t> ev_buckets;  // bucket count of each profiled call
@@ -521,6 +524,8 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     const size_t at_status = reserve<int32_t>(&total, B);
 
     if (total > h->ws_bytes) {
+        h->desc_lengths.clear();
+        h->desc_T = -1;
         if (h->ws) {
             (void)hipDeviceSynchronize();
             (void)hipFree(h->ws);
@@ -534,37 +539,47 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
         }
         h->ws_bytes = total;
     }
-    if (stage_need > h->stage_bytes) {
-        if (h->stage) {
-            if (h->stage_pending) (void)hipEventSynchronize(h->stage_done);
-            (void)hipHostFree(h->stage);
-            h->stage = nullptr;
-            h->stage_bytes = 0;
-        }
-        if ((e = hipHostMalloc(&h->stage, stage_need, hipHostMallocDefault)) != hipSuccess) {
-            h->stage = nullptr;
-            return fail(LFMMI_ERR_OOM, std::string("hipHostMalloc: ") + hipGetErrorString(e));
-        }
-        h->stage_bytes = stage_need;
-    }
-    if (!h->stage_done &&
-        (e = hipEventCreateWithFlags(&h->stage_done, hipEventDisableTiming)) != hipSuccess)
-        return fail_hip(e, "hipEventCreate");
-    if (h->stage_pending) {
-        // the previous call's descriptor copy must have left the staging buffer
-        if ((e = hipEventSynchronize(h->stage_done)) != hipSuccess)
-            return fail_hip(e, "hipEventSynchronize");
-        h->stage_pending = false;
-    }
-    unsigned char* st = static_cast<unsigned char*>(h->stage);
-    std::memcpy(st + at_seqs, seqs.data(), sizeof(SeqDesc) * B);
-    std::memcpy(st + at_order, order.data(), sizeof(int32_t) * 2 * B);
+    // descriptors depend on the lengths and T only: a call with the same ones as
+    // the last finds them on the device already
+    const bool same_desc = h->desc_T == T && (int32_t)h->desc_lengths.size() == B &&
+                           std::equal(h->desc_lengths.begin(), h->desc_lengths.end(), lengths);
     unsigned char* ws = static_cast<unsigned char*>(h->ws);
-    if ((e = hipMemcpyAsync(ws, st, stage_need, hipMemcpyHostToDevice, stream)) != hipSuccess)
-        return fail_hip(e, "hipMemcpyAsync");
-    if ((e = hipEventRecord(h->stage_done, stream)) != hipSuccess)
-        return fail_hip(e, "hipEventRecord");
-    h->stage_pending = true;
+    if (!same_desc) {
+        if (stage_need > h->stage_bytes) {
+            if (h->stage) {
+                if (h->stage_pending) (void)hipEventSynchronize(h->stage_done);
+                (void)hipHostFree(h->stage);
+                h->stage = nullptr;
+                h->stage_bytes = 0;
+            }
+            if ((e = hipHostMalloc(&h->stage, stage_need, hipHostMallocDefault)) != hipSuccess) {
+                h->stage = nullptr;
+                return fail(LFMMI_ERR_OOM, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+            }
+            h->stage_bytes = stage_need;
+        }
+        if (!h->stage_done &&
+            (e = hipEventCreateWithFlags(&h->stage_done, hipEventDisableTiming)) != hipSuccess)
+            return fail_hip(e, "hipEventCreate");
+        if (h->stage_pending) {
+            // the previous call's descriptor copy must have left the staging buffer
+            if ((e = hipEventSynchronize(h->stage_done)) != hipSuccess)
+                return fail_hip(e, "hipEventSynchronize");
+            h->stage_pending = false;
+        }
+        unsigned char* st = static_cast<unsigned char*>(h->stage);
+        std::memcpy(st + at_seqs, seqs.data(), sizeof(SeqDesc) * B);
+        std::memcpy(st + at_order, order.data(), sizeof(int32_t) * 2 * B);
+        h->desc_lengths.clear();
+        h->desc_T = -1;
+        if ((e = hipMemcpyAsync(ws, st, stage_need, hipMemcpyHostToDevice, stream)) != hipSuccess)
+            return fail_hip(e, "hipMemcpyAsync");
+        if ((e = hipEventRecord(h->stage_done, stream)) != hipSuccess)
+            return fail_hip(e, "hipEventRecord");
+        h->stage_pending = true;
+        h->desc_lengths.assign(lengths, lengths + B);
+        h->desc_T = T;
+    }
 
     FbParams p{};
     p.g = h->dg;
@@ -579,7 +594,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     p.cfac = ws + at_cfac;
     p.zfin = ws + at_zfin;
     p.wide = h->wide ? 1 : 0;
-    p.status_ws = reinterpret_cast<int32_t*>(ws + at_status);
+    p.done = reinterpret_cast<int32_t*>(ws + at_status);
     p.status_out = status;
     p.objf = objf;
     p.grad = grad;
@@ -651,7 +666,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
 
     hipEvent_t* ev = nullptr;
     if (h->profile) {
-        const size_t first = h->ev.size(), count = 2 + 4 * (size_t)bk.n;
+        const size_t first = h->ev.size(), count = 4 * (size_t)bk.n;
         h->ev.resize(first + count, nullptr);
         for (size_t i = first; i < first + count; ++i)
             if ((e = hipEventCreate(&h->ev[i])) != hipSuccess) {
@@ -748,20 +763,20 @@ lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4], int32_t* calls, int
     };
     size_t at = 0;
     for (size_t c = 0; c < n && st == LFMMI_OK; ++c) {
-        elapsed(at, at + 1, &sum[0]);
         for (int q = 0; q < h->ev_buckets[c] && st == LFMMI_OK; ++q) {
-            const size_t b0 = at + 2 + 4 * (size_t)q;
-            for (int i = 0; i < 3 && st == LFMMI_OK; ++i) elapsed(b0 + i, b0 + i + 1, &sum[1 + i]);
+            const size_t b0 = at + 4 * (size_t)q;
+            elapsed(b0, b0 + 1, &sum[0]);
+            elapsed(b0 + 1, b0 + 2, &sum[1]);
+            elapsed(b0 + 2, b0 + 3, &sum[3]);
             ++runs;
         }
-        at += 2 + 4 * (size_t)h->ev_buckets[c];
+        at += 4 * (size_t)h->ev_buckets[c];
     }
     for (hipEvent_t x : h->ev) (void)hipEventDestroy(x);
     h->ev.clear();
     h->ev_buckets.clear();
     if (st == LFMMI_OK) {
-        ms[0] = (float)(sum[0] / (double)n);
-        for (int i = 1; i < 4; ++i) ms[i] = (float)(sum[i] / (double)runs);
+        for (int i = 0; i < 4; ++i) ms[i] = (float)(sum[i] / (double)runs);
         if (launches) *launches = (int32_t)runs;
     }
     return st;

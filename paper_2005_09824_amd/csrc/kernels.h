@@ -62,7 +62,7 @@ struct FbParams {
     void* scal;             // [4][scal_total] per frame: alpha n, alpha s, beta n, beta s
     void* cfac;             // [scal_total] occupancy scale of frame t at scal_at + t
     void* zfin;             // [2][B] closing dot products (alpha side, beta side)
-    int32_t* status_ws;     // [B]
+    int32_t* done;          // [B] finished recursions of a sequence (0, 1, 2)
     int32_t* status_out;    // [B] or null
     float* objf;            // [B]
     float* grad;            // [B, T, P]
@@ -104,8 +104,7 @@ struct Buckets {
 };
 
 // Returns the first HIP error met (hipSuccess otherwise). ev, if non-null, holds
-// 2 + 4 * n events: around the emission kernel, then per bucket before, between
-// and after its three kernels.
+// 4 * n events: per bucket before, between and after its three kernels.
 hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
                                    hipStream_t stream, hipEvent_t* ev, const Buckets& bk);
 hipError_t configure_kernels();

@@ -1,13 +1,14 @@
 // HIP kernels (gfx950) of the batched LF-MMI forward-backward.
 //
-// Pipeline of one call (all on the caller's stream):
+// Pipeline of one call, per bucket of sequences (buckets run concurrently):
 //   k_emit  e_t[d] = exp(x_t[d] - max_d x_t[d]) for every valid frame, in parallel
 //   k_rec   one workgroup per (sequence, direction): the alpha recursion of
 //           Algorithm 1 and the mirrored beta recursion, time loop on device,
-//           the current vector in LDS, arcs streamed as sliced-ELL records,
-//           leaky-HMM mixing and per-frame rescaling fused, scaled trellis rows
-//           and per-frame normalisers spilled to HBM
-//   k_scan  fp64 prefix sums of the log normalisers: log Z, per-frame occupancy
+//           the current vector in LDS, arcs in registers or streamed as
+//           sliced-ELL records, leaky-HMM mixing and per-frame rescaling fused,
+//           scaled trellis rows and per-frame normalisers spilled to HBM; the
+//           workgroup that finishes a sequence second then runs the scan: fp64
+//           prefix sums of the log normalisers, log Z, per-frame occupancy
 //           scale, objective and status
 //   k_occ   pdf occupancies of Eq. 3 for every frame in parallel and the
 //           gradient write
@@ -53,7 +54,8 @@ __global__ void __launch_bounds__(256) k_emit(FbParams p)
 {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int b = blockIdx.y;
+    const int b = p.order[2 * (p.seq_first + blockIdx.y)] >> 1;
+    if (blockIdx.x == 0 && threadIdx.x == 0) p.done[b] = 0;  // see k_rec
     if (t >= p.T) return;
     const size_t at = ((size_t)b * p.T + t) * p.P;
     if (t >= p.seqs[b].T) {  // a padding frame: its gradient row is zero
@@ -724,6 +726,72 @@ struct RecRegs {
     }
 };
 
+// ---------------------------------------------------------------------------
+// Scales of one sequence, once both of its recursions are done:
+//   log Z_b = log(zfin) + sum_t log n_t (+ the frame maxima), and the factor that
+//   turns ahat_{t-1} * w * e_t * bhat_t into an occupancy,
+//   c_t = exp(A_{t-1} + B_t - log Z'),  A, B = prefix / suffix sums of log n,
+// in fp64. Called by every thread of a workgroup (at most 256 of them work);
+// scratch: 8 KB of LDS nobody else uses.
+// ---------------------------------------------------------------------------
+template <typename Real>
+__device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scratch_raw)
+{
+    double* sa = reinterpret_cast<double*>(scratch_raw);
+    double* sb = sa + 256;
+    double* sm = sb + 256;
+    double* tot = sm + 256;
+    const int tid = threadIdx.x;
+    const int workers = min((int)blockDim.x, 256);
+    const SeqDesc sd = p.seqs[b];
+    const int T = sd.T;
+    const int n = T + 1;
+    const Real* na = static_cast<const Real*>(p.scal) + sd.scal_at;
+    const Real* nb = static_cast<const Real*>(p.scal) + 2 * p.scal_total + sd.scal_at;
+    Real* cfac = static_cast<Real*>(p.cfac) + sd.scal_at;
+    const int chunk = (n + workers - 1) / workers;
+    const bool work = tid < workers;
+    const int i0 = work ? min(tid * chunk, n) : n, i1 = min(i0 + chunk, n);
+    double la = 0.0, lb = 0.0, lm = 0.0;
+    for (int i = i0; i < i1; ++i) {
+        la += log((double)na[i]);
+        lb += log((double)nb[i]);
+    }
+    if (work)
+        for (int t = tid; t < T; t += workers) lm += (double)p.rowmax[(size_t)b * p.T + t];
+    if (work) { sa[tid] = la; sb[tid] = lb; sm[tid] = lm; }
+    __syncthreads();
+    if (tid == 0) {
+        double ra = 0.0, rb = 0.0, rm = 0.0;
+        for (int i = 0; i < workers; ++i) {
+            const double xa = sa[i], xb = sb[i];
+            sa[i] = ra; sb[i] = rb;  // exclusive prefixes
+            ra += xa; rb += xb; rm += sm[i];
+        }
+        tot[0] = ra; tot[1] = rb; tot[2] = rm;
+    }
+    __syncthreads();
+    const double totB = tot[1], msum = tot[2];
+    const double lz = log((double)static_cast<const Real*>(p.zfin)[b]) + tot[0];
+    const bool nonfinite_in = !(msum == msum);
+    const bool dead = !(lz > -INFINITY && lz < INFINITY) || nonfinite_in;
+    double ra = work ? sa[tid] : 0.0, rb = work ? sb[tid] : 0.0;
+    for (int i = i0; i < i1; ++i) {
+        if (i >= 1) cfac[i] = dead ? (Real)0 : (Real)exp(ra + (totB - rb) - lz);
+        ra += log((double)na[i]);
+        rb += log((double)nb[i]);
+    }
+    if (tid == 0) {
+        int st = 0;
+        if (nonfinite_in) st |= 2;
+        if (dead) st |= 1;
+        const float val = nonfinite_in ? __builtin_nanf("") : (float)(lz + msum);
+        const float out = p.grad_scale * val;
+        p.objf[b] = p.accumulate ? p.objf[b] + out : out;
+        if (p.status_out) p.status_out[b] = p.accumulate ? (p.status_out[b] | st) : st;
+    }
+}
+
 template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT>
 __global__ void __launch_bounds__(NT) k_rec(FbParams p)
 {
@@ -738,66 +806,16 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     } else {
         rec_run<Real, YREP, HAS_WB, NT>(p, sd, od, b, dir, lds_raw);
     }
-}
-
-// ---------------------------------------------------------------------------
-// Scales: log Z_b = log(zfin) + sum_t log n_t (+ the frame maxima), and the
-// factor that turns ahat_{t-1} * w * e_t * bhat_t into an occupancy:
-//   c_t = exp(A_{t-1} + B_t - log Z'),  A, B = prefix / suffix sums of log n.
-// ---------------------------------------------------------------------------
-template <typename Real>
-__global__ void __launch_bounds__(256) k_scan(FbParams p)
-{
-    __shared__ double sa[256], sb[256], sm[256];
-    __shared__ double tot[3];
-    const int tid = threadIdx.x;
-    const int b = p.order[2 * (p.seq_first + blockIdx.x)] >> 1;
-    const SeqDesc sd = p.seqs[b];
-    const int T = sd.T;
-    const int n = T + 1;
-    const Real* na = static_cast<const Real*>(p.scal) + sd.scal_at;
-    const Real* nb = static_cast<const Real*>(p.scal) + 2 * p.scal_total + sd.scal_at;
-    Real* cfac = static_cast<Real*>(p.cfac) + sd.scal_at;
-    const int chunk = (n + 255) / 256;
-    const int i0 = min(tid * chunk, n), i1 = min(i0 + chunk, n);
-    double la = 0.0, lb = 0.0, lm = 0.0;
-    for (int i = i0; i < i1; ++i) {
-        la += log((double)na[i]);
-        lb += log((double)nb[i]);
-    }
-    for (int t = tid; t < T; t += 256) lm += (double)p.rowmax[(size_t)b * p.T + t];
-    sa[tid] = la; sb[tid] = lb; sm[tid] = lm;
+    // The workgroup that finishes a sequence second (alpha or beta) computes its
+    // scales: no launch of their own, and no wait for the other sequences.
+    __threadfence();   // this thread's trellis rows and scalars are visible device-wide
+    __syncthreads();   // ... and so are everybody's; LDS is free from here on
+    int* ticket = reinterpret_cast<int*>(lds_raw);
+    if (threadIdx.x == 0) *ticket = atomicAdd(p.done + b, 1);
     __syncthreads();
-    if (tid == 0) {
-        double ra = 0.0, rb = 0.0, rm = 0.0;
-        for (int i = 0; i < 256; ++i) {
-            const double xa = sa[i], xb = sb[i];
-            sa[i] = ra; sb[i] = rb;  // exclusive prefixes
-            ra += xa; rb += xb; rm += sm[i];
-        }
-        tot[0] = ra; tot[1] = rb; tot[2] = rm;
-    }
-    __syncthreads();
-    const double totB = tot[1], msum = tot[2];
-    const double lz = log((double)static_cast<const Real*>(p.zfin)[b]) + tot[0];
-    const bool nonfinite_in = !(msum == msum);
-    const bool dead = !(lz > -INFINITY && lz < INFINITY) || nonfinite_in;
-    double ra = sa[tid], rb = sb[tid];
-    for (int i = i0; i < i1; ++i) {
-        if (i >= 1) cfac[i] = dead ? (Real)0 : (Real)exp(ra + (totB - rb) - lz);
-        ra += log((double)na[i]);
-        rb += log((double)nb[i]);
-    }
-    if (tid == 0) {
-        int st = 0;
-        if (nonfinite_in) st |= 2;
-        if (dead) st |= 1;
-        const float val = nonfinite_in ? __builtin_nanf("") : (float)(lz + msum);
-        const float out = p.grad_scale * val;
-        p.objf[b] = p.accumulate ? p.objf[b] + out : out;
-        p.status_ws[b] = st;
-        if (p.status_out) p.status_out[b] = p.accumulate ? (p.status_out[b] | st) : st;
-    }
+    if (*ticket != 1) return;  // workgroup-uniform
+    __threadfence();           // read the other workgroup's results from memory
+    scan_sequence<Real>(p, b, lds_raw + 64);
 }
 
 // ---------------------------------------------------------------------------
@@ -1223,15 +1241,6 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     const RecVariant* rv =
         find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0);
     if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
-#define LFMMI_EV(i, on)                                               \
-    if (ev) { e = hipEventRecord(ev[i], on); if (e != hipSuccess) return e; }
-    LFMMI_EV(0, stream)
-    if (p.T > 0) {
-        dim3 grid((p.T + 3) / 4, p.B);
-        hipLaunchKernelGGL(k_emit, grid, dim3(256), 0, stream, p);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    LFMMI_EV(1, stream)
     if (bk.n > 1 && (e = hipEventRecord(bk.fork, stream)) != hipSuccess) return e;
 
     int rec_threads = shape.rec_threads;
@@ -1244,6 +1253,12 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         rec_threads = std::max(rec_threads, need);
         if (rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
     }
+    // at least the scan's scratch
+    const size_t rec_lds =
+        std::max<size_t>(shape.rec_nslot > 0
+                             ? reg_lds_bytes()
+                             : rec_lds_bytes(p.lds_rows, p.P, wide, shape.rec_yrep != 0),
+                         8192 + 64);
     // bucket 0 (the longest sequences) first, on the caller's stream
     for (int q = 0; q < bk.n; ++q) {
         if (bk.count[q] <= 0) continue;
@@ -1252,18 +1267,17 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         FbParams pq = p;
         pq.seq_first = bk.first[q];
         const int nb = bk.count[q];
-        hipEvent_t* evq = ev ? ev + 2 + 4 * q : nullptr;
+        hipEvent_t* evq = ev ? ev + 4 * q : nullptr;
 #define LFMMI_EVQ(i) \
     if (evq) { e = hipEventRecord(evq[i], on); if (e != hipSuccess) return e; }
         LFMMI_EVQ(0)
-        hipLaunchKernelGGL(rv->fn, dim3(2 * nb), dim3(rec_threads),
-                           shape.rec_nslot > 0
-                               ? reg_lds_bytes()
-                               : rec_lds_bytes(p.lds_rows, p.P, wide, shape.rec_yrep != 0),
-                           on, pq);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        {  // also when T == 0: it resets the per-sequence tickets of k_rec
+            dim3 grid(std::max(1, (p.T + 3) / 4), nb);
+            hipLaunchKernelGGL(k_emit, grid, dim3(256), 0, on, pq);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
         LFMMI_EVQ(1)
-        hipLaunchKernelGGL(k_scan<Real>, dim3(nb), dim3(256), 0, on, pq);
+        hipLaunchKernelGGL(rv->fn, dim3(2 * nb), dim3(rec_threads), rec_lds, on, pq);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         LFMMI_EVQ(2)
         const int tq = std::min(bk.tmax[q], p.T);
@@ -1294,7 +1308,6 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     for (int q = 1; q < bk.n; ++q)
         if (bk.count[q] > 0 && (e = hipStreamWaitEvent(stream, bk.join[q], 0)) != hipSuccess)
             return e;
-#undef LFMMI_EV
     return hipSuccess;
 }
 

@@ -98,6 +98,23 @@ def test_nonuniform_start_distribution_on_the_register_path():
     h.close()
 
 
+def test_concurrent_buckets_do_not_change_any_bit(monkeypatch):
+    # sequences are cut by length into buckets that run on streams of their own;
+    # every sequence is computed the same way whichever bucket it lands in
+    wl = workloads.make_workload(2, scale={"S": 400, "B": 13, "Tlo": 5, "Thi": 90}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    outs = []
+    for buckets in ("1", "2", "4"):
+        monkeypatch.setenv("LFMMI_BUCKETS", buckets)
+        outs.append(run_gpu(h, wl["logits"], wl["lengths"], wl["leak"]))
+    for o in outs[1:]:
+        assert np.array_equal(o[0], outs[0][0]) and np.array_equal(o[1], outs[0][1])
+        assert np.array_equal(o[2], outs[0][2])
+    lz, gamma = oracle.forward_backward(wl["den"], wl["logits"], wl["lengths"], wl["leak"])
+    check(*outs[-1], lz, gamma, "4 buckets")
+    h.close()
+
+
 def test_config5_scaled_full_loss():
     wl = workloads.make_workload(5, scale={"S": 400, "B": 6, "nlo": 5, "nhi": 25})
     den = binding.lfmmi_graph_create(wl["den"])
