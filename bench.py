@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes of the recursion kernel per step (all its launches), from rocprofv3 FETCH_SIZE /
 # WRITE_SIZE scaled by a plain copy of known size (profiles/hbm_traffic_wsj_mono_2k.txt); other
 # workloads: not measured
-REC_TRAFFIC_BYTES = {"wsj_mono_2k": 357.8e6}
+REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6}
 
 
 def main():
@@ -131,9 +131,11 @@ def main():
                      "traffic": (REC_TRAFFIC_BYTES[wl["name"]] / launches_per_call
                                  if wl["name"] in REC_TRAFFIC_BYTES else None),
                      "kernel_ms": kern["rec"], "launches_per_step": launches_per_call,
-                     "workgroups": 2 * B, "compute_units": 256,
-                     # the same against the LDS peak of the compute units a workgroup holds
-                     "frac_of_occupied_cus": achieved / (LDS_PEAK_GBPS * min(2 * B, 256) / 256.0),
+                     # a launch holds one compute unit per workgroup (the launches of a
+                     # step overlap on different ones): the same against their LDS peak
+                     "workgroups_per_launch": 2 * B / launches_per_call, "compute_units": 256,
+                     "frac_of_occupied_cus": achieved / (LDS_PEAK_GBPS *
+                                                         min(2 * B / launches_per_call, 256) / 256.0),
                      "hbm_frac": (REC_TRAFFIC_BYTES.get(wl["name"], 0.0) / launches_per_call
                                   / rec_s / 1e9) / HBM_PEAK_GBPS},
         "kernels_ms": {k: kern[k] for k in ("emit", "rec", "scan", "occ")},
