@@ -97,6 +97,23 @@ def main():
         print("bench.py: a sequence was flagged", file=sys.stderr)
         return 1
 
+    # For reference, outside the timed region: the same work with the whole batch
+    # as one bucket, i.e. one recursion launch over all 2B workgroups and nothing
+    # overlapping it. The library reads LFMMI_BUCKETS at every call.
+    os.environ["LFMMI_BUCKETS"] = "1"
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    binding.lfmmi_profile_enable(den, True)
+    t0 = time.perf_counter()
+    for _ in range(10):
+        step()
+    torch.cuda.synchronize()
+    one_dt = (time.perf_counter() - t0) / 10
+    one = binding.lfmmi_profile_read(den)
+    binding.lfmmi_profile_enable(den, False)
+    del os.environ["LFMMI_BUCKETS"]
+
     ms_per_step = dt / args.steps * 1e3
     fps = frames / (dt / args.steps)
 
@@ -137,7 +154,12 @@ def main():
                      "frac_of_occupied_cus": achieved / (LDS_PEAK_GBPS *
                                                          min(2 * B / launches_per_call, 256) / 256.0),
                      "hbm_frac": (REC_TRAFFIC_BYTES.get(wl["name"], 0.0) / launches_per_call
-                                  / rec_s / 1e9) / HBM_PEAK_GBPS},
+                                  / rec_s / 1e9) / HBM_PEAK_GBPS,
+                     # one launch for the whole batch (LFMMI_BUCKETS=1), not the timed path
+                     "one_launch": {"kernel_ms": one["rec"], "ms_per_step": one_dt * 1e3,
+                                    "achieved": frames * (16.0 * A + 24.0 * S) / (one["rec"] * 1e-3) / 1e9,
+                                    "frac": frames * (16.0 * A + 24.0 * S) / (one["rec"] * 1e-3) / 1e9
+                                            / LDS_PEAK_GBPS}},
         "kernels_ms": {k: kern[k] for k in ("emit", "rec", "scan", "occ")},
         "arc_updates_per_s": 2.0 * A * fps,
         "workspace_bytes": info["workspace_bytes"],
