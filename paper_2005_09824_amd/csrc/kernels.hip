@@ -537,7 +537,7 @@ struct RecRegs {
             const float t0 = wr[i] * e0;
             const float t1 = wr[i + 1] * e1;
             acc1 = fmaf(t0, x0, acc1);
-            acc2 = HAS_WB ? fmaf(wbr[i], e0, acc2) : acc2 + t0;
+            acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i : 0], e0, acc2) : acc2 + t0;
             acc1 = fmaf(t1, x1, acc1);
             acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i + 1 : 0], e1, acc2) : acc2 + t1;
             if (__builtin_expect(i + 1 == next_close, 0)) {  // wave-uniform: a slice ends
