@@ -175,10 +175,10 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         // for the register-resident kernel only: `registers_possible` rules it out
         // beforehand where it can, else streamed arcs are packed once more without.
         auto registers_possible = [&](int wv) {
-            if (h->wide) return false;
             if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return false;  // staging limits
             for (int32_t g = 0; g < n; ++g) {
-                if (state_off[g + 1] - state_off[g] > 8192) return false;  // fixed LDS map
+                // fixed LDS map: 32 KB per state vector
+                if (state_off[g + 1] - state_off[g] > (h->wide ? 4096 : 8192)) return false;
                 if ((double)(arc_off[g + 1] - arc_off[g]) / (64.0 * wv) > 48.0) return false;
             }
             return true;
@@ -210,14 +210,14 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             int max_slots = 0;
             bool even = registers_possible(waves);
             lfmmi_status st = pack_with(waves, even, &max_slots);
-            h->rec_nslot = even ? rec_register_slots(false, h->has_wb, max_slots, waves * kLanes) : 0;
+            h->rec_nslot = even ? rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes) : 0;
             if (st == LFMMI_OK && h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
                 registers_possible(waves / 2) &&
-                rec_register_slots(false, h->has_wb, 2 * max_slots, waves / 2 * kLanes) != 0) {
+                rec_register_slots(h->wide, h->has_wb, 2 * max_slots, waves / 2 * kLanes) != 0) {
                 waves /= 2;
                 even = true;
                 st = pack_with(waves, true, &max_slots);
-                h->rec_nslot = rec_register_slots(false, h->has_wb, max_slots, waves * kLanes);
+                h->rec_nslot = rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
             }
             if (st == LFMMI_OK && h->rec_nslot == 0 && even) st = pack_with(waves, false, &max_slots);
             if (st != LFMMI_OK) {

@@ -317,8 +317,19 @@ __device__ __forceinline__ float dpp_add(float v)
     return v + __int_as_float(moved);
 }
 
+// fp64: the two halves of the value travel separately
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double v)
+{
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xf, false);
+    return v + __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
 // After this every lane holds the sum over its row of 16 lanes.
-__device__ __forceinline__ float row16_allsum(float v)
+template <typename Real>
+__device__ __forceinline__ Real row16_allsum(Real v)
 {
     v = dpp_add<0xB1, 0xf>(v);   // quad_perm [1,0,3,2]
     v = dpp_add<0x4E, 0xf>(v);   // quad_perm [2,3,0,1]
@@ -327,13 +338,27 @@ __device__ __forceinline__ float row16_allsum(float v)
     return v;
 }
 
+// The value lane `l` holds, as a wave-uniform value.
+__device__ __forceinline__ float lane_value(float v, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ double lane_value(double v, int l)
+{
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)bits, l);
+    const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), l);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
 // Sum over the 64 lanes, returned as a wave-uniform value.
-__device__ __forceinline__ float wave_sum_uniform(float v)
+template <typename Real>
+__device__ __forceinline__ Real wave_sum_uniform(Real v)
 {
     v = row16_allsum(v);
     v = dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
     v = dpp_add<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    return lane_value(v, 63);
 }
 
 // Wave sums of a and b at once: a 32-lane swap puts a[l] + a[l + 32] in the lower
@@ -348,9 +373,21 @@ __device__ __forceinline__ float half_wave_sums(float a, float b)
     v = row16_allsum(v);
     return dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
 }
+__device__ __forceinline__ double half_wave_sums(double a, double b)
+{
+    const long long ab = __double_as_longlong(a), bb = __double_as_longlong(b);
+    const auto lo = __builtin_amdgcn_permlane32_swap((unsigned)ab, (unsigned)bb, false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap((unsigned)(ab >> 32), (unsigned)(bb >> 32),
+                                                     false, false);
+    double v = __longlong_as_double(((long long)hi[0] << 32) | lo[0]) +
+               __longlong_as_double(((long long)hi[1] << 32) | lo[1]);
+    v = row16_allsum(v);
+    return dpp_add<0x142, 0xa>(v);
+}
 
 // Lane 63 returns the sum over the wave (other lanes: partial sums).
-__device__ __forceinline__ float wave_sum_lane63(float v)
+template <typename Real>
+__device__ __forceinline__ Real wave_sum_lane63(Real v)
 {
     v = row16_allsum(v);
     v = dpp_add<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
@@ -358,8 +395,8 @@ __device__ __forceinline__ float wave_sum_lane63(float v)
 }
 
 // ---------------------------------------------------------------------------
-// The recursion with the wave's arc records in registers (fp32 graphs whose
-// waves own at most NSLOT slots). Fixed LDS map, so that the buffer of the
+// The recursion with the wave's arc records in registers (graphs whose waves
+// own at most NSLOT slots; state values fp32 or fp64). Fixed LDS map, so that the buffer of the
 // current parity is an immediate offset on every LDS instruction:
 //   [0, 32K) X0   [32K, 64K) X1   [64K, 96K) Y0   [96K, 128K) Y1   [128K, ...) partials
 // The last word of each Y buffer is 0: closing slots read it as their emission,
@@ -368,7 +405,7 @@ __device__ __forceinline__ float wave_sum_lane63(float v)
 constexpr uint32_t kRegX1 = 32768, kRegY0 = 65536, kRegY1 = 98304, kRegPart = 131072;
 constexpr uint32_t kRegYZero = 32764;  // byte offset of the zero word inside a Y buffer
 
-__host__ __device__ constexpr size_t reg_lds_bytes() { return kRegPart + 3 * 32 * sizeof(float); }
+__host__ __device__ constexpr size_t reg_lds_bytes() { return kRegPart + 3 * 32 * sizeof(double); }
 
 // LDS access by absolute byte address (the kernel's dynamic LDS starts at 0: it
 // declares no static LDS), so that the address register goes straight into the
@@ -382,6 +419,19 @@ __device__ __forceinline__ void lds_st(uint32_t addr, float v)
 {
     *reinterpret_cast<lds_float_t*>(static_cast<uintptr_t>(addr)) = v;
 }
+typedef __attribute__((address_space(3))) double lds_double_t;
+__device__ __forceinline__ void lds_st(uint32_t addr, double v)
+{
+    *reinterpret_cast<lds_double_t*>(static_cast<uintptr_t>(addr)) = v;
+}
+template <typename Real>
+__device__ __forceinline__ Real lds_ldr(uint32_t addr)
+{
+    if constexpr (sizeof(Real) == 8)
+        return *reinterpret_cast<const lds_double_t*>(static_cast<uintptr_t>(addr));
+    else
+        return *reinterpret_cast<const lds_float_t*>(static_cast<uintptr_t>(addr));
+}
 
 // Emission staging passes of the variant for workgroups of up to NT threads.
 __host__ __device__ constexpr int stage_passes(bool yrep, int nt)
@@ -389,16 +439,20 @@ __host__ __device__ constexpr int stage_passes(bool yrep, int nt)
     return yrep ? (nt >= 1024 ? 2 : (nt >= 768 ? 3 : 4)) : (nt >= 1024 ? 3 : (nt >= 768 ? 4 : 6));
 }
 
-template <bool YREP, bool HAS_WB, int NSLOT, int NT>
+template <typename Real, bool YREP, bool HAS_WB, int NSLOT, int NT>
 struct RecRegs {
+    static constexpr uint32_t kRB = sizeof(Real);  // bytes of a state value
     // Emission staging. Replicated rows (YREP): a thread writes four of the 32
     // copies of one value with one 16-byte store, kYPass passes of NT threads
     // cover 8 * P <= kYPass * NT quads. Plain rows: one value per thread and pass.
     static constexpr int kYPass = stage_passes(YREP, NT);
     static constexpr int kPrefetch = NT >= 1024 ? 2 : (NT >= 768 ? 4 : 6);
     static constexpr int kTailSlots = 4;
-    static constexpr int kStageAt = 4;  // slot before which a step does its global memory work
-    static_assert(kStageAt % 2 == 0 && kStageAt < NSLOT - kTailSlots, "every wave reaches it");
+    // slot before which a step does its global memory work; every wave must get
+    // there, also one that leaves the slot loop early
+    static constexpr int kStageAt = NSLOT - kTailSlots > 4 ? 4 : 0;
+    static_assert(kStageAt % 2 == 0 && (kStageAt == 0 || kStageAt < NSLOT - kTailSlots),
+                  "every wave reaches it");
     static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
 
     uint32_t xa[NSLOT];  // byte address of the state value inside X0
@@ -412,9 +466,9 @@ struct RecRegs {
 
     // per-step pointers, moved by one frame after every step
     const float* e2;  // emission row loaded during this step (used two steps on)
-    float* trow;      // trellis row written by this step
-    float* sN;        // where the scalars of the previous step go
-    float* sS;
+    Real* trow;       // trellis row written by this step
+    Real* sN;         // where the scalars of the previous step go
+    Real* sS;
     ptrdiff_t estep, tstep, sstep;
 
     __device__ __forceinline__ void load_y()
@@ -447,7 +501,7 @@ struct RecRegs {
 
     template <int PAR>
     __device__ __forceinline__ void step(const int k, const int T, const int tid, const int lane,
-                                         const float eps, const float aconst, const float bconst,
+                                         const Real eps, const Real aconst, const Real bconst,
                                          const uint64_t mask, const uint32_t row4_first,
                                          const uint32_t part_at, const int nsl)
     {
@@ -455,33 +509,37 @@ struct RecRegs {
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
         // Y addresses in ya[] are absolute addresses inside Y0; Y1 is 32 KB further
         constexpr uint32_t yc = PAR ? 0u : (kRegY1 - kRegY0), yn = PAR ? kRegY1 : kRegY0;
-        constexpr uint32_t pc = kRegPart + (PAR ? 0u : 128u), pn = kRegPart + (PAR ? 128u : 0u);
+        constexpr uint32_t pc = kRegPart + (PAR ? 0u : 32u * kRB), pn = kRegPart + (PAR ? 32u * kRB : 0u);
 
         // First the LDS reads this wave waits for: the partial sums of step k - 1
         // (lanes 0-15 fetch the n partials, 16-31 the s partials) and the first
         // gathers. The scalar chain below then runs while the gathers are in flight.
-        float pv = lds_ld(pc + (lane & (HAS_WB ? 31 : 15)) * 4);
-        float xv[kPrefetch ? kPrefetch : 1], ev[kPrefetch ? kPrefetch : 1];
+        Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
+        Real xv[kPrefetch ? kPrefetch : 1];
+        float ev[kPrefetch ? kPrefetch : 1];
 #pragma unroll
         for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
-            xv[i] = lds_ld(xc + xa[i]);
+            xv[i] = lds_ldr<Real>(xc + xa[i]);
             ev[i] = lds_ld(yc + ya[i]);
         }
         asm volatile("" ::: "memory");  // nothing else moves ahead of these reads
         // Without per-row leak-dot weights s is a_const * n.
         pv = row16_allsum(pv);
-        const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
-        const float Sd = HAS_WB ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16))
-                                : aconst * N;
-        float inv = 0.f;
-        if (N > 0.f) {
-            inv = __builtin_amdgcn_rcpf(N);
-            inv = fmaf(fmaf(-N, inv, 1.f), inv, inv);  // one Newton step
+        const Real N = lane_value(pv, 0);
+        const Real Sd = HAS_WB ? lane_value(pv, 16) : aconst * N;
+        Real inv = 0;
+        if (N > 0) {
+            if constexpr (sizeof(Real) == 4) {
+                inv = __builtin_amdgcn_rcpf(N);
+                inv = fmaf(fmaf(-N, inv, 1.f), inv, inv);  // one Newton step
+            } else {
+                inv = (Real)1 / N;
+            }
         }
-        const float c = eps * Sd * inv;
-        const float cb = HAS_WB ? c : c * bconst;
+        const Real c = eps * Sd * inv;
+        const Real cb = HAS_WB ? c : c * bconst;
 
-        float acc1 = 0.f, acc2 = 0.f, n = 0.f, s = 0.f;
+        Real acc1 = 0, acc2 = 0, n = 0, s = 0;
         uint64_t left = mask;
         int next_close = left ? __builtin_ctzll(left) : 64;
         uint32_t row4 = row4_first;  // byte offset of this lane's row in a state vector
@@ -515,40 +573,48 @@ struct RecRegs {
                     *sS = Sd;
                 }
             }
-            float x0, e0, x1, e1;
+            Real x0, x1;
+            float e0, e1;
             if constexpr (kPrefetch == 0) {
-                x0 = lds_ld(xc + xa[i]); e0 = lds_ld(yc + ya[i]);
-                x1 = lds_ld(xc + xa[i + 1]); e1 = lds_ld(yc + ya[i + 1]);
+                x0 = lds_ldr<Real>(xc + xa[i]); e0 = lds_ld(yc + ya[i]);
+                x1 = lds_ldr<Real>(xc + xa[i + 1]); e1 = lds_ld(yc + ya[i + 1]);
             } else {
                 x0 = xv[i % (kPrefetch ? kPrefetch : 1)]; e0 = ev[i % (kPrefetch ? kPrefetch : 1)];
                 x1 = xv[(i + 1) % (kPrefetch ? kPrefetch : 1)]; e1 = ev[(i + 1) % (kPrefetch ? kPrefetch : 1)];
             }
             if (kPrefetch > 0 && i + kPrefetch < NSLOT) {
                 constexpr int kp = kPrefetch ? kPrefetch : 1;
-                xv[i % kp] = lds_ld(xc + xa[(i + kp) % NSLOT]);
+                xv[i % kp] = lds_ldr<Real>(xc + xa[(i + kp) % NSLOT]);
                 ev[i % kp] = lds_ld(yc + ya[(i + kp) % NSLOT]);
-                xv[(i + 1) % kp] = lds_ld(xc + xa[(i + 1 + kp) % NSLOT]);
+                xv[(i + 1) % kp] = lds_ldr<Real>(xc + xa[(i + 1 + kp) % NSLOT]);
                 ev[(i + 1) % kp] = lds_ld(yc + ya[(i + 1 + kp) % NSLOT]);
             }
             // one wait for the pair: this names the value loaded last, so the first
             // use of any of the four comes after all of them have arrived
-            asm volatile("" : "+v"(x0), "+v"(e0) : "v"(x1), "v"(e1));
+            asm volatile("" : "+v"(x0), "+v"(e0) : "v"(x1), "v"(e1));  // (fp64: register pairs)
             // arc slots; closing and padding slots see e == 0 or w == 0 and add nothing
             const float t0 = wr[i] * e0;
             const float t1 = wr[i + 1] * e1;
-            acc1 = fmaf(t0, x0, acc1);
-            acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i : 0], e0, acc2) : acc2 + t0;
-            acc1 = fmaf(t1, x1, acc1);
-            acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i + 1 : 0], e1, acc2) : acc2 + t1;
+            if constexpr (sizeof(Real) == 4) {
+                acc1 = fmaf(t0, x0, acc1);
+                acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i : 0], e0, acc2) : acc2 + t0;
+                acc1 = fmaf(t1, x1, acc1);
+                acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i + 1 : 0], e1, acc2) : acc2 + t1;
+            } else {  // products of the arc weight and the emission stay fp32
+                acc1 += (Real)t0 * x0;
+                acc2 += HAS_WB ? (Real)(wbr[HAS_WB ? i : 0] * e0) : (Real)t0;
+                acc1 += (Real)t1 * x1;
+                acc2 += HAS_WB ? (Real)(wbr[HAS_WB ? i + 1 : 0] * e1) : (Real)t1;
+            }
             if (__builtin_expect(i + 1 == next_close, 0)) {  // wave-uniform: a slice ends
-                const float v = fmaf(inv, acc1, cb * acc2);
+                const Real v = inv * acc1 + cb * acc2;
                 lds_st(xn + row4, v);
-                *reinterpret_cast<float*>(tr + row4) = v;
+                *reinterpret_cast<Real*>(tr + row4) = v;
                 n += v;
-                if (HAS_WB) s = fmaf(wr[i + 1], v, s);  // the closing slot's w is a[row]
-                acc1 = 0.f;
-                acc2 = 0.f;
-                row4 += 256;
+                if (HAS_WB) s += (Real)wr[i + 1] * v;  // the closing slot's w is a[row]
+                acc1 = 0;
+                acc2 = 0;
+                row4 += 64 * kRB;
                 left &= left - 1;
                 next_close = left ? __builtin_ctzll(left) : 64;
             }
@@ -556,10 +622,10 @@ struct RecRegs {
         __builtin_amdgcn_s_setprio(3);  // the serial end of this step and start of the next
         if constexpr (HAS_WB) {
             // both wave sums in one reduction: lane 31 ends up with n, lane 63 with s
-            const float ns = half_wave_sums(n, s);
+            const Real ns = half_wave_sums(n, s);
             if ((lane & 31) == 31) lds_st(pn + part_at, ns);
         } else {
-            const float ns = wave_sum_lane63(n);
+            const Real ns = wave_sum_lane63(n);
             if (lane == 63) lds_st(pn + part_at, ns);
         }
         if (k + 2 < T) e2 += estep;
@@ -579,16 +645,16 @@ struct RecRegs {
         const int T = sd.T;
         const int P = p.P;
         const int rows = od.num_slices * 64;
-        float* trel = static_cast<float*>(dir == 0 ? p.alpha : p.beta) +
-                      (dir == 0 ? sd.alpha_at : sd.beta_at);
-        float* scalN = static_cast<float*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
-        float* scalS = scalN + p.scal_total;
+        Real* trel = static_cast<Real*>(dir == 0 ? p.alpha : p.beta) +
+                     (dir == 0 ? sd.alpha_at : sd.beta_at);
+        Real* scalN = static_cast<Real*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
+        Real* scalS = scalN + p.scal_total;
         const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
         const float* wbp = p.g.wb + (size_t)od.rec_at * 64 + lane;
         const int32_t* so = p.g.slice_off + od.slice_off_at;
-        const float eps = p.leak;
-        const float aconst = od.a_const;
-        const float bconst = od.b_const;
+        const Real eps = (Real)p.leak;
+        const Real aconst = (Real)od.a_const;
+        const Real bconst = (Real)od.b_const;
         const float* erows = p.emis + (size_t)b * p.T * P;  // this sequence's emission rows
 
         int s0 = 0, s1 = 0;
@@ -605,7 +671,7 @@ struct RecRegs {
             const bool on = i < nsl;
             const bool closing = HAS_WB && ((mask >> i) & 1);  // holds a[row], no arc
             const uint2 r = on ? recs[(size_t)(first + i) * 64] : make_uint2(0u, 0u);
-            xa[i] = r.x & 0xffffu;
+            xa[i] = (r.x & 0xffffu) * (kRB / 4u);
             ya[i] = kRegY0 +
                     ((on && !closing)
                          ? (YREP ? (r.x >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (r.x >> 16))
@@ -635,26 +701,26 @@ struct RecRegs {
             lds_st(kRegY0 + kRegYZero, 0.f);
             lds_st(kRegY1 + kRegYZero, 0.f);
         }
-        if (tid < 64) lds_st(kRegPart + tid * 4, 0.f);
+        if (tid < 64) lds_st(kRegPart + tid * kRB, (Real)0);
         __syncthreads();
 
         // ---- step 0: v_0 = init into X0, partials into slot set 0
         {
-            float n = 0.f, s = 0.f;
+            Real n = 0, s = 0;
             const int ti = dir == 0 ? 0 : T;
             for (int sl = s0; sl < s1; ++sl) {
                 const int row = sl * 64 + lane;
-                const float v = p.g.vinit[od.vec_at + row];
-                lds_st(row * 4, v);
+                const Real v = (Real)p.g.vinit[od.vec_at + row];
+                lds_st(row * kRB, v);
                 trel[(size_t)ti * rows + row] = v;
                 n += v;
-                s = fmaf(p.g.va[od.vec_at + row], v, s);
+                s += (Real)p.g.va[od.vec_at + row] * v;
             }
             n = wave_sum_uniform(n);
             s = wave_sum_uniform(s);
             if (lane == 0) {
-                lds_st(kRegPart + wave * 4, n);
-                lds_st(kRegPart + 64 + wave * 4, s);
+                lds_st(kRegPart + wave * kRB, n);
+                lds_st(kRegPart + (16 + wave) * kRB, s);
             }
             // rows of steps 1 (into Y0 now) and 2 (into registers); frame of step k:
             // FWD k - 1, BWD T - k, kept inside the sequence when T is short
@@ -679,9 +745,9 @@ struct RecRegs {
         sN = scalN + (dir == 0 ? 0 : T);                      // and the scalars of step 0
         sS = scalS + (dir == 0 ? 0 : T);
 
-        const uint32_t row4_first = (uint32_t)(s0 * 64 + lane) * 4u;
-        // where this lane's end-of-step sum goes: n of wave w at word w, s at 16 + w
-        const uint32_t part_at = (uint32_t)wave * 4u + (HAS_WB && lane >= 32 ? 64u : 0u);
+        const uint32_t row4_first = (uint32_t)(s0 * 64 + lane) * kRB;
+        // where this lane's end-of-step sum goes: n of wave w at value w, s at 16 + w
+        const uint32_t part_at = ((uint32_t)wave + (HAS_WB && lane >= 32 ? 16u : 0u)) * kRB;
         int k = 1;
         for (; k + 1 <= T; k += 2) {
             step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
@@ -692,35 +758,34 @@ struct RecRegs {
         // ---- last scalars and the closing dot product
         {
             const uint32_t xc = (T & 1) ? kRegX1 : 0u;
-            const uint32_t pc = kRegPart + ((T & 1) ? 128u : 0u);
-            float pv = lds_ld(pc + (lane & (HAS_WB ? 31 : 15)) * 4);
+            const uint32_t pc = kRegPart + ((T & 1) ? 32u * kRB : 0u);
+            Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
             pv = row16_allsum(pv);
-            const float N = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 0));
-            const float Sd =
-                HAS_WB ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pv), 16)) : aconst * N;
-            const float inv = N > 0.f ? 1.f / N : 0.f;
-            const float c = eps * Sd * inv;
+            const Real N = lane_value(pv, 0);
+            const Real Sd = HAS_WB ? lane_value(pv, 16) : aconst * N;
+            const Real inv = N > 0 ? (Real)1 / N : (Real)0;
+            const Real c = eps * Sd * inv;
             if (tid == 0) {
                 const int tp = dir == 0 ? T : 0;
                 scalN[tp] = N;
                 scalS[tp] = Sd;
             }
-            float z = 0.f;
+            Real z = 0;
             for (int sl = s0; sl < s1; ++sl) {
                 const int row = sl * 64 + lane;
-                const float v = fmaf(lds_ld(xc + row * 4), inv,
-                                     c * p.g.vb[od.vec_at + row]);
-                z = fmaf(p.g.vfin[od.vec_at + row], v, z);
+                const Real v = lds_ldr<Real>(xc + row * kRB) * inv +
+                               c * (Real)p.g.vb[od.vec_at + row];
+                z += (Real)p.g.vfin[od.vec_at + row] * v;
             }
             z = wave_sum_uniform(z);
             __syncthreads();  // every wave has read the partials
-            if (lane == 0) lds_st(kRegPart + 256 + wave * 4, z);
+            if (lane == 0) lds_st(kRegPart + (64 + wave) * kRB, z);
             __syncthreads();
             if (tid == 0) {
-                float Z = 0.f;
+                Real Z = 0;
                 for (int w = 0; w < (nthreads >> 6); ++w)
-                    Z += lds_ld(kRegPart + 256 + w * 4);
-                static_cast<float*>(p.zfin)[(size_t)dir * p.B + b] = Z;
+                    Z += lds_ldr<Real>(kRegPart + (64 + w) * kRB);
+                static_cast<Real*>(p.zfin)[(size_t)dir * p.B + b] = Z;
             }
         }
     }
@@ -801,7 +866,7 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
     if constexpr (NSLOT > 0) {
-        RecRegs<YREP, HAS_WB, NSLOT, NT> r;
+        RecRegs<Real, YREP, HAS_WB, NSLOT, NT> r;
         r.run(p, sd, od, b, dir, lds_raw);
     } else {
         rec_run<Real, YREP, HAS_WB, NT>(p, sd, od, b, dir, lds_raw);
@@ -1150,6 +1215,10 @@ const RecVariant kRecVariants[] = {
     // register-resident arcs, 8 waves (256 VGPRs per lane)
     LFMMI_REC(float, 0, 32, 0, 512), LFMMI_REC(float, 0, 48, 0, 512),
     LFMMI_REC(float, 0, 32, 1, 512), LFMMI_REC(float, 0, 48, 1, 512),
+    // fp64 state vectors (graphs with non-final states: numerators are small)
+    LFMMI_REC(double, 1, 8, 1, 1024), LFMMI_REC(double, 1, 16, 1, 1024),
+    LFMMI_REC(double, 1, 32, 1, 512),
+    LFMMI_REC(double, 1, 16, 0, 1024), LFMMI_REC(double, 1, 32, 0, 512),
 };
 #undef LFMMI_REC
 
