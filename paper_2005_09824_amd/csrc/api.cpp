@@ -186,8 +186,11 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         auto pack_with = [&](int wv, bool even, int* max_slots) -> lfmmi_status {
             tune.even_slices = even;
             h->rec_waves = wv;
-            // the occupancy pass is throughput work: at most 8 waves
-            h->occ_waves = std::min(wv, env_int("LFMMI_OCC_WAVES", 8));
+            // the occupancy pass is throughput work: about 8 arcs per lane, at most 8 waves
+            int64_t most_arcs = 0;
+            for (int32_t g = 0; g < n; ++g) most_arcs = std::max(most_arcs, arc_off[g + 1] - arc_off[g]);
+            const int by_arcs = (int)std::max<int64_t>(1, (most_arcs + 511) / 512);
+            h->occ_waves = std::min(by_arcs, env_int("LFMMI_OCC_WAVES", 8));
             h->packed.assign(n, PackedGraph());
             h->max_rows_f = h->max_rows_b = h->max_rows_occ = 0;
             *max_slots = 0;

@@ -487,9 +487,9 @@ int64_t gather_cycles(const Ordering& o, bool count_y)
 
 int choose_waves(int64_t num_arcs, int32_t num_states)
 {
-    // about 8 arc slots per lane before a further wave pays for its share of
+    // about 2 arc slots per lane before a further wave pays for its share of
     // the per-frame barriers; never more waves than slices of states
-    int64_t by_arcs = (num_arcs + (int64_t)kLanes * 8 - 1) / ((int64_t)kLanes * 8);
+    int64_t by_arcs = (num_arcs + (int64_t)kLanes * 2 - 1) / ((int64_t)kLanes * 2);
     int64_t slices = (num_states + kLanes - 1) / kLanes;
     int64_t w = std::max<int64_t>(1, std::min<int64_t>(by_arcs, slices));
     return (int)std::min<int64_t>(w, kMaxWaves);
