@@ -254,3 +254,22 @@ def test_config5_full_size_num_all_den_sampled():
     assert np.all(np.abs(objf[idx] - (lz_n[idx] - lz_d)) <= tol)
     assert np.abs(grad[idx] - (g_n[idx] - g_d)).max() <= GRAD_ATOL
     den.close(); num.close()
+
+
+def test_autograd_wrapper_gives_the_objective_and_its_gradient():
+    torch = _torch()
+    from paper_2005_09824_amd import chain
+    wl = workloads.make_workload(5, scale={"S": 300, "B": 5, "nlo": 4, "nhi": 12})
+    den = binding.lfmmi_graph_create(wl["den"])
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    x = torch.from_numpy(wl["logits"]).cuda().requires_grad_(True)
+    loss = chain.chain_loss(x, wl["lengths"], num, den, wl["leak"])
+    loss.backward()
+    torch.cuda.synchronize()
+    want_objf, want_grad, lz_n, lz_d = oracle.loss(wl["num"], wl["den"], wl["logits"],
+                                                   wl["lengths"], wl["leak"])
+    frames = float(wl["lengths"].sum())
+    tol = 1e-4 * np.maximum(np.maximum(np.abs(lz_n), np.abs(lz_d)), 1.0).sum() / frames
+    assert abs(float(loss.item()) - (-want_objf.sum() / frames)) <= tol
+    assert np.abs(x.grad.cpu().numpy().astype(np.float64) * (-frames) - want_grad).max() <= GRAD_ATOL
+    den.close(); num.close()
