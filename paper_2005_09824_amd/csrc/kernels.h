@@ -114,6 +114,6 @@ size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
 int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
 size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide);
 int occ_plane_frames(int rows, int occ_rows);
-size_t occ_plane_lds_bytes(int occ_rows, int frames);
+size_t occ_plane_lds_bytes(int rows, int occ_rows, int frames);
 
 }  // namespace lfmmi

@@ -1000,7 +1000,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 template <int F, int STRIDE>
 __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_wg)
 {
-    static_assert(2 * F * STRIDE <= 65536, "plane offsets must fit the ds immediate");
+    static_assert((2 * F - 1) * STRIDE <= 65535, "plane offsets must fit the ds immediate");
     constexpr uint32_t kRowSum = 2u * F * STRIDE;
     constexpr int kPre = 8;  // row positions a thread fetches ahead of the gathers
     const int tid = threadIdx.x;
@@ -1265,7 +1265,8 @@ hipError_t configure_kernels()
                          reinterpret_cast<const void*>(k_occ<double>),
                          reinterpret_cast<const void*>(k_occ_planes<4, 8192>),
                          reinterpret_cast<const void*>(k_occ_planes<2, 16384>),
-                         reinterpret_cast<const void*>(k_occ_planes<1, 32768>)};
+                         reinterpret_cast<const void*>(k_occ_planes<1, 32768>),
+                         reinterpret_cast<const void*>(k_occ_planes<1, 49152>)};
     for (const void* f : fns) {
         hipError_t e =
             hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -1287,18 +1288,27 @@ size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide)
     return ((size_t)rows_a + rows_b + occ_rows) * (wide ? 8 : 4);
 }
 
+// Bytes between the planes of the plane-layout occupancy kernel for this many
+// state rows and frames per record (one frame: a wider plane for large graphs).
+static int occ_plane_stride(int rows, int frames)
+{
+    return frames == 1 && rows * 4 > 32768 ? 49152 : 32768 / frames;
+}
+
 // Frames per record of the plane-layout occupancy kernel for this many state
 // rows and OCC rows (0: they do not fit its LDS map).
 int occ_plane_frames(int rows, int occ_rows)
 {
     for (int f : {4, 2, 1})
-        if (rows * 4 <= 32768 / f && occ_plane_lds_bytes(occ_rows, f) <= 160 * 1024) return f;
+        if (rows * 4 <= (f == 1 ? 49152 : 32768 / f) &&
+            occ_plane_lds_bytes(rows, occ_rows, f) <= 160 * 1024)
+            return f;
     return 0;
 }
 
-size_t occ_plane_lds_bytes(int occ_rows, int frames)
+size_t occ_plane_lds_bytes(int rows, int occ_rows, int frames)
 {
-    return 65536 + (size_t)frames * occ_rows * 4;
+    return 2 * (size_t)frames * occ_plane_stride(rows, frames) + (size_t)frames * occ_rows * 4;
 }
 
 template <typename Real>
@@ -1355,11 +1365,13 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
                 const int F = shape.occ_multi;
                 const int per_wg = F * shape.occ_groups;
                 dim3 grid((tq + per_wg - 1) / per_wg, nb);
-                void (*fn)(FbParams, int) = F == 4   ? k_occ_planes<4, 8192>
-                                            : F == 2 ? k_occ_planes<2, 16384>
-                                                     : k_occ_planes<1, 32768>;
+                void (*fn)(FbParams, int) =
+                    F == 4   ? k_occ_planes<4, 8192>
+                    : F == 2 ? k_occ_planes<2, 16384>
+                    : occ_plane_stride(p.lds_rows, 1) == 32768 ? k_occ_planes<1, 32768>
+                                                               : k_occ_planes<1, 49152>;
                 hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads),
-                                   occ_plane_lds_bytes(p.lds_rows_occ, F), on, pq,
+                                   occ_plane_lds_bytes(p.lds_rows, p.lds_rows_occ, F), on, pq,
                                    shape.occ_groups);
             } else {
                 dim3 grid((tq + shape.occ_frames - 1) / shape.occ_frames, nb);
