@@ -19,7 +19,8 @@ struct OrdDesc {
     int32_t mask_at;        // FWD/BWD: first entry in wave_mask (num_waves entries)
     int32_t has_wb;         // FWD: the leak target differs per state
     float b_const;          // the leak target when it is one constant
-    int32_t pdf_first_at;   // OCC: first entry in pdf_first (num_pdfs + 1 entries)
+    int32_t pdf_first_at;   // OCC: first entry in pdf_first (num_pdfs + 1 offsets, then the
+                            // heavy-pdf list: count, row limit, pdf-ids)
     int32_t closing;        // FWD/BWD: slices end in a slot that holds the row's leak-dot weight
     float a_const;          // that weight when it is one constant (no closing slots)
 };
@@ -81,6 +82,7 @@ struct LaunchShape {
     int rec_nslot;     // arc slots held in registers per lane (0: streamed)
     int rec_yrep;      // emission row replicated across LDS banks
     int rec_has_wb;    // arcs carry a per-arc leak factor
+    int rec_hybrid;    // only the leading slices of a wave are register-resident
     int occ_threads;   // workgroup size of the occupancy kernel
     int occ_frames;    // frames per occupancy workgroup (frame-at-a-time kernel)
     int occ_multi;     // frames per record of the plane-layout occupancy kernel (0: not used)
@@ -112,6 +114,9 @@ hipError_t configure_kernels();
 size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
 // Register-resident slot count the recursion kernel offers for this shape (0: none).
 int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
+// Slots of the hybrid variant (a wave's leading slices in registers, the others
+// streamed) for this kind of graph, 0 if there is none.
+int rec_hybrid_slots(bool wide, bool has_wb);
 size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide);
 int occ_plane_frames(int rows, int occ_rows);
 size_t occ_plane_lds_bytes(int rows, int occ_rows, int frames);

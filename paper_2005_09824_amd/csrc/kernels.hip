@@ -439,8 +439,12 @@ __host__ __device__ constexpr int stage_passes(bool yrep, int nt)
     return yrep ? (nt >= 1024 ? 2 : (nt >= 768 ? 3 : 4)) : (nt >= 1024 ? 3 : (nt >= 768 ? 4 : 6));
 }
 
-template <typename Real, bool YREP, bool HAS_WB, int NSLOT, int NT>
+// HYBRID: a wave keeps in registers only the first of its slices that fit NSLOT
+// slots and streams the records of the others from L2 every frame (graphs too
+// large for the registers: less record traffic than streaming everything).
+template <typename Real, bool YREP, bool HAS_WB, int NSLOT, int NT, bool HYBRID = false>
 struct RecRegs {
+    static_assert(!HYBRID || (!HAS_WB && sizeof(Real) == 4), "hybrid: fp32, constant leak weights");
     static constexpr uint32_t kRB = sizeof(Real);  // bytes of a state value
     // Emission staging. Replicated rows (YREP): a thread writes four of the 32
     // copies of one value with one 16-byte store, kYPass passes of NT threads
@@ -503,7 +507,10 @@ struct RecRegs {
     __device__ __forceinline__ void step(const int k, const int T, const int tid, const int lane,
                                          const Real eps, const Real aconst, const Real bconst,
                                          const uint64_t mask, const uint32_t row4_first,
-                                         const uint32_t part_at, const int nsl)
+                                         const uint32_t part_at, const int nsl,
+                                         const int sl_stream, const int sl_end,
+                                         const int first_streamed, const int32_t* so,
+                                         const uint2* recs)
     {
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
@@ -619,6 +626,42 @@ struct RecRegs {
                 next_close = left ? __builtin_ctzll(left) : 64;
             }
         }
+        if constexpr (HYBRID) {
+            // the wave's other slices: records from L2, four (then two) slots at a time
+            // (the first of them may have begun in the registers: acc1, acc2)
+            const int lane_y = (lane & 31) * 4;
+            int i = first_streamed;
+            const uint2* rp = recs + (size_t)i * 64;
+            Real a1 = acc1, a2 = acc2;
+            for (int sl = sl_stream; sl < sl_end; ++sl) {
+                const int o1 = so[sl + 1];
+                auto slot = [&](const uint2 r) {
+                    const uint32_t ykey = r.x >> 16;
+                    const float e = lds_ld(yc + kRegY0 + (YREP ? ykey * 32u + (uint32_t)lane_y : ykey));
+                    const Real x = lds_ldr<Real>(xc + (r.x & 0xffffu));
+                    const float t = __uint_as_float(r.y) * e;
+                    a1 = fmaf(t, x, a1);
+                    a2 += t;
+                };
+                for (; i + 4 <= o1; i += 4) {
+                    const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
+                    rp += 256;
+                    slot(r0); slot(r1); slot(r2); slot(r3);
+                }
+                for (; i < o1; i += 2) {  // widths are even
+                    const uint2 r0 = rp[0], r1 = rp[64];
+                    rp += 128;
+                    slot(r0); slot(r1);
+                }
+                const Real v = inv * a1 + cb * a2;
+                const uint32_t at = (uint32_t)(sl * 64 + lane) * kRB;
+                lds_st(xn + at, v);
+                *reinterpret_cast<Real*>(tr + at) = v;
+                n += v;
+                a1 = 0;
+                a2 = 0;
+            }
+        }
         __builtin_amdgcn_s_setprio(3);  // the serial end of this step and start of the next
         if constexpr (HAS_WB) {
             // both wave sums in one reduction: lane 31 ends up with n, lane 63 with s
@@ -665,7 +708,19 @@ struct RecRegs {
             mask = p.g.wave_mask[od.mask_at + wave];
         }
         const int first = so[s0];
-        const int nsl = so[s1] - first;
+        int sl_stream = s1;  // first slice with streamed records
+        int nsl = so[s1] - first;
+        if constexpr (HYBRID) {
+            // resident: the wave's first NSLOT slots; the slices that end there make
+            // the mask, the one that straddles the limit is finished from L2
+            nsl = min(nsl, NSLOT);
+            mask = 0;
+            sl_stream = s0;
+            while (sl_stream < s1 && so[sl_stream + 1] - first <= nsl) {
+                mask |= (uint64_t)1 << (so[sl_stream + 1] - 1 - first);
+                ++sl_stream;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
             const bool on = i < nsl;
@@ -750,10 +805,13 @@ struct RecRegs {
         const uint32_t part_at = ((uint32_t)wave + (HAS_WB && lane >= 32 ? 16u : 0u)) * kRB;
         int k = 1;
         for (; k + 1 <= T; k += 2) {
-            step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
-            step<0>(k + 1, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
+            step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl, sl_stream, s1,
+                    first + nsl, so, recs);
+            step<0>(k + 1, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl, sl_stream, s1,
+                    first + nsl, so, recs);
         }
-        if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl);
+        if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl, sl_stream, s1,
+                    first + nsl, so, recs);
 
         // ---- last scalars and the closing dot product
         {
@@ -857,7 +915,7 @@ __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scr
     }
 }
 
-template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT>
+template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT, bool HYBRID = false>
 __global__ void __launch_bounds__(NT) k_rec(FbParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -866,7 +924,7 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
     if constexpr (NSLOT > 0) {
-        RecRegs<Real, YREP, HAS_WB, NSLOT, NT> r;
+        RecRegs<Real, YREP, HAS_WB, NSLOT, NT, HYBRID> r;
         r.run(p, sd, od, b, dir, lds_raw);
     } else {
         rec_run<Real, YREP, HAS_WB, NT>(p, sd, od, b, dir, lds_raw);
@@ -921,6 +979,9 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
     const int32_t* pdf_rows = p.g.pdf_rows + od.vec_at;
+    // pdfs with more than heavy_rows rows: their row sums are added by a whole wave
+    const int heavy_n = pdf_first[P + 1], heavy_rows = pdf_first[P + 2];
+    const int32_t* heavy = pdf_first + P + 3;
     const Real* cfac = static_cast<const Real*>(p.cfac) + sd.scal_at;
     const Real* scal = static_cast<const Real*>(p.scal) + sd.scal_at;
     const float* vb_f = p.g.vb + p.g.ords[sd.graph * 3 + 0].vec_at;
@@ -976,10 +1037,23 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
         const Real scale = (Real)p.grad_scale * c;
         const float* e = p.emis + at;
         for (int d = tid; d < P; d += nthreads) {
+            const int r0 = pdf_first[d], r1 = pdf_first[d + 1];
+            if (r1 - r0 > heavy_rows) continue;  // a wave adds these up, below
             Real sum = 0;
-            for (int r = pdf_first[d], r1 = pdf_first[d + 1]; r < r1; ++r) sum += rowsum[pdf_rows[r]];
+            for (int r = r0; r < r1; ++r) sum += rowsum[pdf_rows[r]];
             const float v = (float)(scale * (Real)e[d] * sum);
             g[d] = p.accumulate ? g[d] + v : v;
+        }
+        for (int h = wave; h < heavy_n; h += nthreads >> 6) {
+            const int d = heavy[h];
+            Real sum = 0;
+            for (int r = pdf_first[d] + lane, r1 = pdf_first[d + 1]; r < r1; r += 64)
+                sum += rowsum[pdf_rows[r]];
+            sum = wave_sum_uniform(sum);
+            if (lane == 0) {
+                const float v = (float)(scale * (Real)e[d] * sum);
+                g[d] = p.accumulate ? g[d] + v : v;
+            }
         }
         // the next frame's row sums are stored after its staging barrier, which
         // every thread reaches only once it is done here
@@ -1021,6 +1095,8 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
     const int32_t* pdf_rows = p.g.pdf_rows + od.vec_at;
+    const int heavy_n = pdf_first[P + 1], heavy_rows = pdf_first[P + 2];
+    const int32_t* heavy = pdf_first + P + 3;
     const float* scal = static_cast<const float*>(p.scal) + sd.scal_at;
     const float* cfac = static_cast<const float*>(p.cfac) + sd.scal_at;
     const float* vb_f = p.g.vb + odf.vec_at;
@@ -1169,6 +1245,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             float sum = 0.f, e, c;
             int r, r1;
             if (idx == tid) {
+                if (my_r1 - my_r0 > heavy_rows) continue;  // a wave adds these up, below
 #pragma unroll
                 for (int k = 0; k < kPre; ++k)
                     if (my_r0 + k < my_r1) sum += lds_ld(my_at[k]);
@@ -1179,6 +1256,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             } else {
                 r = pdf_first[d];
                 r1 = pdf_first[d + 1];
+                if (r1 - r > heavy_rows) continue;
                 e = p.emis[group_at + idx];
                 c = cfac[t];
             }
@@ -1187,15 +1265,34 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             const float v = c == 0.f ? 0.f : p.grad_scale * c * e * sum;
             *g = p.accumulate ? *g + v : v;
         }
+        // pdfs with many rows: one wave per pdf and frame, lanes striding over the rows
+        for (int u = wave; u < heavy_n * F; u += nthreads >> 6) {
+            const int h = u / F, f = u - h * F;
+            const int t = t0 + f;
+            if (t > T) continue;  // zeroed above
+            const int d = heavy[h];
+            float sum = 0.f;
+            for (int r = pdf_first[d] + lane, r1 = pdf_first[d + 1]; r < r1; r += 64)
+                sum += lds_ld(kRowSum + (uint32_t)(f * occ_rows + pdf_rows[r]) * 4u);
+            sum = wave_sum_uniform(sum);
+            if (lane == 0) {
+                float* g = p.grad + group_at + (size_t)f * P + d;
+                const float c = cfac[t];
+                const float v = c == 0.f ? 0.f : p.grad_scale * c * p.emis[group_at + (size_t)f * P + d] * sum;
+                *g = p.accumulate ? *g + v : v;
+            }
+        }
     }
 }
 
 // ---- kernel variants ---------------------------------------------------------
 using RecKernel = void (*)(FbParams);
+constexpr int kHybridSlots = 26;
 
 struct RecVariant {
     int wide, nslot, yrep, has_wb, max_threads;
     RecKernel fn;
+    int hybrid = 0;
 };
 
 #define LFMMI_REC(REAL, WIDE, NSLOT, WB, NT)                                  \
@@ -1219,14 +1316,17 @@ const RecVariant kRecVariants[] = {
     LFMMI_REC(double, 1, 8, 1, 1024), LFMMI_REC(double, 1, 16, 1, 1024),
     LFMMI_REC(double, 1, 32, 1, 512),
     LFMMI_REC(double, 1, 16, 0, 1024), LFMMI_REC(double, 1, 32, 0, 512),
+    // hybrid: 20 slots of a wave in registers, its other slices streamed
+    {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true>, 1},
+    {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true>, 1},
 };
 #undef LFMMI_REC
 
-const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb)
+const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, bool hybrid)
 {
     for (const RecVariant& v : kRecVariants)
         if (v.wide == (wide ? 1 : 0) && v.nslot == nslot && v.yrep == (yrep ? 1 : 0) &&
-            v.has_wb == (has_wb ? 1 : 0))
+            v.has_wb == (has_wb ? 1 : 0) && v.hybrid == (hybrid ? 1 : 0))
             return &v;
     return nullptr;
 }
@@ -1237,10 +1337,15 @@ int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
 {
     int best = 0;
     for (const RecVariant& v : kRecVariants)
-        if (v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) && v.nslot > 0 &&
+        if (v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) && v.nslot > 0 && !v.hybrid &&
             v.nslot >= max_wave_slots && threads <= v.max_threads && (best == 0 || v.nslot < best))
             best = v.nslot;
     return best;
+}
+
+int rec_hybrid_slots(bool wide, bool has_wb)
+{
+    return (!wide && !has_wb) ? kHybridSlots : 0;
 }
 
 hipError_t configure_kernels()
@@ -1318,7 +1423,8 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     hipError_t e;
     const bool wide = sizeof(Real) == 8;
     const RecVariant* rv =
-        find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0);
+        find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0,
+                 shape.rec_hybrid != 0);
     if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
     if (bk.n > 1 && (e = hipEventRecord(bk.fork, stream)) != hipSuccess) return e;
 

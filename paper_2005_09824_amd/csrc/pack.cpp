@@ -716,6 +716,16 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         out->pdf_first.assign((size_t)num_pdfs + 1, 0);
         out->pdf_rows.assign((size_t)ao.num_slices * kLanes, 0);
         for (int32_t d = 0; d <= num_pdfs; ++d) out->pdf_first[d] = (int32_t)first_row[d];
+        // pdfs cut into many rows: listed after the offsets, for the kernels to add
+        // their row sums with a whole wave instead of one thread
+        {
+            std::vector<int32_t> heavy;
+            for (int32_t d = 0; d < num_pdfs; ++d)
+                if (pieces[d] > kHeavyPdfRows) heavy.push_back(d);
+            out->pdf_first.push_back((int32_t)heavy.size());
+            out->pdf_first.push_back(kHeavyPdfRows);
+            out->pdf_first.insert(out->pdf_first.end(), heavy.begin(), heavy.end());
+        }
         for (int64_t r = 0; r < R; ++r) {
             out->ord[2].row_id[ao.pos[r]] = pdf_of[r];
             out->pdf_rows[r] = ao.pos[r];

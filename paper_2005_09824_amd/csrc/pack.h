@@ -19,6 +19,7 @@
 namespace lfmmi {
 
 constexpr int kLanes = 64;
+constexpr int kHeavyPdfRows = 16;  // OCC: more rows than this and a wave adds them up
 constexpr int kMaxWaves = 16;
 constexpr int kMaxIndex = 16384;  // x / y index * 4 must fit 16 bits
 
@@ -58,7 +59,9 @@ struct PackedGraph {
     std::vector<float> vinit[2], va[2], vb[2], vfin[2];
     // OCC: the rows of pdf d are pdf_rows[pdf_first[d] .. pdf_first[d + 1]), each
     // a position slice * 64 + lane; their sums are added in this order
-    std::vector<int32_t> pdf_first;  // [num_pdfs + 1]
+    // then: the number H of pdfs with more than kHeavyPdfRows rows, that limit,
+    // and the H pdf-ids (ascending)
+    std::vector<int32_t> pdf_first;  // [num_pdfs + 1] + [2 + H]
     std::vector<int32_t> pdf_rows;   // [OCC num_slices * 64], the tail unused
 };
 

@@ -98,6 +98,43 @@ def test_nonuniform_start_distribution_on_the_register_path():
     h.close()
 
 
+def test_graph_too_large_for_the_registers_keeps_part_of_each_wave_there():
+    # config 4's graph: more arcs per wave than any register-resident variant holds;
+    # the first slots of a wave stay in registers, the others are streamed
+    wl = workloads.make_workload(4, scale={"B": 3, "Tlo": 9, "Thi": 40}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    for o in (0, 1):
+        info = binding.lfmmi_graph_ordering_info(h, 0, o)
+        assert 0 < info["register_slots"] < info["max_wave_slots"]
+    lz, gamma = oracle.forward_backward(wl["den"], wl["logits"], wl["lengths"], wl["leak"])
+    check(*run_gpu(h, wl["logits"], wl["lengths"], wl["leak"]), lz, gamma, "hybrid")
+    h.close()
+
+
+def test_pdf_with_many_occupancy_rows_fp32_and_fp64():
+    # one pdf on most arcs: its arc list is cut into many rows, whose sums a whole
+    # wave adds up; with some final weights zero the graph runs in fp64
+    wl = workloads.make_workload(3, scale={"S": 600, "P": 40, "B": 3, "Tlo": 15, "Thi": 40},
+                                 pad_value=np.nan)
+    g = wl["den"]
+    rng = np.random.default_rng(11)
+    pdf = g["pdf"].copy()
+    pdf[rng.random(len(pdf)) < 0.6] = 5
+    g["pdf"] = pdf
+    for fp64 in (0, 1):
+        if fp64:
+            fin = g["final_prob"].copy()
+            fin[rng.random(len(fin)) < 0.5] = 0.0
+            g["final_prob"] = fin
+        h = binding.lfmmi_graph_create(g)
+        assert binding.lfmmi_graph_info(h)["fp64"] == fp64
+        oc = binding.lfmmi_graph_ordering_copy(h, 0, binding.ORD_OCC)
+        assert np.count_nonzero(oc["row_id"] == 5) > 64
+        lz, gamma = oracle.forward_backward(g, wl["logits"], wl["lengths"], wl["leak"])
+        check(*run_gpu(h, wl["logits"], wl["lengths"], wl["leak"]), lz, gamma, "heavy pdf")
+        h.close()
+
+
 def test_concurrent_buckets_do_not_change_any_bit(monkeypatch):
     # sequences are cut by length into buckets that run on streams of their own;
     # every sequence is computed the same way whichever bucket it lands in
