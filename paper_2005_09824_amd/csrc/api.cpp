@@ -191,7 +191,13 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             int64_t most_arcs = 0;
             for (int32_t g = 0; g < n; ++g) most_arcs = std::max(most_arcs, arc_off[g + 1] - arc_off[g]);
             const int by_arcs = (int)std::max<int64_t>(1, (most_arcs + 511) / 512);
-            h->occ_waves = std::min(by_arcs, env_int("LFMMI_OCC_WAVES", 8));
+            // (16 where the states allow one frame per arc record only: its kernel
+            // keeps more loads in flight with more waves)
+            int64_t most_states = 0;
+            for (int32_t g = 0; g < n; ++g)
+                most_states = std::max(most_states, state_off[g + 1] - state_off[g]);
+            const int cap = !h->wide && most_states * 4 > 16384 ? 16 : 8;
+            h->occ_waves = std::min(by_arcs, env_int("LFMMI_OCC_WAVES", cap));
             h->packed.assign(n, PackedGraph());
             h->max_rows_f = h->max_rows_b = h->max_rows_occ = 0;
             *max_slots = 0;
@@ -360,7 +366,7 @@ lfmmi_status upload(lfmmi_graph* h)
                 std::memcpy(host.data() + at_vfin + (size_t)d.vec_at * 4, pg.vfin[o].data(), nrow * 4);
             } else {
                 const PackedGraph& pg = h->packed[g];
-                std::memcpy(host.data() + at_rowpdf + (size_t)d.vec_at * 4, pg.pdf_rows.data(),
+                std::memcpy(host.data() + at_rowpdf + (size_t)d.vec_at * 4, pg.row_slot.data(),
                             nrow * 4);
                 std::memcpy(host.data() + at_pfirst + (size_t)d.pdf_first_at * 4,
                             pg.pdf_first.data(), pg.pdf_first.size() * 4);
@@ -387,7 +393,7 @@ lfmmi_status upload(lfmmi_graph* h)
     h->dg.va = reinterpret_cast<const float*>(base + at_va);
     h->dg.vb = reinterpret_cast<const float*>(base + at_vb);
     h->dg.vfin = reinterpret_cast<const float*>(base + at_vfin);
-    h->dg.pdf_rows = reinterpret_cast<const int32_t*>(base + at_rowpdf);
+    h->dg.row_slot = reinterpret_cast<const int32_t*>(base + at_rowpdf);
     h->dg.pdf_first = reinterpret_cast<const int32_t*>(base + at_pfirst);
     h->dg.ords = reinterpret_cast<const OrdDesc*>(base + at_ords);
     h->uploaded = true;
@@ -643,7 +649,9 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
         const int forced = env_int("LFMMI_OCC_MULTI", -1);
         if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;
     }
-    shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", 1));
+    // groups of frames per workgroup: with one frame per group a workgroup takes four,
+    // which spreads its start-up cost and lets it fetch the next frame's rows early
+    shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", shape.occ_multi == 1 ? 4 : 1));
 
     // ---- buckets of sequences that run concurrently (longest sequences first):
     // an eighth, a quarter, a quarter and the rest, so that the bucket that ends

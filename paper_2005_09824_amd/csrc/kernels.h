@@ -13,7 +13,7 @@ struct OrdDesc {
     int32_t rec_at;         // first slot (units of 64 records) in recs
     int32_t slice_off_at;   // first entry in slice_off (num_slices + 1 entries)
     int32_t wave_first_at;  // first entry in wave_first (num_waves + 1 entries)
-    int32_t vec_at;         // FWD/BWD: first row in vinit/va/vb/vfin; OCC: in pdf_rows
+    int32_t vec_at;         // FWD/BWD: first row in vinit/va/vb/vfin; OCC: in row_slot
     int32_t max_wave_slots;
     int32_t total_slots;
     int32_t mask_at;        // FWD/BWD: first entry in wave_mask (num_waves entries)
@@ -35,8 +35,9 @@ struct DeviceGraph {
     const float* va;
     const float* vb;
     const float* vfin;
-    const int32_t* pdf_first;   // OCC rows of pdf d: pdf_rows[pdf_first[d] .. pdf_first[d + 1])
-    const int32_t* pdf_rows;    // row positions (slice * 64 + lane)
+    const int32_t* pdf_first;   // OCC: the sums of pdf d's rows are words pdf_first[d] ..
+                                // pdf_first[d + 1] - 1 of a frame's row sums
+    const int32_t* row_slot;    // OCC: the word the sum of row (slice * 64 + lane) goes to
     const OrdDesc* ords;        // [num_graphs * 3]
 };
 

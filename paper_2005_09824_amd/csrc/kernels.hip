@@ -978,7 +978,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
-    const int32_t* pdf_rows = p.g.pdf_rows + od.vec_at;
+    const int32_t* row_slot = p.g.row_slot + od.vec_at;
     // pdfs with more than heavy_rows rows: their row sums are added by a whole wave
     const int heavy_n = pdf_first[P + 1], heavy_rows = pdf_first[P + 2];
     const int32_t* heavy = pdf_first + P + 3;
@@ -1017,6 +1017,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
             const uint2* rp = recs + (size_t)o0 * 64;
+            const int slot = row_slot[sl * 64 + lane];  // where this row's sum goes
             Real acc = 0;
             int i = o0;
             for (; i + 4 <= o1; i += 4) {
@@ -1031,7 +1032,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
                 acc += occ_term(rp[0], XA, XB);
                 rp += 64;
             }
-            rowsum[sl * 64 + lane] = acc;
+            rowsum[slot] = acc;
         }
         __syncthreads();
         const Real scale = (Real)p.grad_scale * c;
@@ -1040,7 +1041,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
             const int r0 = pdf_first[d], r1 = pdf_first[d + 1];
             if (r1 - r0 > heavy_rows) continue;  // a wave adds these up, below
             Real sum = 0;
-            for (int r = r0; r < r1; ++r) sum += rowsum[pdf_rows[r]];
+            for (int r = r0; r < r1; ++r) sum += rowsum[r];
             const float v = (float)(scale * (Real)e[d] * sum);
             g[d] = p.accumulate ? g[d] + v : v;
         }
@@ -1048,7 +1049,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
             const int d = heavy[h];
             Real sum = 0;
             for (int r = pdf_first[d] + lane, r1 = pdf_first[d + 1]; r < r1; r += 64)
-                sum += rowsum[pdf_rows[r]];
+                sum += rowsum[r];
             sum = wave_sum_uniform(sum);
             if (lane == 0) {
                 const float v = (float)(scale * (Real)e[d] * sum);
@@ -1076,7 +1077,8 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
 {
     static_assert((2 * F - 1) * STRIDE <= 65535, "plane offsets must fit the ds immediate");
     constexpr uint32_t kRowSum = 2u * F * STRIDE;
-    constexpr int kPre = 8;  // row positions a thread fetches ahead of the gathers
+    constexpr int kPre = 16;  // a thread adds up the row sums of a pdf with at most that many
+                              // rows; more and a wave does it
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1094,7 +1096,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
     const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
-    const int32_t* pdf_rows = p.g.pdf_rows + od.vec_at;
+    const int32_t* row_slot = p.g.row_slot + od.vec_at;
     const int heavy_n = pdf_first[P + 1], heavy_rows = pdf_first[P + 2];
     const int32_t* heavy = pdf_first + P + 3;
     const float* scal = static_cast<const float*>(p.scal) + sd.scal_at;
@@ -1109,23 +1111,59 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
         s0 = p.g.wave_first[od.wave_first_at + wave];
         s1 = p.g.wave_first[od.wave_first_at + wave + 1];
     }
-    // this thread's first gradient entry of a group: frame my_f, pdf my_d; the
-    // LDS addresses of the first kPre of that pdf's row sums stay in registers
+    // this thread's first gradient entry of a group: frame my_f, pdf my_d, whose row
+    // sums are the words my_r0 .. my_r1 - 1 of a frame's row sums
     const int my_f = tid / P, my_d = tid - my_f * P;
     int my_r0 = 0, my_r1 = 0;
-    uint32_t my_at[kPre];
     if (my_f < F) {
         my_r0 = pdf_first[my_d];
         my_r1 = pdf_first[my_d + 1];
     }
+    // one frame per group: a thread writes the same pdfs tid + j * nthreads in every
+    // frame; the row ranges of the next kMore of them stay in registers too
+    constexpr int kMore = F == 1 ? 2 : 0;
+    int more_r0[kMore ? kMore : 1], more_r1[kMore ? kMore : 1];
 #pragma unroll
-    for (int k = 0; k < kPre; ++k)
-        my_at[k] = my_r0 + k < my_r1
-                       ? kRowSum + (uint32_t)(my_f * occ_rows + pdf_rows[my_r0 + k]) * 4u
-                       : 0u;
+    for (int j = 0; j < kMore; ++j) {
+        const int d = tid + (j + 1) * nthreads;
+        more_r0[j] = d < P ? pdf_first[d] : 0;
+        more_r1[j] = d < P ? pdf_first[d + 1] : 0;
+    }
+    // pdfs with many rows: wave w adds up (pdf, frame) pairs w, w + nwaves, ... of every
+    // group; the row ranges of its first kHeavyKept pairs stay in registers
+    constexpr int kHeavyKept = 2;
+    const int nwaves = nthreads >> 6;
+    int hv_d[kHeavyKept], hv_r0[kHeavyKept], hv_r1[kHeavyKept];
+#pragma unroll
+    for (int k = 0; k < kHeavyKept; ++k) {
+        const int u = wave + k * nwaves;
+        hv_d[k] = hv_r0[k] = hv_r1[k] = 0;
+        if (u < heavy_n * F) {
+            hv_d[k] = heavy[u / F];
+            hv_r0[k] = pdf_first[hv_d[k]];
+            hv_r1[k] = pdf_first[hv_d[k] + 1];
+        }
+    }
+    // ... and the rows of the next frame are fetched while this frame's arcs are
+    // gathered: kStageRows of each side per thread (uniform leak target only)
+    constexpr int kStageRows = F == 1 ? STRIDE / 4096 : 1;
+    const int rows_most = max(rows_f, rows_b);
+    const bool ahead = F == 1 && !odf.has_wb && nthreads * kStageRows >= rows_most;
+    float next_a[kStageRows], next_b[kStageRows];
+    auto fetch_rows = [&](const int t) {  // alpha of frame t - 1, beta of frame t, as stored
+#pragma unroll
+        for (int u = 0; u < kStageRows; ++u) {
+            int r = u * nthreads + tid;
+            asm volatile("" : "+v"(r));  // recomputed here: no address registers held per row
+            next_a[u] = r < rows_f ? alpha[(size_t)(t - 1) * rows_f + r] : 0.f;
+            next_b[u] = r < rows_b ? beta[(size_t)t * rows_b + r] : 0.f;
+        }
+    };
 
     const int t_begin = blockIdx.x * groups_per_wg * F + 1;
     const int t_end = min(t_begin + groups_per_wg * F - 1, p.T);
+    if constexpr (F == 1)
+        if (ahead && t_begin <= min(t_end, T)) fetch_rows(t_begin);
     for (int t0 = t_begin; t0 <= t_end; t0 += F) {
         if (t0 > T) {  // nothing but padding rows from here on
             if (!p.accumulate)
@@ -1154,7 +1192,19 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
         __syncthreads();  // the previous group's gathers and row-sum reads are done
         // staging: two rows per thread and side in flight, all loads (alpha and beta)
         // issued before any is used
-        const int rows_max = max(rows_f, rows_b);
+        const int rows_max = ahead ? 0 : rows_most;
+        if constexpr (F == 1)
+            if (ahead) {
+                const float la = ca[0] * odf.b_const, lb = cb[0] * odb.b_const;
+#pragma unroll
+                for (int u = 0; u < kStageRows; ++u) {
+                    int r = u * nthreads + tid;
+                    asm volatile("" : "+v"(r));
+                    if (r < rows_f) lds_st((uint32_t)r * 4u, fmaf(next_a[u], inva[0], la));
+                    if (r < rows_b)
+                        lds_st((uint32_t)STRIDE + (uint32_t)r * 4u, fmaf(next_b[u], invb[0], lb));
+                }
+            }
         for (int r0 = 0; r0 < rows_max; r0 += 2 * nthreads) {
             float va[2][F], vbt[2][F], ba[2], bbt[2];
 #pragma unroll
@@ -1184,6 +1234,8 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             }
         }
         __syncthreads();
+        if constexpr (F == 1)
+            if (ahead && t0 + 1 <= min(t_end, T)) fetch_rows(t0 + 1);
 
         auto one_slot = [&](const uint2 r, float* acc) {
             const uint32_t xa = r.x & 0xffffu, xb = r.x >> 16;
@@ -1201,39 +1253,75 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
         const bool my_live = my_f < F && t0 + my_f <= T;
         const float my_e = my_live ? p.emis[group_at + tid] : 0.f;
         const float my_c = my_live ? cfac[t0 + my_f] : 0.f;
+        float more_e[kMore ? kMore : 1];
+#pragma unroll
+        for (int j = 0; j < kMore; ++j) {
+            const int d = tid + (j + 1) * nthreads;
+            more_e[j] = d < P ? p.emis[group_at + d] : 0.f;
+        }
 
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
             const uint2* rp = recs + (size_t)o0 * 64;
+            const uint32_t slot = (uint32_t)row_slot[sl * 64 + lane];  // where this row's sum goes
             float acc[F];
 #pragma unroll
             for (int f = 0; f < F; ++f) acc[f] = 0.f;
-            // chunks of 8 records, the next chunk loading while this one is used
-            uint2 cur[8], nxt[8];
+            // chunks of kChunk records, the next chunk loading while this one is used
+            constexpr int kChunk = 8;
+            uint2 cur[kChunk], nxt[kChunk];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) cur[u] = o0 + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
-            for (int i = o0; i < o1; i += 8) {
-                rp += 512;
+            for (int u = 0; u < kChunk; ++u) cur[u] = o0 + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
+            for (int i = o0; i < o1; i += kChunk) {
+                rp += kChunk * 64;
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    nxt[u] = i + 8 + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
-                if (i + 8 <= o1) {
+                for (int u = 0; u < kChunk; ++u)
+                    nxt[u] = i + kChunk + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
+                if (i + kChunk <= o1) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) one_slot(cur[u], acc);
+                    for (int u = 0; u < kChunk; ++u) one_slot(cur[u], acc);
                 } else {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
+                    for (int u = 0; u < kChunk; ++u)
                         if (i + u < o1) one_slot(cur[u], acc);
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
+                for (int u = 0; u < kChunk; ++u) cur[u] = nxt[u];
             }
 #pragma unroll
             for (int f = 0; f < F; ++f)
-                lds_st(kRowSum + (uint32_t)(f * occ_rows + sl * 64 + lane) * 4u, acc[f]);
+                lds_st(kRowSum + ((uint32_t)(f * occ_rows) + slot) * 4u, acc[f]);
         }
         __syncthreads();
+        // a pdf's row sums lie side by side; a thread adds up at most kPre of them
+        auto few_rows = [&](const int f, const int r0, const int r1) {
+            const uint32_t at = kRowSum + (uint32_t)(f * occ_rows + r0) * 4u;
+            const int cnt = r1 - r0;
+            float sum = 0.f;
+            // eight reads in flight at once: past the end the last word again, unused
+            for (int k0 = 0; k0 < kPre && k0 < cnt; k0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    v[k] = lds_ld(at + (uint32_t)min(k0 + k, cnt - 1) * 4u);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sum += k0 + k < cnt ? v[k] : 0.f;
+            }
+            return sum;
+        };
+        if constexpr (kMore > 0) {  // F == 1: frame t0 <= T, pdf = idx
+#pragma unroll
+            for (int j = 0; j < kMore; ++j) {
+                const int d = tid + (j + 1) * nthreads;
+                if (d >= P || more_r1[j] - more_r0[j] > heavy_rows) continue;
+                const float sum = few_rows(0, more_r0[j], more_r1[j]);
+                float* g = p.grad + group_at + d;
+                const float v = my_c == 0.f ? 0.f : p.grad_scale * my_c * more_e[j] * sum;
+                *g = p.accumulate ? *g + v : v;
+            }
+        }
         for (int idx = tid; idx < F * P; idx += nthreads) {
+            if (kMore > 0 && idx > tid && idx <= tid + kMore * nthreads) continue;  // done above
             const int f = idx / P, d = idx - f * P;
             const int t = t0 + f;
             if (t > p.T) break;
@@ -1242,38 +1330,46 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 if (!p.accumulate) *g = 0.f;
                 continue;
             }
-            float sum = 0.f, e, c;
-            int r, r1;
+            float e, c;
+            int r0, r1;
             if (idx == tid) {
-                if (my_r1 - my_r0 > heavy_rows) continue;  // a wave adds these up, below
-#pragma unroll
-                for (int k = 0; k < kPre; ++k)
-                    if (my_r0 + k < my_r1) sum += lds_ld(my_at[k]);
-                r = my_r0 + kPre;
+                r0 = my_r0;
                 r1 = my_r1;
                 e = my_e;
                 c = my_c;
             } else {
-                r = pdf_first[d];
+                r0 = pdf_first[d];
                 r1 = pdf_first[d + 1];
-                if (r1 - r > heavy_rows) continue;
                 e = p.emis[group_at + idx];
                 c = cfac[t];
             }
-            for (; r < r1; ++r)
-                sum += lds_ld(kRowSum + (uint32_t)(f * occ_rows + pdf_rows[r]) * 4u);
+            if (r1 - r0 > heavy_rows) continue;  // a wave adds these up, below
+            const float sum = few_rows(f, r0, r1);
             const float v = c == 0.f ? 0.f : p.grad_scale * c * e * sum;
             *g = p.accumulate ? *g + v : v;
         }
         // pdfs with many rows: one wave per pdf and frame, lanes striding over the rows
-        for (int u = wave; u < heavy_n * F; u += nthreads >> 6) {
+        for (int u = wave, k = 0; u < heavy_n * F; u += nwaves, ++k) {
             const int h = u / F, f = u - h * F;
             const int t = t0 + f;
             if (t > T) continue;  // zeroed above
-            const int d = heavy[h];
+            int d = 0, r0 = 0, r1 = 0;
+            if (k < kHeavyKept) {
+#pragma unroll
+                for (int q = 0; q < kHeavyKept; ++q)
+                    if (q == k) {
+                        d = hv_d[q];
+                        r0 = hv_r0[q];
+                        r1 = hv_r1[q];
+                    }
+            } else {
+                d = heavy[h];
+                r0 = pdf_first[d];
+                r1 = pdf_first[d + 1];
+            }
             float sum = 0.f;
-            for (int r = pdf_first[d] + lane, r1 = pdf_first[d + 1]; r < r1; r += 64)
-                sum += lds_ld(kRowSum + (uint32_t)(f * occ_rows + pdf_rows[r]) * 4u);
+            for (int r = r0 + lane; r < r1; r += 64)
+                sum += lds_ld(kRowSum + (uint32_t)(f * occ_rows + r) * 4u);
             sum = wave_sum_uniform(sum);
             if (lane == 0) {
                 float* g = p.grad + group_at + (size_t)f * P + d;

@@ -714,7 +714,7 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         const Arrangement ao = arrange(len, occ_waves, 0);
         start_ordering(ao, (int32_t)R, &out->ord[2]);
         out->pdf_first.assign((size_t)num_pdfs + 1, 0);
-        out->pdf_rows.assign((size_t)ao.num_slices * kLanes, 0);
+        out->row_slot.assign((size_t)ao.num_slices * kLanes, -1);
         for (int32_t d = 0; d <= num_pdfs; ++d) out->pdf_first[d] = (int32_t)first_row[d];
         // pdfs cut into many rows: listed after the offsets, for the kernels to add
         // their row sums with a whole wave instead of one thread
@@ -728,7 +728,12 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         }
         for (int64_t r = 0; r < R; ++r) {
             out->ord[2].row_id[ao.pos[r]] = pdf_of[r];
-            out->pdf_rows[r] = ao.pos[r];
+            out->row_slot[ao.pos[r]] = (int32_t)r;
+        }
+        {  // padding rows: the words after the last pdf's
+            int32_t next = (int32_t)R;
+            for (int32_t& q : out->row_slot)
+                if (q < 0) q = next++;
         }
         std::vector<int64_t> seen(num_pdfs, 0);
         std::vector<int32_t> prow(A), nth(A), wo(ao.num_slices);

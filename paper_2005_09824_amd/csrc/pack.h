@@ -57,12 +57,13 @@ struct PackedGraph {
     //   init: start vector (FWD pi, BWD final)      fin: closing dot (FWD final, BWD pi)
     //   a:    leak dot weights (FWD 1, BWD pi)      b:   leak target (FWD pi, BWD 1)
     std::vector<float> vinit[2], va[2], vb[2], vfin[2];
-    // OCC: the rows of pdf d are pdf_rows[pdf_first[d] .. pdf_first[d + 1]), each
-    // a position slice * 64 + lane; their sums are added in this order
+    // OCC: a frame's row sums are stored sorted by pdf: the sum of row position
+    // slice * 64 + lane is word row_slot[position]; pdf d owns words pdf_first[d] ..
+    // pdf_first[d + 1] - 1, added up in that order (padding rows: the words after)
     // then: the number H of pdfs with more than kHeavyPdfRows rows, that limit,
     // and the H pdf-ids (ascending)
     std::vector<int32_t> pdf_first;  // [num_pdfs + 1] + [2 + H]
-    std::vector<int32_t> pdf_rows;   // [OCC num_slices * 64], the tail unused
+    std::vector<int32_t> row_slot;   // [OCC num_slices * 64], a permutation
 };
 
 struct ArcList {
