@@ -172,9 +172,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         if (forced > 0) waves = std::min(forced, kMaxWaves);
         // Pack for `waves` waves; when the arcs of a wave then fit no register-resident
         // variant of the recursion kernel, try half the waves (twice the registers per
-        // lane) before settling for streamed arcs. Slices are padded to even widths
-        // for the register-resident kernel only: `registers_possible` rules it out
-        // beforehand where it can, else streamed arcs are packed once more without.
+        // lane) before settling for streamed arcs.
         auto registers_possible = [&](int wv) {
             if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return false;  // staging limits
             for (int32_t g = 0; g < n; ++g) {
@@ -184,8 +182,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             }
             return true;
         };
-        auto pack_with = [&](int wv, bool even, int* max_slots) -> lfmmi_status {
-            tune.even_slices = even;
+        auto pack_with = [&](int wv, int* max_slots) -> lfmmi_status {
             h->rec_waves = wv;
             // the occupancy pass is throughput work: about 8 arcs per lane, at most 8 waves
             int64_t most_arcs = 0;
@@ -218,15 +215,15 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         };
         {
             int max_slots = 0;
-            bool even = registers_possible(waves);
-            lfmmi_status st = pack_with(waves, even, &max_slots);
-            h->rec_nslot = even ? rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes) : 0;
+            lfmmi_status st = pack_with(waves, &max_slots);
+            h->rec_nslot = registers_possible(waves)
+                               ? rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes)
+                               : 0;
             if (st == LFMMI_OK && h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
                 registers_possible(waves / 2) &&
                 rec_register_slots(h->wide, h->has_wb, 2 * max_slots, waves / 2 * kLanes) != 0) {
                 waves /= 2;
-                even = true;
-                st = pack_with(waves, true, &max_slots);
+                st = pack_with(waves, &max_slots);
                 h->rec_nslot = rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
             }
             // too many arcs for the registers: keep the first slots of every wave there
@@ -239,12 +236,9 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
                 return rec_hybrid_slots(h->wide, h->has_wb) > 0;
             };
             if (st == LFMMI_OK && h->rec_nslot == 0 && hybrid_possible()) {
-                if (!even) st = pack_with(waves, true, &max_slots);
-                even = true;
                 h->rec_nslot = rec_hybrid_slots(h->wide, h->has_wb);
                 h->rec_hybrid = true;
             }
-            if (st == LFMMI_OK && h->rec_nslot == 0 && even) st = pack_with(waves, false, &max_slots);
             if (st != LFMMI_OK) {
                 delete h;
                 return st;
@@ -315,6 +309,8 @@ lfmmi_status upload(lfmmi_graph* h)
             }
         }
     if (n_slots > (size_t)1 << 30) return fail(LFMMI_ERR_UNSUPPORTED, "packed graph too large");
+    for (const OrdDesc& d : h->ords)
+        if (d.total_slots % 2 != 0) return fail(LFMMI_ERR_INVALID_ARG, "odd slot count (packer)");
 
     size_t total = 0;
     const size_t at_recs = reserve<uint2>(&total, n_slots * kLanes);
@@ -341,15 +337,19 @@ lfmmi_status upload(lfmmi_graph* h)
         for (int o = 0; o < 3; ++o) {
             const Ordering& od = h->packed[g].ord[o];
             const OrdDesc& d = h->ords[(size_t)g * 3 + o];
+            // On the device the records of slots 2q and 2q + 1 of a lane lie side by
+            // side (one 16-byte load), pair q of lane l at [q * 64 + l]; every slice
+            // starts at an even slot.
             uint2* recs = reinterpret_cast<uint2*>(host.data() + at_recs) + (size_t)d.rec_at * kLanes;
+            float* wbs = reinterpret_cast<float*>(host.data() + at_wb) + (size_t)d.rec_at * kLanes;
             for (size_t i = 0; i < od.key.size(); ++i) {
+                const size_t slot = i / kLanes, lane = i % kLanes;
+                const size_t to = ((slot >> 1) * kLanes + lane) * 2 + (slot & 1);
                 uint32_t wbits;
                 std::memcpy(&wbits, &od.w[i], 4);
-                recs[i] = make_uint2(od.key[i], wbits);
+                recs[to] = make_uint2(od.key[i], wbits);
+                if (!od.wb.empty()) wbs[to] = od.wb[i];
             }
-            if (!od.wb.empty())
-                std::memcpy(host.data() + at_wb + (size_t)d.rec_at * kLanes * 4, od.wb.data(),
-                            od.wb.size() * 4);
             if (!od.wave_mask.empty())
                 std::memcpy(host.data() + at_mask + (size_t)d.mask_at * 8, od.wave_mask.data(),
                             od.wave_mask.size() * 8);

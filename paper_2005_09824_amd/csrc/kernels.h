@@ -26,7 +26,8 @@ struct OrdDesc {
 };
 
 struct DeviceGraph {
-    const uint2* recs;          // {key, float bits of w}, lane-minor
+    const uint2* recs;          // {key, float bits of w}; slots 2q, 2q + 1 of lane l at
+                                // [(q * 64 + l) * 2 + (0, 1)]
     const float* wb;            // w * b[from] per record (0 where unused), same indexing
     const uint64_t* wave_mask;  // closing-slot bit masks of the FWD/BWD waves
     const int32_t* slice_off;   // slot offsets, local to the ordering

@@ -98,6 +98,21 @@ __device__ __forceinline__ float lds_f32(const float* base, uint32_t byte_off)
     return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
 }
 
+// Arc records on the device: the records of slots 2q and 2q + 1 of a lane lie side
+// by side, {key, w, key, w}, pair q of lane l at [q * 64 + l] (a 16-byte load per
+// lane streams from L2 at twice the rate of an 8-byte one); slices start at even
+// slots. The per-arc leak factors are paired up the same way.
+__device__ __forceinline__ const uint4* rec_pairs(const FbParams& p, const OrdDesc& od, const int lane)
+{
+    return reinterpret_cast<const uint4*>(p.g.recs) + (size_t)(od.rec_at >> 1) * 64 + lane;
+}
+__device__ __forceinline__ const float2* wb_pairs(const FbParams& p, const OrdDesc& od, const int lane)
+{
+    return reinterpret_cast<const float2*>(p.g.wb) + (size_t)(od.rec_at >> 1) * 64 + lane;
+}
+__device__ __forceinline__ uint2 rec_lo(const uint4 r) { return make_uint2(r.x, r.y); }
+__device__ __forceinline__ uint2 rec_hi(const uint4 r) { return make_uint2(r.z, r.w); }
+
 // The recursion of one (sequence, direction).
 //
 // Real   float when every state of the graph is final (denominator-like: the
@@ -142,8 +157,8 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
                  (dir == 0 ? sd.alpha_at : sd.beta_at);
     Real* scalN = static_cast<Real*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
     Real* scalS = scalN + p.scal_total;
-    const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
-    const float* wbp = p.g.wb + (size_t)od.rec_at * 64 + lane;
+    const uint4* recs = rec_pairs(p, od, lane);
+    const float2* wbp = wb_pairs(p, od, lane);
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const Real eps = (Real)p.leak;
     const Real bconst = (Real)od.b_const;
@@ -219,38 +234,38 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
         {
             for (int sl = s0; sl < s1; ++sl) {
                 const int o0 = so[sl], o1 = so[sl + 1] - od.closing;  // without the closing slot
-                const uint2* rp = recs + (size_t)o0 * 64;
-                const float* wp = wbp + (size_t)o0 * 64;
+                const uint4* rp = recs + (size_t)(o0 >> 1) * 64;
+                const float2* wp = wbp + (size_t)(o0 >> 1) * 64;
                 Real acc1 = 0, acc2 = 0;
-                int i = o0;
-                for (; i + 4 <= o1; i += 4) {
-                    uint2 r[4];
-                    float wbv[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        r[u] = rp[u * 64];
-                        if (HAS_WB) wbv[u] = wp[u * 64];
-                    }
-                    rp += 256;
-                    wp += 256;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float e = lds_f32(Yc, y_offset<YREP>(r[u].x, lane));
-                        const Real x = lds_at(Xc, r[u].x & 0xffffu);
-                        const float t = __uint_as_float(r[u].y) * e;
-                        acc1 += (Real)t * x;
-                        acc2 += HAS_WB ? (Real)(wbv[u] * e) : (Real)t;
-                    }
-                }
-                for (; i < o1; ++i) {
-                    const uint2 r = rp[0];
+                auto slot = [&](const uint2 r, const float wbv) {
                     const float e = lds_f32(Yc, y_offset<YREP>(r.x, lane));
                     const Real x = lds_at(Xc, r.x & 0xffffu);
                     const float t = __uint_as_float(r.y) * e;
                     acc1 += (Real)t * x;
-                    acc2 += HAS_WB ? (Real)(wp[0] * e) : (Real)t;
+                    acc2 += HAS_WB ? (Real)(wbv * e) : (Real)t;
+                };
+                int i = o0;
+                for (; i + 4 <= o1; i += 4) {
+                    const uint4 r0 = rp[0], r1 = rp[64];
+                    float2 w0 = make_float2(0.f, 0.f), w1 = w0;
+                    if (HAS_WB) {
+                        w0 = wp[0];
+                        w1 = wp[64];
+                    }
+                    rp += 128;
+                    wp += 128;
+                    slot(rec_lo(r0), w0.x);
+                    slot(rec_hi(r0), w0.y);
+                    slot(rec_lo(r1), w1.x);
+                    slot(rec_hi(r1), w1.y);
+                }
+                for (; i < o1; i += 2) {
+                    const uint4 r = rp[0];
+                    const float2 w = HAS_WB ? wp[0] : make_float2(0.f, 0.f);
                     rp += 64;
                     wp += 64;
+                    slot(rec_lo(r), w.x);
+                    if (i + 1 < o1) slot(rec_hi(r), w.y);  // else: the closing slot
                 }
                 const int row = sl * 64 + lane;
                 const Real arow = (Real)p.g.va[od.vec_at + row];
@@ -510,7 +525,7 @@ struct RecRegs {
                                          const uint32_t part_at, const int nsl,
                                          const int sl_stream, const int sl_end,
                                          const int first_streamed, const int32_t* so,
-                                         const uint2* recs)
+                                         const uint4* recs)
     {
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
@@ -630,8 +645,8 @@ struct RecRegs {
             // the wave's other slices: records from L2, four (then two) slots at a time
             // (the first of them may have begun in the registers: acc1, acc2)
             const int lane_y = (lane & 31) * 4;
-            int i = first_streamed;
-            const uint2* rp = recs + (size_t)i * 64;
+            int i = first_streamed;  // even
+            const uint4* rp = recs + (size_t)(i >> 1) * 64;
             Real a1 = acc1, a2 = acc2;
             for (int sl = sl_stream; sl < sl_end; ++sl) {
                 const int o1 = so[sl + 1];
@@ -644,14 +659,14 @@ struct RecRegs {
                     a2 += t;
                 };
                 for (; i + 4 <= o1; i += 4) {
-                    const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
-                    rp += 256;
-                    slot(r0); slot(r1); slot(r2); slot(r3);
+                    const uint4 r0 = rp[0], r1 = rp[64];
+                    rp += 128;
+                    slot(rec_lo(r0)); slot(rec_hi(r0)); slot(rec_lo(r1)); slot(rec_hi(r1));
                 }
                 for (; i < o1; i += 2) {  // widths are even
-                    const uint2 r0 = rp[0], r1 = rp[64];
-                    rp += 128;
-                    slot(r0); slot(r1);
+                    const uint4 r0 = rp[0];
+                    rp += 64;
+                    slot(rec_lo(r0)); slot(rec_hi(r0));
                 }
                 const Real v = inv * a1 + cb * a2;
                 const uint32_t at = (uint32_t)(sl * 64 + lane) * kRB;
@@ -692,8 +707,10 @@ struct RecRegs {
                      (dir == 0 ? sd.alpha_at : sd.beta_at);
         Real* scalN = static_cast<Real*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
         Real* scalS = scalN + p.scal_total;
-        const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
-        const float* wbp = p.g.wb + (size_t)od.rec_at * 64 + lane;
+        const uint4* recs = rec_pairs(p, od, lane);
+        // one record: slot s of this lane is the (s & 1)-th half of pair s >> 1
+        const uint2* rec1 = reinterpret_cast<const uint2*>(recs);
+        const float* wb1 = reinterpret_cast<const float*>(wb_pairs(p, od, lane));
         const int32_t* so = p.g.slice_off + od.slice_off_at;
         const Real eps = (Real)p.leak;
         const Real aconst = (Real)od.a_const;
@@ -725,14 +742,15 @@ struct RecRegs {
         for (int i = 0; i < NSLOT; ++i) {
             const bool on = i < nsl;
             const bool closing = HAS_WB && ((mask >> i) & 1);  // holds a[row], no arc
-            const uint2 r = on ? recs[(size_t)(first + i) * 64] : make_uint2(0u, 0u);
+            const size_t at = (size_t)((first + i) >> 1) * 128 + ((first + i) & 1);
+            const uint2 r = on ? rec1[at] : make_uint2(0u, 0u);
             xa[i] = (r.x & 0xffffu) * (kRB / 4u);
             ya[i] = kRegY0 +
                     ((on && !closing)
                          ? (YREP ? (r.x >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (r.x >> 16))
                          : kRegYZero);
             wr[i] = __uint_as_float(r.y);
-            if (HAS_WB) wbr[i] = (on && !closing) ? wbp[(size_t)(first + i) * 64] : 0.f;
+            if (HAS_WB) wbr[i] = (on && !closing) ? wb1[at] : 0.f;
             // opaque from here on: the three values stay in three registers for the
             // whole time loop instead of being re-derived from the record each frame
             asm volatile("" : "+v"(xa[i]), "+v"(ya[i]), "+v"(wr[i]));
@@ -975,7 +993,7 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
     Real* XB = XA + p.lds_rows_occ_a;
     Real* rowsum = XB + p.lds_rows_occ_b;
 
-    const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+    const uint4* recs = rec_pairs(p, od, lane);
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
     const int32_t* row_slot = p.g.row_slot + od.vec_at;
@@ -1016,21 +1034,23 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
         __syncthreads();
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
-            const uint2* rp = recs + (size_t)o0 * 64;
+            const uint4* rp = recs + (size_t)(o0 >> 1) * 64;
             const int slot = row_slot[sl * 64 + lane];  // where this row's sum goes
             Real acc = 0;
             int i = o0;
             for (; i + 4 <= o1; i += 4) {
-                const uint2 r0 = rp[0], r1 = rp[64], r2 = rp[128], r3 = rp[192];
-                rp += 256;
-                acc += occ_term(r0, XA, XB);
-                acc += occ_term(r1, XA, XB);
-                acc += occ_term(r2, XA, XB);
-                acc += occ_term(r3, XA, XB);
+                const uint4 r0 = rp[0], r1 = rp[64];
+                rp += 128;
+                acc += occ_term(rec_lo(r0), XA, XB);
+                acc += occ_term(rec_hi(r0), XA, XB);
+                acc += occ_term(rec_lo(r1), XA, XB);
+                acc += occ_term(rec_hi(r1), XA, XB);
             }
-            for (; i < o1; ++i) {
-                acc += occ_term(rp[0], XA, XB);
+            for (; i < o1; i += 2) {  // widths are even
+                const uint4 r0 = rp[0];
                 rp += 64;
+                acc += occ_term(rec_lo(r0), XA, XB);
+                acc += occ_term(rec_hi(r0), XA, XB);
             }
             rowsum[slot] = acc;
         }
@@ -1077,8 +1097,6 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
 {
     static_assert((2 * F - 1) * STRIDE <= 65535, "plane offsets must fit the ds immediate");
     constexpr uint32_t kRowSum = 2u * F * STRIDE;
-    constexpr int kPre = 16;  // a thread adds up the row sums of a pdf with at most that many
-                              // rows; more and a wave does it
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1093,7 +1111,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
     const int rows_f = odf.num_slices * 64, rows_b = odb.num_slices * 64;
     const int occ_rows = od.num_slices * 64;
 
-    const uint2* recs = p.g.recs + (size_t)od.rec_at * 64 + lane;
+    const uint4* recs = rec_pairs(p, od, lane);
     const int32_t* so = p.g.slice_off + od.slice_off_at;
     const int32_t* pdf_first = p.g.pdf_first + od.pdf_first_at;
     const int32_t* row_slot = p.g.row_slot + od.vec_at;
@@ -1262,28 +1280,35 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
 
         for (int sl = s0; sl < s1; ++sl) {
             const int o0 = so[sl], o1 = so[sl + 1];
-            const uint2* rp = recs + (size_t)o0 * 64;
             const uint32_t slot = (uint32_t)row_slot[sl * 64 + lane];  // where this row's sum goes
             float acc[F];
 #pragma unroll
             for (int f = 0; f < F; ++f) acc[f] = 0.f;
-            // chunks of kChunk records, the next chunk loading while this one is used
-            constexpr int kChunk = 8;
-            uint2 cur[kChunk], nxt[kChunk];
+            // chunks of kChunk record pairs, the next chunk loading while this one is used
+            // (a load past the end of the slice fetches its last pair again, unused:
+            // a conditional 16-byte load would be split into four 4-byte ones)
+            constexpr int kChunk = 4;
+            const int q_last = (o1 >> 1) - 1;
+            uint4 cur[kChunk], nxt[kChunk];
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) cur[u] = o0 + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
-            for (int i = o0; i < o1; i += kChunk) {
-                rp += kChunk * 64;
+            for (int u = 0; u < kChunk; ++u) cur[u] = recs[(size_t)min((o0 >> 1) + u, q_last) * 64];
+            for (int i = o0; i < o1; i += 2 * kChunk) {
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u)
-                    nxt[u] = i + kChunk + u < o1 ? rp[u * 64] : make_uint2(0u, 0u);
-                if (i + kChunk <= o1) {
+                    nxt[u] = recs[(size_t)min((i >> 1) + kChunk + u, q_last) * 64];
+                if (i + 2 * kChunk <= o1) {
 #pragma unroll
-                    for (int u = 0; u < kChunk; ++u) one_slot(cur[u], acc);
+                    for (int u = 0; u < kChunk; ++u) {
+                        one_slot(rec_lo(cur[u]), acc);
+                        one_slot(rec_hi(cur[u]), acc);
+                    }
                 } else {
 #pragma unroll
                     for (int u = 0; u < kChunk; ++u)
-                        if (i + u < o1) one_slot(cur[u], acc);
+                        if (i + 2 * u < o1) {  // widths are even
+                            one_slot(rec_lo(cur[u]), acc);
+                            one_slot(rec_hi(cur[u]), acc);
+                        }
                 }
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u) cur[u] = nxt[u];
@@ -1293,13 +1318,13 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 lds_st(kRowSum + ((uint32_t)(f * occ_rows) + slot) * 4u, acc[f]);
         }
         __syncthreads();
-        // a pdf's row sums lie side by side; a thread adds up at most kPre of them
+        // a pdf's row sums lie side by side; a thread adds up those of a pdf with few rows
         auto few_rows = [&](const int f, const int r0, const int r1) {
             const uint32_t at = kRowSum + (uint32_t)(f * occ_rows + r0) * 4u;
             const int cnt = r1 - r0;
             float sum = 0.f;
             // eight reads in flight at once: past the end the last word again, unused
-            for (int k0 = 0; k0 < kPre && k0 < cnt; k0 += 8) {
+            for (int k0 = 0; k0 < cnt; k0 += 8) {
                 float v[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k)

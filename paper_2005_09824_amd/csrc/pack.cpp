@@ -20,8 +20,7 @@ struct Arrangement {
     int32_t num_slices = 0, num_waves = 0, max_wave_slots = 0;
 };
 
-Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
-                    bool even_widths = false)
+Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots)
 {
     Arrangement ar;
     const int32_t R = (int32_t)len.size();
@@ -34,10 +33,11 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
     std::vector<int32_t> sorted_width(ar.num_slices);
     for (int32_t s = 0; s < ar.num_slices; ++s)
         sorted_width[s] = std::max(len[idx[(size_t)s * kLanes]] + extra_slots, 1);
-    // even_widths: one more padding slot where needed (the register-resident
-    // recursion kernel looks for the end of a slice at every other slot only)
-    if (even_widths)
-        for (int32_t& wd : sorted_width) wd += wd & 1;
+    // Widths are even, with one more padding slot where needed: the kernels load
+    // the records of two slots at a time (16 bytes per lane stream at twice the rate
+    // of 8), and the register-resident recursion looks for the end of a slice at
+    // every other slot only.
+    for (int32_t& wd : sorted_width) wd += wd & 1;
 
     std::vector<std::vector<int32_t>> owned(ar.num_waves);
     std::vector<int64_t> load(ar.num_waves, 0);
@@ -540,8 +540,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
     // with a uniform pi the leak-dot weights are constants and need no slot
     const int closing = per_arc_leak ? 1 : 0;
-    Arrangement af = arrange(indeg, rec_waves, closing, tune.even_slices);
-    Arrangement ab = arrange(outdeg, rec_waves, closing, tune.even_slices);
+    Arrangement af = arrange(indeg, rec_waves, closing);
+    Arrangement ab = arrange(outdeg, rec_waves, closing);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {
@@ -650,8 +650,9 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         // few: k slices per wave, i.e. waves * 64 * k rows, handed to the pdfs one
         // at a time, always to the pdf whose pieces are longest at that moment. A
         // pdf's pieces then differ by at most one arc, and sorting rows by length
-        // leaves little padding. k: the smallest whose fullest wave is within 3 %
-        // of the best over all k tried.
+        // leaves little padding. k: the smallest whose fullest wave is within 8 %
+        // of the best over all k tried (rows cost LDS: fewer of them can let a
+        // second workgroup share the compute unit).
         const int waves_o = std::max(1, occ_waves);
         int64_t nonempty = 0;
         for (int32_t d = 0; d < num_pdfs; ++d) nonempty += count[d] > 0;
@@ -703,7 +704,7 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             }
             int64_t k_pick = k_min;
             for (const auto& t : tried)
-                if ((double)t.second <= 1.03 * (double)best) { k_pick = t.first; break; }
+                if ((double)t.second <= 1.08 * (double)best) { k_pick = t.first; break; }
             allot(k_pick * per_k, &pieces);
             lengths_of(pieces, &len, &pdf_of);
         }

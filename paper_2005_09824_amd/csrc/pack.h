@@ -19,7 +19,7 @@
 namespace lfmmi {
 
 constexpr int kLanes = 64;
-constexpr int kHeavyPdfRows = 16;  // OCC: more rows than this and a wave adds them up
+constexpr int kHeavyPdfRows = 64;  // OCC: more rows than this and a wave adds them up
 constexpr int kMaxWaves = 16;
 constexpr int kMaxIndex = 16384;  // x / y index * 4 must fit 16 bits
 
@@ -87,7 +87,6 @@ struct PackTuning {
     bool balance_banks = true;        // re-deal lanes inside half-slices (state -> bank)
     bool order_slots = true;          // order each row's arcs over its slots
     bool emission_conflicts = true;   // the emission gather can conflict (row not replicated)
-    bool even_slices = true;          // FWD / BWD slices an even number of slots wide
 };
 
 // per_arc_leak: fill the per-arc leak factors (required when init_prob is not
