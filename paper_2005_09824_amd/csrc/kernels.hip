@@ -259,25 +259,28 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
                     slot(rec_lo(r1), w1.x);
                     slot(rec_hi(r1), w1.y);
                 }
+                // the closing slot (the second half of the slice's last pair: widths are
+                // even) holds the row's leak-dot weight
+                uint32_t closing_w = 0;
                 for (; i < o1; i += 2) {
                     const uint4 r = rp[0];
                     const float2 w = HAS_WB ? wp[0] : make_float2(0.f, 0.f);
                     rp += 64;
                     wp += 64;
                     slot(rec_lo(r), w.x);
-                    if (i + 1 < o1) slot(rec_hi(r), w.y);  // else: the closing slot
+                    if (i + 1 < o1) slot(rec_hi(r), w.y);
+                    else closing_w = r.w;
                 }
                 const int row = sl * 64 + lane;
-                const Real arow = (Real)p.g.va[od.vec_at + row];
                 const Real v = inv * acc1 + cb * acc2;
                 Xn[row] = v;
                 tr[row] = v;
                 n += v;
-                s += arow * v;
+                if (HAS_WB) s += (Real)__uint_as_float(closing_w) * v;
             }
         }
         n = wave_sum(n);
-        s = wave_sum(s);
+        s = HAS_WB ? wave_sum(s) : (Real)od.a_const * n;  // one weight for all rows
         if (lane == 0) { partn[wave * 2] = n; partn[wave * 2 + 1] = s; }
         if (more) {
 #pragma unroll
