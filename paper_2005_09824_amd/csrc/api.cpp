@@ -57,7 +57,8 @@ struct lfmmi_graph {
     bool wide = false;  // fp64 state vectors (some state is not final)
     int rec_nslot = 0;  // register-resident arc slots of the recursion kernel (0: streamed)
     bool rec_yrep = false;
-    bool rec_hybrid = false;  // rec_nslot slots of a wave in registers, its others streamed
+    int rec_hybrid = 0;  // 1, 2: rec_nslot slots of a wave in registers, its others streamed
+                         // (2: LDS map for up to 12288 states)
     bool has_wb = false;  // arcs carry a per-arc leak factor (some init_prob is not uniform)
 
     // device copy
@@ -228,16 +229,18 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             }
             // too many arcs for the registers: keep the first slots of every wave there
             // and stream the others, where the fixed LDS map of that kernel holds the graph
-            auto hybrid_possible = [&]() {
-                if (h->wide || h->has_wb || env_int("LFMMI_HYBRID", 1) == 0) return false;
-                if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return false;
-                for (int32_t g = 0; g < n; ++g)
-                    if (state_off[g + 1] - state_off[g] > 8192) return false;
-                return rec_hybrid_slots(h->wide, h->has_wb) > 0;
+            auto hybrid_possible = [&]() {  // 0: no; 1: 32 KB state vectors; 2: 48 KB
+                if (h->wide || h->has_wb || env_int("LFMMI_HYBRID", 1) == 0) return 0;
+                if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return 0;
+                if (rec_hybrid_slots(h->wide, h->has_wb) <= 0) return 0;
+                int64_t most = 0;
+                for (int32_t g = 0; g < n; ++g) most = std::max(most, state_off[g + 1] - state_off[g]);
+                if (most <= 8192) return 1;
+                return most <= 12288 && !h->rec_yrep ? 2 : 0;
             };
-            if (st == LFMMI_OK && h->rec_nslot == 0 && hybrid_possible()) {
+            if (st == LFMMI_OK && h->rec_nslot == 0 && hybrid_possible() != 0) {
                 h->rec_nslot = rec_hybrid_slots(h->wide, h->has_wb);
-                h->rec_hybrid = true;
+                h->rec_hybrid = hybrid_possible();
             }
             if (st != LFMMI_OK) {
                 delete h;
@@ -639,7 +642,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     shape.rec_threads = h->rec_waves * kLanes;
     shape.rec_nslot = h->rec_nslot;
     shape.rec_yrep = h->rec_yrep ? 1 : 0;
-    shape.rec_hybrid = h->rec_hybrid ? 1 : 0;
+    shape.rec_hybrid = h->rec_hybrid;
     shape.rec_has_wb = h->has_wb ? 1 : 0;
     shape.occ_threads = h->occ_waves * kLanes;
     shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));

@@ -84,7 +84,8 @@ struct LaunchShape {
     int rec_nslot;     // arc slots held in registers per lane (0: streamed)
     int rec_yrep;      // emission row replicated across LDS banks
     int rec_has_wb;    // arcs carry a per-arc leak factor
-    int rec_hybrid;    // only the leading slices of a wave are register-resident
+    int rec_hybrid;    // 1: only the first slots of a wave are register-resident;
+                       // 2: the same, with the LDS map for up to 12288 states
     int occ_threads;   // workgroup size of the occupancy kernel
     int occ_frames;    // frames per occupancy workgroup (frame-at-a-time kernel)
     int occ_multi;     // frames per record of the plane-layout occupancy kernel (0: not used)

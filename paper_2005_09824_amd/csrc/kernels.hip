@@ -460,9 +460,19 @@ __host__ __device__ constexpr int stage_passes(bool yrep, int nt)
 // HYBRID: a wave keeps in registers only the first of its slices that fit NSLOT
 // slots and streams the records of the others from L2 every frame (graphs too
 // large for the registers: less record traffic than streaming everything).
-template <typename Real, bool YREP, bool HAS_WB, int NSLOT, int NT, bool HYBRID = false>
+// BIG: state vectors of 48 KB and emission rows of 16 KB (graphs of up to 12288
+// states) instead of 32 KB each.
+template <typename Real, bool YREP, bool HAS_WB, int NSLOT, int NT, bool HYBRID = false,
+          bool BIG = false>
 struct RecRegs {
     static_assert(!HYBRID || (!HAS_WB && sizeof(Real) == 4), "hybrid: fp32, constant leak weights");
+    static_assert(!BIG || (HYBRID && !YREP), "the large map: hybrid, plain emission rows");
+    // this variant's LDS map (the names hide the 32 KB map's constants)
+    static constexpr uint32_t kRegX1 = BIG ? 49152u : lfmmi::kRegX1;
+    static constexpr uint32_t kRegY0 = BIG ? 98304u : lfmmi::kRegY0;
+    static constexpr uint32_t kRegY1 = BIG ? 114688u : lfmmi::kRegY1;
+    static constexpr uint32_t kRegYZero = BIG ? 16380u : lfmmi::kRegYZero;
+    static_assert(lfmmi::kRegPart == 131072u, "both maps end where the partial sums begin");
     static constexpr uint32_t kRB = sizeof(Real);  // bytes of a state value
     // Emission staging. Replicated rows (YREP): a thread writes four of the 32
     // copies of one value with one 16-byte store, kYPass passes of NT threads
@@ -936,7 +946,8 @@ __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scr
     }
 }
 
-template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT, bool HYBRID = false>
+template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT, bool HYBRID = false,
+          bool BIG = false>
 __global__ void __launch_bounds__(NT) k_rec(FbParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -945,7 +956,7 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
     if constexpr (NSLOT > 0) {
-        RecRegs<Real, YREP, HAS_WB, NSLOT, NT, HYBRID> r;
+        RecRegs<Real, YREP, HAS_WB, NSLOT, NT, HYBRID, BIG> r;
         r.run(p, sd, od, b, dir, lds_raw);
     } else {
         rec_run<Real, YREP, HAS_WB, NT>(p, sd, od, b, dir, lds_raw);
@@ -1416,7 +1427,7 @@ constexpr int kHybridSlots = 26;
 struct RecVariant {
     int wide, nslot, yrep, has_wb, max_threads;
     RecKernel fn;
-    int hybrid = 0;
+    int hybrid = 0;  // 1: hybrid, 2: hybrid with the large LDS map
 };
 
 #define LFMMI_REC(REAL, WIDE, NSLOT, WB, NT)                                  \
@@ -1443,14 +1454,16 @@ const RecVariant kRecVariants[] = {
     // hybrid: 20 slots of a wave in registers, its other slices streamed
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true>, 1},
     {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true>, 1},
+    // ... with the LDS map for up to 12288 states
+    {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, true>, 2},
 };
 #undef LFMMI_REC
 
-const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, bool hybrid)
+const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, int hybrid)
 {
     for (const RecVariant& v : kRecVariants)
         if (v.wide == (wide ? 1 : 0) && v.nslot == nslot && v.yrep == (yrep ? 1 : 0) &&
-            v.has_wb == (has_wb ? 1 : 0) && v.hybrid == (hybrid ? 1 : 0))
+            v.has_wb == (has_wb ? 1 : 0) && v.hybrid == hybrid)
             return &v;
     return nullptr;
 }
@@ -1548,7 +1561,7 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     const bool wide = sizeof(Real) == 8;
     const RecVariant* rv =
         find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0,
-                 shape.rec_hybrid != 0);
+                 shape.rec_hybrid);
     if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
     if (bk.n > 1 && (e = hipEventRecord(bk.fork, stream)) != hipSuccess) return e;
 

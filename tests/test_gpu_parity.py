@@ -111,6 +111,17 @@ def test_graph_too_large_for_the_registers_keeps_part_of_each_wave_there():
     h.close()
 
 
+def test_large_graph_keeps_part_of_each_wave_in_registers_too():
+    # config 3's graph: more than 8192 states (48 KB state vectors in LDS)
+    wl = workloads.make_workload(3, scale={"B": 2, "Tlo": 8, "Thi": 25}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    assert info["rows"] > 8192 and 0 < info["register_slots"] < info["max_wave_slots"]
+    lz, gamma = oracle.forward_backward(wl["den"], wl["logits"], wl["lengths"], wl["leak"])
+    check(*run_gpu(h, wl["logits"], wl["lengths"], wl["leak"]), lz, gamma, "hybrid, large map")
+    h.close()
+
+
 def test_pdf_with_many_occupancy_rows_fp32_and_fp64():
     # one pdf on most arcs: its arc list is cut into many rows, whose sums a whole
     # wave adds up; with some final weights zero the graph runs in fp64
