@@ -192,3 +192,37 @@ def test_unsupported_sizes_and_invalid_arguments():
     assert rc == 1 and "not uploaded" in binding.lfmmi_last_error()
     h.close()
     lib.lfmmi_graph_destroy(None)  # no-op
+
+
+def test_fst_text_reader_round_trip_and_errors():
+    from paper_2005_09824_amd import fst_text
+    text = """0 1 3 3 0.5
+1 1 3 3 0.25
+1 2 5 5
+2 0.125
+"""
+    g = fst_text.read_fst_text(text.splitlines())
+    assert g["num_states"] == 3 and g["num_pdfs"] == 5
+    assert g["src"].tolist() == [0, 1, 1] and g["dst"].tolist() == [1, 1, 2]
+    assert g["pdf"].tolist() == [2, 2, 4]
+    assert np.allclose(g["logw"], [-0.5, -0.25, 0.0])
+    assert g["init_prob"].tolist() == [1.0, 0.0, 0.0]
+    assert np.allclose(g["final_prob"], [0.0, 0.0, np.exp(-0.125)])
+    # acceptor columns, explicit pdf count, another start state
+    g2 = fst_text.read_fst_text(["4 2 1 0.5", "2 2 2", "2"], num_pdfs=7, acceptor=True)
+    assert g2["num_states"] == 5 and g2["num_pdfs"] == 7 and g2["init_prob"][4] == 1.0
+    assert g2["final_prob"][2] == 1.0 and g2["pdf"].tolist() == [0, 1]
+    # what it writes it reads back
+    back = fst_text.read_fst_text(fst_text.write_fst_text(g))
+    for k in ("src", "dst", "pdf"):
+        assert back[k].tolist() == g[k].tolist()
+    assert np.allclose(back["logw"], g["logw"]) and np.allclose(back["final_prob"], g["final_prob"])
+    # the packer accepts it
+    h = binding.lfmmi_graph_pack(g)
+    assert binding.lfmmi_graph_info(h)["total_arcs"] == 3
+    h.close()
+    for bad in (["0 1 0 0 1.0"], ["0 1 x 1"], ["0 1 2 2 inf"], ["3"], ["0 1 2 2 0.1 9"]):
+        with pytest.raises(ValueError):
+            fst_text.read_fst_text(bad)
+    with pytest.raises(ValueError):
+        fst_text.read_fst_text(["0 1 9 9"], num_pdfs=4)
