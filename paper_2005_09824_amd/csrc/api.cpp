@@ -666,10 +666,22 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
         if (T == 0) want = 1;
         static const double upto[Buckets::kMax][Buckets::kMax] = {
             {1.0, 1.0, 1.0, 1.0}, {0.25, 1.0, 1.0, 1.0}, {0.15, 0.5, 1.0, 1.0}, {0.125, 0.375, 0.625, 1.0}};
+        double fr[Buckets::kMax];
+        for (int q = 0; q < Buckets::kMax; ++q) fr[q] = upto[want - 1][q];
+        if (const char* txt = std::getenv("LFMMI_BUCKET_FRACS")) {  // "f0,f1,f2": tuning
+            const char* c = txt;
+            for (int q = 0; q + 1 < want && *c; ++q) {
+                char* stop = nullptr;
+                const double v = std::strtod(c, &stop);
+                if (stop == c) break;
+                if (v > 0.0 && v <= 1.0) fr[q] = v;
+                c = *stop == ',' ? stop + 1 : stop;
+            }
+        }
         bk.n = want;
         int at = 0;
         for (int q = 0; q < want; ++q) {
-            int end = q == want - 1 ? B : (int)std::lround(upto[want - 1][q] * B);
+            int end = q == want - 1 ? B : (int)std::lround(fr[q] * B);
             end = std::max(at + 1, std::min(end, B - (want - 1 - q)));
             bk.first[q] = at;
             bk.count[q] = end - at;
