@@ -175,13 +175,16 @@ lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph *graph, int32_t g, int3
 /* Per-kernel timing with HIP events. While enabled, every lfmmi_forward_backward
  * on this handle records events around its kernels, on the streams they run on:
  * one emission, one recursion and one occupancy launch per bucket of sequences
- * (see lfmmi_forward_backward). lfmmi_profile_read waits for them and returns
- * mean durations per launch in milliseconds - ms[0] emission; [1] recursion
- * (alpha and beta, and the scales, which the last workgroup of a sequence
- * computes); [2] 0; [3] occupancy + gradient - with the number of calls in
- * *calls and of launches of each kernel in *launches (either may be NULL), then
- * forgets them. Launches of one call overlap: the means do not add up to the
- * time of a call. */
+ * (see lfmmi_forward_backward). enable: 0 off; 1 events around every kernel;
+ * 2 around the recursion launches only (half the events: they cost about 3 % of
+ * a call on the WSJ-shaped workload at level 1). Calls recorded at one level
+ * must be read before the level changes. lfmmi_profile_read waits for the
+ * events and returns mean durations per launch in milliseconds - ms[0] emission
+ * (0 at level 2); [1] recursion (alpha and beta, and the scales, which the last
+ * workgroup of a sequence computes); [2] 0; [3] occupancy + gradient (0 at
+ * level 2) - with the number of calls in *calls and of launches of each kernel
+ * in *launches (either may be NULL), then forgets them. Launches of one call
+ * overlap: the means do not add up to the time of a call. */
 lfmmi_status lfmmi_profile_enable(lfmmi_graph *graph, int enable);
 lfmmi_status lfmmi_profile_read(lfmmi_graph *graph, float ms[4], int32_t *calls,
                                 int32_t *launches);

@@ -246,7 +246,8 @@ def lfmmi_forward_backward(graph, logits, lengths, leak, grad_scale=1.0, accumul
 
 
 def lfmmi_profile_enable(graph, enable=True):
-    _check(load_library().lfmmi_profile_enable(graph.handle, 1 if enable else 0))
+    """enable: False / 0 off, True / 1 every kernel, 2 the recursion launches only."""
+    _check(load_library().lfmmi_profile_enable(graph.handle, int(enable)))
 
 
 def lfmmi_profile_read(graph):

@@ -85,7 +85,7 @@ struct lfmmi_graph {
     hipEvent_t join[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
 
     // profiling: per call made while enabled 4 * (its bucket count) events
-    bool profile = false;
+    int profile = 0;  // 0 off, 1 events around every kernel, 2 around the recursion only
     std::vector<hipEvent_t> ev;
     std::vector<int32_t> ev_buckets;  // bucket count of each profiled call
 };
@@ -643,6 +643,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     shape.rec_nslot = h->rec_nslot;
     shape.rec_yrep = h->rec_yrep ? 1 : 0;
     shape.rec_hybrid = h->rec_hybrid;
+    shape.profile_rec_only = h->profile == 2 ? 1 : 0;
     shape.rec_has_wb = h->has_wb ? 1 : 0;
     shape.occ_threads = h->occ_waves * kLanes;
     shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
@@ -779,7 +780,10 @@ lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph* h, int32_t g, int32_t 
 lfmmi_status lfmmi_profile_enable(lfmmi_graph* h, int enable)
 {
     if (!h) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
-    h->profile = enable != 0;
+    if (enable < 0 || enable > 2) return fail(LFMMI_ERR_INVALID_ARG, "enable must be 0, 1 or 2");
+    if (enable != h->profile && !h->ev_buckets.empty())
+        return fail(LFMMI_ERR_INVALID_ARG, "read the recorded calls before changing the level");
+    h->profile = enable;
     return LFMMI_OK;
 }
 
@@ -808,9 +812,9 @@ lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4], int32_t* calls, int
     for (size_t c = 0; c < n && st == LFMMI_OK; ++c) {
         for (int q = 0; q < h->ev_buckets[c] && st == LFMMI_OK; ++q) {
             const size_t b0 = at + 4 * (size_t)q;
-            elapsed(b0, b0 + 1, &sum[0]);
+            if (h->profile != 2) elapsed(b0, b0 + 1, &sum[0]);
             elapsed(b0 + 1, b0 + 2, &sum[1]);
-            elapsed(b0 + 2, b0 + 3, &sum[3]);
+            if (h->profile != 2) elapsed(b0 + 2, b0 + 3, &sum[3]);
             ++runs;
         }
         at += 4 * (size_t)h->ev_buckets[c];

@@ -84,6 +84,7 @@ struct LaunchShape {
     int rec_nslot;     // arc slots held in registers per lane (0: streamed)
     int rec_yrep;      // emission row replicated across LDS banks
     int rec_has_wb;    // arcs carry a per-arc leak factor
+    int profile_rec_only;  // of the four events per bucket record only those around k_rec
     int rec_hybrid;    // 1: only the first slots of a wave are register-resident;
                        // 2: the same, with the LDS map for up to 12288 states
     int occ_threads;   // workgroup size of the occupancy kernel

@@ -1591,7 +1591,10 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         const int nb = bk.count[q];
         hipEvent_t* evq = ev ? ev + 4 * q : nullptr;
 #define LFMMI_EVQ(i) \
-    if (evq) { e = hipEventRecord(evq[i], on); if (e != hipSuccess) return e; }
+    if (evq && (!shape.profile_rec_only || i == 1 || i == 2)) { \
+        e = hipEventRecord(evq[i], on); \
+        if (e != hipSuccess) return e; \
+    }
         LFMMI_EVQ(0)
         {  // also when T == 0: it resets the per-sequence tickets of k_rec
             dim3 grid(std::max(1, (p.T + 3) / 4), nb);
@@ -1627,11 +1630,19 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
         }
         LFMMI_EVQ(3)
 #undef LFMMI_EVQ
-        if (q > 0 && (e = hipEventRecord(bk.join[q], on)) != hipSuccess) return e;
     }
-    for (int q = 1; q < bk.n; ++q)
-        if (bk.count[q] > 0 && (e = hipStreamWaitEvent(stream, bk.join[q], 0)) != hipSuccess)
+    // Join: the streams wait for one another in a chain, last bucket first, and the
+    // caller's stream for the head of the chain only. Its own bucket ends last as a
+    // rule, and every wait it has to process then delays whatever follows the call.
+    int after = -1;  // the stream whose join event the next one in the chain waits for
+    for (int q = bk.n - 1; q >= 1; --q) {
+        if (bk.count[q] <= 0) continue;
+        if (after > 0 && (e = hipStreamWaitEvent(bk.streams[q], bk.join[after], 0)) != hipSuccess)
             return e;
+        if ((e = hipEventRecord(bk.join[q], bk.streams[q])) != hipSuccess) return e;
+        after = q;
+    }
+    if (after > 0 && (e = hipStreamWaitEvent(stream, bk.join[after], 0)) != hipSuccess) return e;
     return hipSuccess;
 }
 
