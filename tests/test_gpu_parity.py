@@ -321,3 +321,26 @@ def test_autograd_wrapper_gives_the_objective_and_its_gradient():
     assert abs(float(loss.item()) - (-want_objf.sum() / frames)) <= tol
     assert np.abs(x.grad.cpu().numpy().astype(np.float64) * (-frames) - want_grad).max() <= GRAD_ATOL
     den.close(); num.close()
+
+
+def test_profiling_levels_report_launch_durations_and_leave_results_alone():
+    wl = workloads.make_workload(2, scale={"S": 300, "B": 6, "Tlo": 20, "Thi": 60}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    plain = run_gpu(h, wl["logits"], wl["lengths"], wl["leak"])
+    for level, timed in ((1, ("emit", "rec", "occ")), (2, ("rec",))):
+        binding.lfmmi_profile_enable(h, level)
+        outs = [run_gpu(h, wl["logits"], wl["lengths"], wl["leak"]) for _ in range(2)]
+        with pytest.raises(binding.LfmmiError):  # recorded calls must be read first
+            binding.lfmmi_profile_enable(h, 3 - level)
+        pr = binding.lfmmi_profile_read(h)
+        binding.lfmmi_profile_enable(h, 0)
+        assert pr["calls"] == 2 and pr["launches"] >= 2
+        for k in ("emit", "rec", "occ"):
+            assert (pr[k] > 0.0) == (k in timed), (level, pr)
+        for o in outs:
+            assert np.array_equal(o[0], plain[0]) and np.array_equal(o[1], plain[1])
+    with pytest.raises(binding.LfmmiError):
+        binding.lfmmi_profile_read(h)  # nothing recorded
+    with pytest.raises(binding.LfmmiError):
+        binding.lfmmi_profile_enable(h, 7)
+    h.close()
