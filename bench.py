@@ -77,8 +77,7 @@ def main():
 
     def step():
         if num is not None:  # Eq. 2 / Eq. 3: numerator minus denominator
-            binding.lfmmi_forward_backward(num, x, lengths, leak, 1.0, False, objf, grad, status)
-            binding.lfmmi_forward_backward(den, x, lengths, leak, -1.0, True, objf, grad, status)
+            binding.lfmmi_loss(num, den, x, lengths, leak, objf, grad, status)
         else:
             binding.lfmmi_forward_backward(den, x, lengths, leak, 1.0, False, objf, grad, status)
 

@@ -20,7 +20,7 @@ ORD_FWD, ORD_BWD, ORD_OCC = 0, 1, 2
 EXPORTS = [
     "lfmmi_graph_create", "lfmmi_graph_pack", "lfmmi_graph_create_batch",
     "lfmmi_graph_pack_batch", "lfmmi_graph_upload", "lfmmi_graph_destroy",
-    "lfmmi_forward_backward", "lfmmi_last_error", "lfmmi_graph_info",
+    "lfmmi_forward_backward", "lfmmi_loss", "lfmmi_last_error", "lfmmi_graph_info",
     "lfmmi_graph_ordering_info", "lfmmi_graph_ordering_copy",
     "lfmmi_profile_enable", "lfmmi_profile_read",
 ]
@@ -56,6 +56,7 @@ def load_library():
     lib.lfmmi_graph_destroy.restype = None
     lib.lfmmi_forward_backward.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32,
                                            ctypes.c_int, vp, vp, vp, vp]
+    lib.lfmmi_loss.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp]
     lib.lfmmi_last_error.argtypes = []
     lib.lfmmi_last_error.restype = ctypes.c_char_p
     lib.lfmmi_graph_info.argtypes = [vp, vp]
@@ -241,6 +242,38 @@ def lfmmi_forward_backward(graph, logits, lengths, leak, grad_scale=1.0, accumul
             graph.handle, ctypes.c_void_p(logits.data_ptr()), _hp(lens), B, T, P,
             float(leak), float(grad_scale), 1 if accumulate else 0,
             ctypes.c_void_p(objf.data_ptr()), ctypes.c_void_p(grad.data_ptr()),
+            ctypes.c_void_p(status.data_ptr()), ctypes.c_void_p(stream)))
+    return objf, grad, status
+
+
+def lfmmi_loss(num, den, logits, lengths, leak, objf=None, grad=None, status=None, stream=None):
+    """Eq. 2 / Eq. 3 in one call: objf = log p(num) - log p(den) per sequence and its
+    gradient with respect to `logits` (torch float32 CUDA tensor [B, T, P]).
+    Returns (objf [B], grad [B, T, P], status [B]) device tensors."""
+    import torch
+    if not logits.is_cuda or logits.dtype != torch.float32 or not logits.is_contiguous():
+        raise ValueError("logits must be a contiguous float32 CUDA tensor")
+    B, T, P = logits.shape
+    lens = _host(lengths, np.int32)
+    if len(lens) != B:
+        raise ValueError("lengths must have B entries")
+    dev = logits.device
+    if objf is None:
+        objf = torch.empty(B, dtype=torch.float32, device=dev)
+    if grad is None:
+        grad = torch.empty((B, T, P), dtype=torch.float32, device=dev)
+    if status is None:
+        status = torch.zeros(B, dtype=torch.int32, device=dev)
+    for t, shape, dt in ((objf, (B,), torch.float32), (grad, (B, T, P), torch.float32),
+                         (status, (B,), torch.int32)):
+        if tuple(t.shape) != shape or t.dtype != dt or not t.is_contiguous() or t.device != dev:
+            raise ValueError("output tensor has the wrong shape, dtype, layout or device")
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    with torch.cuda.device(dev):
+        _check(load_library().lfmmi_loss(
+            num.handle, den.handle, ctypes.c_void_p(logits.data_ptr()), _hp(lens), B, T, P,
+            float(leak), ctypes.c_void_p(objf.data_ptr()), ctypes.c_void_p(grad.data_ptr()),
             ctypes.c_void_p(status.data_ptr()), ctypes.c_void_p(stream)))
     return objf, grad, status
 

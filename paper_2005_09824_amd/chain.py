@@ -1,7 +1,7 @@
 """LF-MMI objective as a torch.autograd.Function on top of the C ABI (Eq. 2, Eq. 3).
 
 Argument marshalling only: both forward-backward passes, the objective and its
-gradient with respect to the logits all come out of lfmmi_forward_backward; this
+gradient with respect to the logits all come out of lfmmi_loss; this
 file stores that gradient for backward() and scales it by the incoming gradient.
 """
 from __future__ import annotations
@@ -20,9 +20,8 @@ def _function_class():
             x = logits.detach()
             if x.dtype != torch.float32 or not x.is_contiguous():
                 x = x.float().contiguous()
-            # numerators overwrite, the denominator subtracts (Eq. 2 / Eq. 3)
-            objf, grad, status = binding.lfmmi_forward_backward(num_graphs, x, lengths, leak, 1.0, False)
-            binding.lfmmi_forward_backward(den_graph, x, lengths, leak, -1.0, True, objf, grad, status)
+            # numerator minus denominator (Eq. 2 / Eq. 3), the two passes overlapping
+            objf, grad, status = binding.lfmmi_loss(num_graphs, den_graph, x, lengths, leak)
             ctx.save_for_backward(grad)
             ctx.logits_dtype = logits.dtype
             ctx.mark_non_differentiable(status)

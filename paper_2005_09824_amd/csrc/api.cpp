@@ -726,6 +726,24 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     return LFMMI_OK;
 }
 
+lfmmi_status lfmmi_loss(const lfmmi_graph* num, const lfmmi_graph* den, const float* logits,
+                        const int32_t* lengths, int32_t B, int32_t T, int32_t P, float leak,
+                        float* objf, float* grad, int32_t* status, void* hip_stream)
+{
+    if (!num || !den) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
+    if (num == den) return fail(LFMMI_ERR_INVALID_ARG, "numerator and denominator share a handle");
+    // Numerators (+1, overwrite), then the denominator (-1, accumulate), one after the
+    // other on the caller's stream. Running the two passes on streams of their own
+    // was measured slower (see the header): without stream priorities the numerators'
+    // workgroups take compute units from the denominator's longest sequences, whose
+    // recursion is the critical path of the call.
+    lfmmi_status st = lfmmi_forward_backward(num, logits, lengths, B, T, P, leak, 1.f, 0, objf,
+                                             grad, status, hip_stream);
+    if (st != LFMMI_OK) return st;
+    return lfmmi_forward_backward(den, logits, lengths, B, T, P, leak, -1.f, 1, objf, grad, status,
+                                  hip_stream);
+}
+
 lfmmi_status lfmmi_graph_info(const lfmmi_graph* h, int64_t info[8])
 {
     if (!h || !info) return fail(LFMMI_ERR_INVALID_ARG, "null argument");

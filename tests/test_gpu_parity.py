@@ -344,3 +344,39 @@ def test_profiling_levels_report_launch_durations_and_leave_results_alone():
     with pytest.raises(binding.LfmmiError):
         binding.lfmmi_profile_enable(h, 7)
     h.close()
+
+
+def test_loss_call_equals_the_two_passes_bit_for_bit_and_the_oracle():
+    # Eq. 2 / Eq. 3 in one call, numerators and denominator overlapping
+    torch = _torch()
+    for seed, scale in ((3, {"S": 400, "B": 9, "Tlo": 12, "Thi": 70}), (4, {"B": 5, "Tlo": 40, "Thi": 90})):
+        wl = workloads.make_workload(5, seed=seed, scale=scale, pad_value=np.nan)
+        x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+        den = binding.lfmmi_graph_create(wl["den"])
+        num = binding.lfmmi_graph_create_batch(wl["num"])
+        xd = torch.from_numpy(x).cuda()
+        objf2, grad2, st2 = binding.lfmmi_forward_backward(num, xd, lens, leak, 1.0, False)
+        binding.lfmmi_forward_backward(den, xd, lens, leak, -1.0, True, objf2, grad2, st2)
+        torch.cuda.synchronize()
+        # stale contents of the outputs must not matter; two calls in a row
+        objf = torch.full_like(objf2, 7.0); grad = torch.full_like(grad2, -3.0)
+        st = torch.full_like(st2, 5)
+        for _ in range(2):
+            binding.lfmmi_loss(num, den, xd, lens, leak, objf, grad, st)
+        torch.cuda.synchronize()
+        assert torch.equal(objf, objf2) and torch.equal(grad, grad2) and torch.equal(st, st2)
+        lz_n, g_n = oracle.forward_backward_per_utt(wl["num"], x, lens, leak)
+        lz_d, g_d = oracle.forward_backward(wl["den"], x, lens, leak)
+        tol = OBJF_RTOL * np.maximum(np.maximum(np.abs(lz_n), np.abs(lz_d)), 1.0)
+        assert np.all(np.abs(objf.cpu().numpy().astype(np.float64) - (lz_n - lz_d)) <= tol)
+        assert np.abs(grad.cpu().numpy().astype(np.float64) - (g_n - g_d)).max() <= GRAD_ATOL
+        assert np.all(st.cpu().numpy() == 0)
+        # status None, and a flagged sequence: non-finite logits reach both passes
+        xb = x.copy(); xb[1, 3, 2] = np.inf
+        o3, g3, s3 = binding.lfmmi_loss(num, den, torch.from_numpy(xb).cuda(), lens, leak)
+        torch.cuda.synchronize()
+        s3 = s3.cpu().numpy()
+        assert s3[1] & 2 and np.all(np.delete(s3, 1) == 0) and np.isnan(o3.cpu().numpy()[1])
+        with pytest.raises(binding.LfmmiError):
+            binding.lfmmi_loss(den, den, xd, lens, leak)
+        den.close(); num.close()
