@@ -171,7 +171,8 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
  * a per-arc leak factor (non-uniform init_prob), [8] modelled LDS cycles of the
  * gathers of one frame (per slot and half-wave, the largest number of distinct
  * addresses in one of the 32 banks), [9] 1 if every FWD / BWD slice ends in a
- * closing slot (packed so when init_prob is not uniform), [10..11] 0. */
+ * closing slot (packed so when init_prob is not uniform), [10] number of hub
+ * slices (see below), [11] 0. */
 lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
                                        int32_t ord, int64_t info[12]);
 /* Copies the packed ordering out (any pointer may be NULL):
@@ -185,12 +186,18 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
  *              weight (FWD: 1 on real rows; BWD: init_prob of the row's state)
  *   row_id     [slices * 64] the state (FWD: to-state, BWD: from-state) or
  *              pdf-id (OCC) a row stands for, -1 for padding rows
+ *   slice_hub  [slices] 1 for a hub slice (FWD / BWD): a state with at least 64
+ *              arcs and far more than the others gets a slice of its own; its
+ *              row is that of lane 0, the arcs in all 64 lanes of the slice are
+ *              its arcs (the kernels add the lanes' sums up), and the other 63
+ *              rows are padding rows
  *   x-index / y-index: FWD (from-state in FWD numbering, pdf), BWD (to-state in
  *   BWD numbering, pdf), OCC (from-state in FWD numbering, to-state in BWD
  *   numbering), where a state's number in an ordering is the row it owns. */
 lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph *graph, int32_t g, int32_t ord,
                                        int32_t *slice_off, int32_t *wave_first,
-                                       uint32_t *key, float *w, int32_t *row_id);
+                                       uint32_t *key, float *w, int32_t *row_id,
+                                       int32_t *slice_hub);
 
 /* Per-kernel timing with HIP events. While enabled, every lfmmi_forward_backward
  * on this handle records events around its kernels, on the streams they run on:

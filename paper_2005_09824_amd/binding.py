@@ -61,7 +61,7 @@ def load_library():
     lib.lfmmi_last_error.restype = ctypes.c_char_p
     lib.lfmmi_graph_info.argtypes = [vp, vp]
     lib.lfmmi_graph_ordering_info.argtypes = [vp, i32, i32, vp]
-    lib.lfmmi_graph_ordering_copy.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.lfmmi_graph_ordering_copy.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.lfmmi_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.lfmmi_profile_read.argtypes = [vp, vp, vp, vp]
     for name in EXPORTS:
@@ -192,7 +192,7 @@ def lfmmi_graph_ordering_info(graph, g, ord_):
     info = np.zeros(12, dtype=np.int64)
     _check(load_library().lfmmi_graph_ordering_info(graph.handle, g, ord_, _hp(info)))
     keys = ("rows", "slices", "waves", "total_slots", "max_wave_slots", "register_slots",
-            "emission_replicated", "per_arc_leak", "gather_cycles", "closing_slots")
+            "emission_replicated", "per_arc_leak", "gather_cycles", "closing_slots", "hub_slices")
     return dict(zip(keys, (int(v) for v in info)))
 
 
@@ -203,9 +203,12 @@ def lfmmi_graph_ordering_copy(graph, g, ord_):
     key = np.zeros(info["total_slots"] * 64, dtype=np.uint32)
     w = np.zeros(info["total_slots"] * 64, dtype=np.float32)
     row_id = np.zeros(info["slices"] * 64, dtype=np.int32)
+    slice_hub = np.zeros(info["slices"], dtype=np.int32)
     _check(load_library().lfmmi_graph_ordering_copy(
-        graph.handle, g, ord_, _hp(slice_off), _hp(wave_first), _hp(key), _hp(w), _hp(row_id)))
-    return dict(info, slice_off=slice_off, wave_first=wave_first, key=key, w=w, row_id=row_id)
+        graph.handle, g, ord_, _hp(slice_off), _hp(wave_first), _hp(key), _hp(w), _hp(row_id),
+        _hp(slice_hub)))
+    return dict(info, slice_off=slice_off, wave_first=wave_first, key=key, w=w, row_id=row_id,
+                slice_hub=slice_hub)
 
 
 def lfmmi_forward_backward(graph, logits, lengths, leak, grad_scale=1.0, accumulate=False,

@@ -57,6 +57,7 @@ struct lfmmi_graph {
     bool wide = false;  // fp64 state vectors (some state is not final)
     int rec_nslot = 0;  // register-resident arc slots of the recursion kernel (0: streamed)
     bool rec_yrep = false;
+    bool rec_hubs = false;  // some FWD / BWD ordering has hub slices
     int rec_hybrid = 0;  // 1, 2: rec_nslot slots of a wave in registers, its others streamed
                          // (2: LDS map for up to 12288 states)
     bool has_wb = false;  // arcs carry a per-arc leak factor (some init_prob is not uniform)
@@ -164,6 +165,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         tune.emission_conflicts = !h->rec_yrep;
         tune.balance_banks = !h->wide && env_int("LFMMI_BALANCE", 1) != 0;
         tune.order_slots = !h->wide && env_int("LFMMI_ORDER", 1) != 0;
+        tune.hub_slices = env_int("LFMMI_HUBS", 1) != 0;
 
         int waves = 1;
         for (int32_t g = 0; g < n; ++g)
@@ -198,6 +200,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             h->occ_waves = std::min(by_arcs, env_int("LFMMI_OCC_WAVES", cap));
             h->packed.assign(n, PackedGraph());
             h->max_rows_f = h->max_rows_b = h->max_rows_occ = 0;
+            h->rec_hubs = false;
             *max_slots = 0;
             for (int32_t g = 0; g < n; ++g) {
                 bool bad = false;
@@ -209,8 +212,10 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
                 h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
                 h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
                 h->max_rows_occ = std::max(h->max_rows_occ, h->packed[g].ord[2].num_slices * kLanes);
-                for (int o = 0; o < 2; ++o)
+                for (int o = 0; o < 2; ++o) {
                     *max_slots = std::max(*max_slots, h->packed[g].ord[o].max_wave_slots);
+                    for (int32_t f : h->packed[g].ord[o].slice_hub) h->rec_hubs = h->rec_hubs || f != 0;
+                }
             }
             return LFMMI_OK;
         };
@@ -319,6 +324,8 @@ lfmmi_status upload(lfmmi_graph* h)
     const size_t at_recs = reserve<uint2>(&total, n_slots * kLanes);
     const size_t at_wb = reserve<float>(&total, n_slots * kLanes);
     const size_t at_mask = reserve<uint64_t>(&total, n_mask);
+    const size_t at_hubmask = reserve<uint64_t>(&total, n_mask);
+    const size_t at_shub = reserve<int32_t>(&total, n_soff);
     const size_t at_soff = reserve<int32_t>(&total, n_soff);
     const size_t at_wf = reserve<int32_t>(&total, n_wf);
     const size_t at_vinit = reserve<float>(&total, n_vec);
@@ -356,6 +363,12 @@ lfmmi_status upload(lfmmi_graph* h)
             if (!od.wave_mask.empty())
                 std::memcpy(host.data() + at_mask + (size_t)d.mask_at * 8, od.wave_mask.data(),
                             od.wave_mask.size() * 8);
+            if (!od.wave_hub.empty())
+                std::memcpy(host.data() + at_hubmask + (size_t)d.mask_at * 8, od.wave_hub.data(),
+                            od.wave_hub.size() * 8);
+            if (!od.slice_hub.empty())  // indexed like slice_off (one entry fewer)
+                std::memcpy(host.data() + at_shub + (size_t)d.slice_off_at * 4, od.slice_hub.data(),
+                            od.slice_hub.size() * 4);
             std::memcpy(host.data() + at_soff + (size_t)d.slice_off_at * 4, od.slice_off.data(),
                         od.slice_off.size() * 4);
             std::memcpy(host.data() + at_wf + (size_t)d.wave_first_at * 4, od.wave_first.data(),
@@ -390,6 +403,8 @@ lfmmi_status upload(lfmmi_graph* h)
     h->dg.recs = reinterpret_cast<const uint2*>(base + at_recs);
     h->dg.wb = reinterpret_cast<const float*>(base + at_wb);
     h->dg.wave_mask = reinterpret_cast<const uint64_t*>(base + at_mask);
+    h->dg.wave_hub = reinterpret_cast<const uint64_t*>(base + at_hubmask);
+    h->dg.slice_hub = reinterpret_cast<const int32_t*>(base + at_shub);
     h->dg.slice_off = reinterpret_cast<const int32_t*>(base + at_soff);
     h->dg.wave_first = reinterpret_cast<const int32_t*>(base + at_wf);
     h->dg.vinit = reinterpret_cast<const float*>(base + at_vinit);
@@ -643,6 +658,7 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     shape.rec_nslot = h->rec_nslot;
     shape.rec_yrep = h->rec_yrep ? 1 : 0;
     shape.rec_hybrid = h->rec_hybrid;
+    shape.rec_hubs = h->rec_hubs ? 1 : 0;
     shape.profile_rec_only = h->profile == 2 ? 1 : 0;
     shape.rec_has_wb = h->has_wb ? 1 : 0;
     shape.occ_threads = h->occ_waves * kLanes;
@@ -775,13 +791,15 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t 
     info[7] = o.has_wb;
     info[8] = o.gather_cycles;
     info[9] = ord < 2 ? o.closing_slots : 0;
-    info[10] = info[11] = 0;
+    info[10] = 0;
+    for (int32_t f : o.slice_hub) info[10] += f != 0;
+    info[11] = 0;
     return LFMMI_OK;
 }
 
 lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph* h, int32_t g, int32_t ord,
                                        int32_t* slice_off, int32_t* wave_first, uint32_t* key,
-                                       float* w, int32_t* row_id)
+                                       float* w, int32_t* row_id, int32_t* slice_hub)
 {
     if (!h) return fail(LFMMI_ERR_INVALID_ARG, "null argument");
     if (g < 0 || g >= h->num_graphs || ord < 0 || ord > 2)
@@ -792,6 +810,9 @@ lfmmi_status lfmmi_graph_ordering_copy(const lfmmi_graph* h, int32_t g, int32_t 
     if (key) std::memcpy(key, o.key.data(), o.key.size() * 4);
     if (w) std::memcpy(w, o.w.data(), o.w.size() * 4);
     if (row_id) std::memcpy(row_id, o.row_id.data(), o.row_id.size() * 4);
+    if (slice_hub)
+        for (int32_t sl = 0; sl < o.num_slices; ++sl)
+            slice_hub[sl] = (size_t)sl < o.slice_hub.size() ? o.slice_hub[sl] : 0;
     return LFMMI_OK;
 }
 

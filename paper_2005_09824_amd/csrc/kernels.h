@@ -30,6 +30,8 @@ struct DeviceGraph {
                                 // [(q * 64 + l) * 2 + (0, 1)]
     const float* wb;            // w * b[from] per record (0 where unused), same indexing
     const uint64_t* wave_mask;  // closing-slot bit masks of the FWD/BWD waves
+    const uint64_t* wave_hub;   // ... those of them that close a hub slice (same indexing)
+    const int32_t* slice_hub;   // FWD/BWD: 1 for a hub slice; indexed like slice_off
     const int32_t* slice_off;   // slot offsets, local to the ordering
     const int32_t* wave_first;
     const float* vinit;
@@ -84,6 +86,7 @@ struct LaunchShape {
     int rec_nslot;     // arc slots held in registers per lane (0: streamed)
     int rec_yrep;      // emission row replicated across LDS banks
     int rec_has_wb;    // arcs carry a per-arc leak factor
+    int rec_hubs;      // some graph of the handle has hub slices
     int profile_rec_only;  // of the four events per bucket record only those around k_rec
     int rec_hybrid;    // 1: only the first slots of a wave are register-resident;
                        // 2: the same, with the LDS map for up to 12288 states

@@ -129,7 +129,7 @@ __device__ __forceinline__ uint2 rec_hi(const uint4 r) { return make_uint2(r.z, 
 // n_t = sum(v_t), s_t = a . v_t, which every lane derives from the 16 wave
 // partials after the single barrier of the step. For an arc into row j:
 //   v_{t+1}[j] = (1/n_t) * sum w e v_t[from] + (eps s_t / n_t) * sum (w b[from]) e
-template <typename Real, bool YREP, bool HAS_WB, int NT>
+template <typename Real, bool YREP, bool HAS_WB, int NT, bool HUBS>
 __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
                                         const int b, const int dir, unsigned char* lds_raw)
 {
@@ -160,6 +160,7 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
     const uint4* recs = rec_pairs(p, od, lane);
     const float2* wbp = wb_pairs(p, od, lane);
     const int32_t* so = p.g.slice_off + od.slice_off_at;
+    const int32_t* hub = p.g.slice_hub + od.slice_off_at;
     const Real eps = (Real)p.leak;
     const Real bconst = (Real)od.b_const;
 
@@ -169,6 +170,14 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
         s1 = p.g.wave_first[od.wave_first_at + wave + 1];
     }
     const size_t erow0 = (size_t)b * p.T;
+    // which of the wave's slices are hub slices: bits for its first 64, a load beyond
+    uint64_t hub_bits = 0;
+    if (HUBS)
+        for (int sl = s0; sl < s1 && sl - s0 < 64; ++sl)
+            if (hub[sl]) hub_bits |= (uint64_t)1 << (sl - s0);
+    auto hub_at = [&](const int sl) {
+        return sl - s0 < 64 ? ((hub_bits >> (sl - s0)) & 1) != 0 : hub[sl] != 0;
+    };
 
     if (tid < 64) part[tid] = 0;  // partials of waves that do not exist stay 0
     __syncthreads();
@@ -272,7 +281,13 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
                     else closing_w = r.w;
                 }
                 const int row = sl * 64 + lane;
-                const Real v = inv * acc1 + cb * acc2;
+                const bool hub_slice = HUBS && hub_at(sl);  // wave-uniform
+                if (hub_slice) {  // its 64 lanes hold the arcs of lane 0's row
+                    acc1 = wave_sum(acc1);
+                    acc2 = wave_sum(acc2);
+                }
+                Real v = inv * acc1 + cb * acc2;
+                if (hub_slice && lane != 0) v = 0;
                 Xn[row] = v;
                 tr[row] = v;
                 n += v;
@@ -462,8 +477,10 @@ __host__ __device__ constexpr int stage_passes(bool yrep, int nt)
 // large for the registers: less record traffic than streaming everything).
 // BIG: state vectors of 48 KB and emission rows of 16 KB (graphs of up to 12288
 // states) instead of 32 KB each.
+// HUBS: the graph has hub slices (64 lanes that share one row's arcs, added up where
+// the slice ends); variants without it carry none of that code.
 template <typename Real, bool YREP, bool HAS_WB, int NSLOT, int NT, bool HYBRID = false,
-          bool BIG = false>
+          bool BIG = false, bool HUBS = false>
 struct RecRegs {
     static_assert(!HYBRID || (!HAS_WB && sizeof(Real) == 4), "hybrid: fp32, constant leak weights");
     static_assert(!BIG || (HYBRID && !YREP), "the large map: hybrid, plain emission rows");
@@ -534,10 +551,12 @@ struct RecRegs {
     template <int PAR>
     __device__ __forceinline__ void step(const int k, const int T, const int tid, const int lane,
                                          const Real eps, const Real aconst, const Real bconst,
-                                         const uint64_t mask, const uint32_t row4_first,
+                                         const uint64_t mask, const uint64_t hubmask,
+                                         const uint32_t row4_first,
                                          const uint32_t part_at, const int nsl,
                                          const int sl_stream, const int sl_end,
                                          const int first_streamed, const int32_t* so,
+                                         const uint64_t hub_bits, const int32_t* hub,
                                          const uint4* recs)
     {
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
@@ -642,7 +661,13 @@ struct RecRegs {
                 acc2 += HAS_WB ? (Real)(wbr[HAS_WB ? i + 1 : 0] * e1) : (Real)t1;
             }
             if (__builtin_expect(i + 1 == next_close, 0)) {  // wave-uniform: a slice ends
-                const Real v = inv * acc1 + cb * acc2;
+                const bool hub_slice = HUBS && ((hubmask >> (i + 1)) & 1);
+                if (hub_slice) {  // its 64 lanes hold the arcs of lane 0's row
+                    acc1 = wave_sum_uniform(acc1);
+                    acc2 = wave_sum_uniform(acc2);
+                }
+                Real v = inv * acc1 + cb * acc2;
+                if (hub_slice && lane != 0) v = 0;
                 lds_st(xn + row4, v);
                 *reinterpret_cast<Real*>(tr + row4) = v;
                 n += v;
@@ -681,7 +706,15 @@ struct RecRegs {
                     rp += 64;
                     slot(rec_lo(r0)); slot(rec_hi(r0));
                 }
-                const Real v = inv * a1 + cb * a2;
+                const bool hub_slice =
+                    HUBS && (sl - sl_stream < 64 ? ((hub_bits >> (sl - sl_stream)) & 1) != 0
+                                                 : hub[sl] != 0);
+                if (hub_slice) {
+                    a1 = wave_sum_uniform(a1);
+                    a2 = wave_sum_uniform(a2);
+                }
+                Real v = inv * a1 + cb * a2;
+                if (hub_slice && lane != 0) v = 0;
                 const uint32_t at = (uint32_t)(sl * 64 + lane) * kRB;
                 lds_st(xn + at, v);
                 *reinterpret_cast<Real*>(tr + at) = v;
@@ -730,14 +763,17 @@ struct RecRegs {
         const Real bconst = (Real)od.b_const;
         const float* erows = p.emis + (size_t)b * p.T * P;  // this sequence's emission rows
 
+        const int32_t* hub = p.g.slice_hub + od.slice_off_at;
         int s0 = 0, s1 = 0;
-        uint64_t mask = 0;
+        uint64_t mask = 0, hubmask = 0;
         if (wave < od.num_waves) {
             s0 = p.g.wave_first[od.wave_first_at + wave];
             s1 = p.g.wave_first[od.wave_first_at + wave + 1];
             mask = p.g.wave_mask[od.mask_at + wave];
+            hubmask = p.g.wave_hub[od.mask_at + wave];
         }
         const int first = so[s0];
+        uint64_t hub_bits = 0;  // hub slices among the streamed ones, from sl_stream on
         int sl_stream = s1;  // first slice with streamed records
         int nsl = so[s1] - first;
         if constexpr (HYBRID) {
@@ -745,11 +781,17 @@ struct RecRegs {
             // the mask, the one that straddles the limit is finished from L2
             nsl = min(nsl, NSLOT);
             mask = 0;
+            hubmask = 0;
             sl_stream = s0;
             while (sl_stream < s1 && so[sl_stream + 1] - first <= nsl) {
-                mask |= (uint64_t)1 << (so[sl_stream + 1] - 1 - first);
+                const uint64_t bit = (uint64_t)1 << (so[sl_stream + 1] - 1 - first);
+                mask |= bit;
+                if (HUBS && hub[sl_stream]) hubmask |= bit;
                 ++sl_stream;
             }
+            if (HUBS)  // bits for the first 64 streamed slices, a load beyond
+                for (int sl = sl_stream; sl < s1 && sl - sl_stream < 64; ++sl)
+                    if (hub[sl]) hub_bits |= (uint64_t)1 << (sl - sl_stream);
         }
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
@@ -836,13 +878,13 @@ struct RecRegs {
         const uint32_t part_at = ((uint32_t)wave + (HAS_WB && lane >= 32 ? 16u : 0u)) * kRB;
         int k = 1;
         for (; k + 1 <= T; k += 2) {
-            step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl, sl_stream, s1,
-                    first + nsl, so, recs);
-            step<0>(k + 1, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl, sl_stream, s1,
-                    first + nsl, so, recs);
+            step<1>(k, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
+                    sl_stream, s1, first + nsl, so, hub_bits, hub, recs);
+            step<0>(k + 1, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
+                    sl_stream, s1, first + nsl, so, hub_bits, hub, recs);
         }
-        if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, part_at, nsl, sl_stream, s1,
-                    first + nsl, so, recs);
+        if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
+                    sl_stream, s1, first + nsl, so, hub_bits, hub, recs);
 
         // ---- last scalars and the closing dot product
         {
@@ -947,7 +989,7 @@ __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scr
 }
 
 template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT, bool HYBRID = false,
-          bool BIG = false>
+          bool BIG = false, bool HUBS = false>
 __global__ void __launch_bounds__(NT) k_rec(FbParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -956,10 +998,10 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
     if constexpr (NSLOT > 0) {
-        RecRegs<Real, YREP, HAS_WB, NSLOT, NT, HYBRID, BIG> r;
+        RecRegs<Real, YREP, HAS_WB, NSLOT, NT, HYBRID, BIG, HUBS> r;
         r.run(p, sd, od, b, dir, lds_raw);
     } else {
-        rec_run<Real, YREP, HAS_WB, NT>(p, sd, od, b, dir, lds_raw);
+        rec_run<Real, YREP, HAS_WB, NT, HUBS>(p, sd, od, b, dir, lds_raw);
     }
     // The workgroup that finishes a sequence second (alpha or beta) computes its
     // scales: no launch of their own, and no wait for the other sequences.
@@ -1428,11 +1470,14 @@ struct RecVariant {
     int wide, nslot, yrep, has_wb, max_threads;
     RecKernel fn;
     int hybrid = 0;  // 1: hybrid, 2: hybrid with the large LDS map
+    int hubs = 0;    // handles hub slices
 };
 
-#define LFMMI_REC(REAL, WIDE, NSLOT, WB, NT)                                  \
-    {WIDE, NSLOT, 0, WB, NT, k_rec<REAL, NSLOT, false, (WB != 0), NT>},       \
-    {WIDE, NSLOT, 1, WB, NT, k_rec<REAL, NSLOT, true, (WB != 0), NT>}
+#define LFMMI_REC(REAL, WIDE, NSLOT, WB, NT)                                                    \
+    {WIDE, NSLOT, 0, WB, NT, k_rec<REAL, NSLOT, false, (WB != 0), NT>},                         \
+    {WIDE, NSLOT, 1, WB, NT, k_rec<REAL, NSLOT, true, (WB != 0), NT>},                          \
+    {WIDE, NSLOT, 0, WB, NT, k_rec<REAL, NSLOT, false, (WB != 0), NT, false, false, true>, 0, 1}, \
+    {WIDE, NSLOT, 1, WB, NT, k_rec<REAL, NSLOT, true, (WB != 0), NT, false, false, true>, 0, 1}
 const RecVariant kRecVariants[] = {
     // streamed arcs
     LFMMI_REC(float, 0, 0, 0, 1024), LFMMI_REC(float, 0, 0, 1, 1024),
@@ -1456,14 +1501,18 @@ const RecVariant kRecVariants[] = {
     {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true>, 1},
     // ... with the LDS map for up to 12288 states
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, true>, 2},
+    // ... and the three for graphs with hub slices
+    {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, false, true>, 1, 1},
+    {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true, false, true>, 1, 1},
+    {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, true, true>, 2, 1},
 };
 #undef LFMMI_REC
 
-const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, int hybrid)
+const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, int hybrid, bool hubs)
 {
     for (const RecVariant& v : kRecVariants)
         if (v.wide == (wide ? 1 : 0) && v.nslot == nslot && v.yrep == (yrep ? 1 : 0) &&
-            v.has_wb == (has_wb ? 1 : 0) && v.hybrid == hybrid)
+            v.has_wb == (has_wb ? 1 : 0) && v.hybrid == hybrid && v.hubs == (hubs ? 1 : 0))
             return &v;
     return nullptr;
 }
@@ -1561,7 +1610,7 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     const bool wide = sizeof(Real) == 8;
     const RecVariant* rv =
         find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0,
-                 shape.rec_hybrid);
+                 shape.rec_hybrid, shape.rec_hubs != 0);
     if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
     if (bk.n > 1 && (e = hipEventRecord(bk.fork, stream)) != hipSuccess) return e;
 

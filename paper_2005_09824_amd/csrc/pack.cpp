@@ -17,22 +17,31 @@ struct Arrangement {
     std::vector<int32_t> pos;  // row -> slice * 64 + lane
     std::vector<int32_t> slice_width;
     std::vector<int32_t> wave_first;
+    std::vector<int32_t> slice_hub;  // 1: a hub slice (all 64 lanes work for the row of lane 0)
     int32_t num_slices = 0, num_waves = 0, max_wave_slots = 0;
 };
 
-Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots)
+// hub[r] != 0: row r gets a slice of its own and its len[r] arcs are spread over
+// the 64 lanes (a row with far more arcs than the others would otherwise make
+// its slice, and so its wave, that many slots long).
+Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots,
+                    const std::vector<uint8_t>* hub = nullptr)
 {
     Arrangement ar;
     const int32_t R = (int32_t)len.size();
-    ar.num_slices = (R + kLanes - 1) / kLanes;
+    std::vector<int32_t> idx, hubs;
+    for (int32_t r = 0; r < R; ++r) (hub && (*hub)[r] ? hubs : idx).push_back(r);
+    const int32_t plain = (int32_t)idx.size();
+    const int32_t plain_slices = (plain + kLanes - 1) / kLanes;
+    ar.num_slices = plain_slices + (int32_t)hubs.size();
     ar.num_waves = std::max(1, std::min(waves, ar.num_slices));
-    std::vector<int32_t> idx(R);
-    std::iota(idx.begin(), idx.end(), 0);
     std::stable_sort(idx.begin(), idx.end(),
                      [&](int32_t a, int32_t b) { return len[a] > len[b]; });
     std::vector<int32_t> sorted_width(ar.num_slices);
-    for (int32_t s = 0; s < ar.num_slices; ++s)
+    for (int32_t s = 0; s < plain_slices; ++s)
         sorted_width[s] = std::max(len[idx[(size_t)s * kLanes]] + extra_slots, 1);
+    for (size_t h = 0; h < hubs.size(); ++h)
+        sorted_width[plain_slices + h] = (len[hubs[h]] + kLanes - 1) / kLanes + extra_slots;
     // Widths are even, with one more padding slot where needed: the kernels load
     // the records of two slots at a time (16 bytes per lane stream at twice the rate
     // of 8), and the register-resident recursion looks for the end of a slice at
@@ -86,16 +95,22 @@ Arrangement arrange(const std::vector<int32_t>& len, int waves, int extra_slots)
     for (int w = 0; w < ar.num_waves; ++w) std::sort(owned[w].begin(), owned[w].end());
     ar.pos.assign(R, 0);
     ar.slice_width.clear();
+    ar.slice_hub.clear();
     ar.wave_first.assign(ar.num_waves + 1, 0);
     int32_t next = 0;
     for (int w = 0; w < ar.num_waves; ++w) {
         ar.wave_first[w] = next;
         for (int32_t s : owned[w]) {
-            for (int l = 0; l < kLanes; ++l) {
-                size_t i = (size_t)s * kLanes + l;
-                if (i < (size_t)R) ar.pos[idx[i]] = next * kLanes + l;
+            if (s >= plain_slices) {
+                ar.pos[hubs[s - plain_slices]] = next * kLanes;  // lane 0 owns the row
+            } else {
+                for (int l = 0; l < kLanes; ++l) {
+                    size_t i = (size_t)s * kLanes + l;
+                    if (i < (size_t)plain) ar.pos[idx[i]] = next * kLanes + l;
+                }
             }
             ar.slice_width.push_back(sorted_width[s]);
+            ar.slice_hub.push_back(s >= plain_slices ? 1 : 0);
             ++next;
         }
         ar.max_wave_slots = std::max<int32_t>(ar.max_wave_slots, (int32_t)load[w]);
@@ -111,6 +126,7 @@ void start_ordering(const Arrangement& ar, int32_t num_rows, Ordering* o)
     o->num_waves = ar.num_waves;
     o->max_wave_slots = ar.max_wave_slots;
     o->wave_first = ar.wave_first;
+    o->slice_hub = ar.slice_hub;
     o->slice_off.assign(ar.num_slices + 1, 0);
     for (int32_t s = 0; s < ar.num_slices; ++s)
         o->slice_off[s + 1] = o->slice_off[s] + ar.slice_width[s];
@@ -129,16 +145,21 @@ inline void put(Ordering* o, int32_t position, int32_t nth, uint32_t x, uint32_t
 }
 
 
-// wave_mask[w]: bit i set when slot i of wave w closes a slice.
+// wave_mask[w]: bit i set when slot i of wave w closes a slice; wave_hub[w]: the
+// same bit when that slice is a hub slice.
 void fill_wave_mask(Ordering* o)
 {
     o->wave_mask.assign(o->num_waves, 0);
+    o->wave_hub.assign(o->num_waves, 0);
     for (int32_t wv = 0; wv < o->num_waves; ++wv) {
         const int32_t first = o->slice_off[o->wave_first[wv]];
         const int32_t count = o->slice_off[o->wave_first[wv + 1]] - first;
         if (count > 64) continue;
-        for (int32_t sl = o->wave_first[wv]; sl < o->wave_first[wv + 1]; ++sl)
-            o->wave_mask[wv] |= (uint64_t)1 << (o->slice_off[sl + 1] - 1 - first);
+        for (int32_t sl = o->wave_first[wv]; sl < o->wave_first[wv + 1]; ++sl) {
+            const uint64_t bit = (uint64_t)1 << (o->slice_off[sl + 1] - 1 - first);
+            o->wave_mask[wv] |= bit;
+            if (o->slice_hub[sl]) o->wave_hub[wv] |= bit;
+        }
     }
 }
 
@@ -540,8 +561,21 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     for (int64_t a = 0; a < A; ++a) { ++indeg[g.dst[a]]; ++outdeg[g.src[a]]; }
     // with a uniform pi the leak-dot weights are constants and need no slot
     const int closing = per_arc_leak ? 1 : 0;
-    Arrangement af = arrange(indeg, rec_waves, closing);
-    Arrangement ab = arrange(outdeg, rec_waves, closing);
+    // Hub rows: at least 64 arcs and more than four times what nine rows in ten
+    // have. Such a row gets a slice of its own, its arcs dealt to the 64 lanes; the
+    // kernels add the lanes' sums up where the slice ends.
+    auto hubs_of = [&](const std::vector<int32_t>& deg) {
+        std::vector<int32_t> sorted(deg);
+        std::sort(sorted.begin(), sorted.end());
+        const int64_t usual = sorted[(size_t)((int64_t)(S - 1) * 9 / 10)];
+        std::vector<uint8_t> hub(S, 0);
+        for (int32_t s = 0; s < S; ++s)
+            hub[s] = tune.hub_slices && deg[s] >= kLanes && deg[s] > 4 * usual ? 1 : 0;
+        return hub;
+    };
+    const std::vector<uint8_t> hub_f = hubs_of(indeg), hub_b = hubs_of(outdeg);
+    Arrangement af = arrange(indeg, rec_waves, closing, &hub_f);
+    Arrangement ab = arrange(outdeg, rec_waves, closing, &hub_b);
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {
@@ -558,12 +592,16 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     for (int64_t a = 0; a < A; ++a) w[a] = (float)std::exp((double)g.logw[a]);
     // slot of every arc inside its row, per ordering
     std::vector<int32_t> nth_f(A), nth_b(A);
+    // position (slice * 64 + lane) of the row an arc is stored in: its state's row,
+    // or for a hub the next of the 64 lanes of the hub's slice
+    std::vector<int32_t> prow_f(A), prow_b(A);
     {
-        std::vector<int32_t> prow_f(A), prow_b(A), wf(af.num_slices), wb_(ab.num_slices);
+        std::vector<int32_t> wf(af.num_slices), wb_(ab.num_slices), dealt_f(S, 0), dealt_b(S, 0);
         std::vector<int16_t> bxf(A), bxb(A), byy(A);
         for (int64_t a = 0; a < A; ++a) {
-            prow_f[a] = af.pos[g.dst[a]];
-            prow_b[a] = ab.pos[g.src[a]];
+            const int32_t i = g.src[a], j = g.dst[a];
+            prow_f[a] = af.pos[j] + (hub_f[j] ? dealt_f[j]++ % kLanes : 0);
+            prow_b[a] = ab.pos[i] + (hub_b[i] ? dealt_b[i]++ % kLanes : 0);
             bxf[a] = (int16_t)(af.pos[g.src[a]] % kBanks);
             bxb[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);
             byy[a] = tune.emission_conflicts ? (int16_t)(g.pdf[a] % kBanks) : (int16_t)-1;
@@ -574,16 +612,17 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             order_slots(prow_f, bxf, byy, af.num_slices, wf, &nth_f);
             order_slots(prow_b, bxb, byy, ab.num_slices, wb_, &nth_b);
         } else {
-            std::vector<int32_t> nf(S, 0), nb(S, 0);
+            std::vector<int32_t> nf((size_t)af.num_slices * kLanes, 0),
+                nb((size_t)ab.num_slices * kLanes, 0);
             for (int64_t a = 0; a < A; ++a) {
-                nth_f[a] = nf[g.dst[a]]++;
-                nth_b[a] = nb[g.src[a]]++;
+                nth_f[a] = nf[prow_f[a]]++;
+                nth_b[a] = nb[prow_b[a]]++;
             }
         }
         for (int64_t a = 0; a < A; ++a) {
             const int32_t i = g.src[a], j = g.dst[a];
-            put(&out->ord[0], af.pos[j], nth_f[a], (uint32_t)af.pos[i], (uint32_t)g.pdf[a], w[a]);
-            put(&out->ord[1], ab.pos[i], nth_b[a], (uint32_t)ab.pos[j], (uint32_t)g.pdf[a], w[a]);
+            put(&out->ord[0], prow_f[a], nth_f[a], (uint32_t)af.pos[i], (uint32_t)g.pdf[a], w[a]);
+            put(&out->ord[1], prow_b[a], nth_b[a], (uint32_t)ab.pos[j], (uint32_t)g.pdf[a], w[a]);
         }
     }
 
@@ -633,8 +672,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             of.wb.assign(of.w.size(), 0.f);
             ob.wb.assign(ob.w.size(), 0.f);
             for (int64_t a = 0; a < A; ++a) {
-                const int32_t i = g.src[a], j = g.dst[a];
-                const int32_t pf = af.pos[j], pb = ab.pos[i];
+                const int32_t i = g.src[a];
+                const int32_t pf = prow_f[a], pb = prow_b[a];
                 of.wb[(size_t)(of.slice_off[pf / kLanes] + nth_f[a]) * kLanes + pf % kLanes] =
                     w[a] * g.init_prob[i];
                 ob.wb[(size_t)(ob.slice_off[pb / kLanes] + nth_b[a]) * kLanes + pb % kLanes] = w[a];

@@ -44,6 +44,12 @@ struct Ordering {
     int32_t closing_slots = 0;
     float a_const = 0.f;
     std::vector<uint64_t> wave_mask;  // [num_waves]
+    // Hub slices (FWD / BWD): slice_hub[s] != 0 when the 64 lanes of slice s all hold
+    // arcs of the row of lane 0 (a row with far more arcs than the others); its
+    // other 63 rows are padding rows. wave_hub[w]: the bits of wave_mask[w] that
+    // belong to hub slices.
+    std::vector<int32_t> slice_hub;   // [num_slices]
+    std::vector<uint64_t> wave_hub;   // [num_waves]
     int64_t gather_cycles = 0;        // modelled LDS cycles of the gathers of one frame
     float b_const = 0.f;              // leak target when it is one constant (BWD 1, FWD uniform pi)
     int32_t has_wb = 0;               // wb is filled
@@ -87,6 +93,7 @@ struct PackTuning {
     bool balance_banks = true;        // re-deal lanes inside half-slices (state -> bank)
     bool order_slots = true;          // order each row's arcs over its slots
     bool emission_conflicts = true;   // the emission gather can conflict (row not replicated)
+    bool hub_slices = true;           // rows with far more arcs than the others get a slice each
 };
 
 // per_arc_leak: fill the per-arc leak factors (required when init_prob is not

@@ -380,3 +380,52 @@ def test_loss_call_equals_the_two_passes_bit_for_bit_and_the_oracle():
         with pytest.raises(binding.LfmmiError):
             binding.lfmmi_loss(den, den, xd, lens, leak)
         den.close(); num.close()
+
+
+def _with_hubs(g, rng, in_hub, out_hub):
+    S, P = g["num_states"], g["num_pdfs"]
+    src = rng.choice(S, size=in_hub, replace=False).astype(np.int32)
+    dst = rng.choice(S, size=out_hub, replace=False).astype(np.int32)
+    g["src"] = np.concatenate([g["src"], src, np.full(out_hub, 3, np.int32)])
+    g["dst"] = np.concatenate([g["dst"], np.full(in_hub, 5, np.int32), dst])
+    n = in_hub + out_hub
+    g["pdf"] = np.concatenate([g["pdf"], rng.integers(0, P, n).astype(np.int32)])
+    g["logw"] = np.concatenate([g["logw"], np.log(rng.uniform(0.01, 0.2, n)).astype(np.float32)])
+    return g
+
+
+@pytest.mark.parametrize("kind", ["registers", "hybrid", "nonuniform_pi", "fp64"])
+def test_hub_states_in_every_recursion_variant(kind):
+    # a state with hundreds of arcs gets a slice of its own whose 64 lanes share its
+    # arcs; the lanes' sums are added up where the slice ends
+    rng = np.random.default_rng(21)
+    if kind == "hybrid":
+        g = workloads.random_den_graph(rng, 3000, 14, 60, 0.5)
+    else:
+        g = workloads.random_den_graph(rng, 900, 8, 60, 0.5)
+    g = _with_hubs(g, rng, 500, 350)
+    if kind in ("nonuniform_pi", "fp64"):
+        pi = rng.uniform(0.05, 1.0, g["num_states"])
+        g["init_prob"] = (pi / pi.sum()).astype(np.float32)
+    if kind == "fp64":
+        fin = g["final_prob"].copy()
+        fin[rng.random(len(fin)) < 0.5] = 0.0
+        fin[5] = 1.0
+        g["final_prob"] = fin
+    B = 4
+    lengths = rng.integers(8, 40, B).astype(np.int32)
+    x = rng.normal(0, 2, (B, int(lengths.max()), 60)).astype(np.float32)
+    for b in range(B):
+        x[b, lengths[b]:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    for o in (0, 1):
+        info = binding.lfmmi_graph_ordering_info(h, 0, o)
+        assert info["hub_slices"] == 1
+        if kind == "registers":
+            assert info["register_slots"] >= info["max_wave_slots"]
+        if kind == "hybrid":
+            assert 0 < info["register_slots"] < info["max_wave_slots"]
+    assert binding.lfmmi_graph_info(h)["fp64"] == (1 if kind == "fp64" else 0)
+    lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
+    check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "hubs, " + kind)
+    h.close()

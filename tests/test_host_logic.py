@@ -51,8 +51,11 @@ def _unpack(graph_handle, g, graph):
                     want = 0.0 if st < 0 else (1.0 if o == 0 else float(graph["init_prob"][st]))
                     assert d["key"][o1 * 64 + lane] == 0
                     assert d["w"][o1 * 64 + lane] == np.float32(want)
+            hub = o < 2 and d["slice_hub"][s]
+            if hub:  # all 64 lanes hold arcs of lane 0's row; the other rows are padding
+                assert d["row_id"][s * 64] >= 0 and np.all(d["row_id"][s * 64 + 1:s * 64 + 64] < 0)
             for lane in range(64):
-                row = s * 64 + lane
+                row = s * 64 if hub else s * 64 + lane
                 for i in range(o0, o1):
                     k, w = int(d["key"][i * 64 + lane]), float(d["w"][i * 64 + lane])
                     if w == 0.0:      # padding: anywhere in the row (slots are ordered to
@@ -226,3 +229,38 @@ def test_fst_text_reader_round_trip_and_errors():
             fst_text.read_fst_text(bad)
     with pytest.raises(ValueError):
         fst_text.read_fst_text(["0 1 9 9"], num_pdfs=4)
+
+
+def _hub_graph(seed=5, S=500, in_hub=300, out_hub=200):
+    rng = np.random.default_rng(seed)
+    g = workloads.random_den_graph(rng, S, 8, 30, 0.5)
+    extra_src = rng.choice(S, size=in_hub, replace=False).astype(np.int32)       # into state 7
+    extra_dst = rng.choice(S, size=out_hub, replace=False).astype(np.int32)      # out of state 11
+    g["src"] = np.concatenate([g["src"], extra_src, np.full(out_hub, 11, np.int32)])
+    g["dst"] = np.concatenate([g["dst"], np.full(in_hub, 7, np.int32), extra_dst])
+    n = in_hub + out_hub
+    g["pdf"] = np.concatenate([g["pdf"], rng.integers(0, 30, n).astype(np.int32)])
+    g["logw"] = np.concatenate([g["logw"], np.log(rng.uniform(0.01, 0.2, n)).astype(np.float32)])
+    return g
+
+
+@pytest.mark.parametrize("nonuniform", [False, True])
+def test_hub_states_get_slices_of_their_own(nonuniform):
+    g = _hub_graph()
+    if nonuniform:  # closing slots: the hub's leak-dot weight sits in lane 0 only
+        pi = np.random.default_rng(1).uniform(0.1, 1.0, g["num_states"])
+        g["init_prob"] = (pi / pi.sum()).astype(np.float32)
+    h = binding.lfmmi_graph_pack(g)
+    got, want, od = _unpack(h, 0, g)
+    for o in range(3):
+        assert got[o] == want, "ordering %d lost or changed arcs" % o
+    # one hub slice per direction, a few slots wide instead of hundreds
+    for o, (state, deg) in enumerate(((7, 300), (11, 200))):
+        assert od[o]["hub_slices"] == 1
+        s = int(np.flatnonzero(od[o]["slice_hub"])[0])
+        assert od[o]["row_id"][s * 64] == state
+        width = od[o]["slice_off"][s + 1] - od[o]["slice_off"][s]
+        assert width <= (deg + 10 + 63) // 64 + 3 and width % 2 == 0
+        assert od[o]["max_wave_slots"] < 64
+    assert od[2]["hub_slices"] == 0
+    h.close()
