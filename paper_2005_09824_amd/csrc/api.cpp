@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <string>
@@ -280,7 +281,16 @@ lfmmi_status upload(lfmmi_graph* h)
     if (h->uploaded) return LFMMI_OK;
     hipError_t e = hipGetDevice(&h->device);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
-    if ((e = configure_kernels()) != hipSuccess) return fail_hip(e, "hipFuncSetAttribute");
+    {
+        // once per device and process: the LDS limits of every kernel variant
+        static std::mutex mu;
+        static std::vector<int> done;
+        std::lock_guard<std::mutex> lock(mu);
+        if (std::find(done.begin(), done.end(), h->device) == done.end()) {
+            if ((e = configure_kernels()) != hipSuccess) return fail_hip(e, "hipFuncSetAttribute");
+            done.push_back(h->device);
+        }
+    }
 
     // concatenate every graph's orderings
     size_t n_slots = 0, n_soff = 0, n_wf = 0, n_vec = 0, n_rowpdf = 0, n_mask = 0, n_pfirst = 0;
