@@ -180,58 +180,84 @@ struct Lcg {
     uint32_t below(uint32_t n) { return (uint32_t)(((uint64_t)next() * n) >> 31) % n; }
 };
 
-// Re-deals the lanes inside every half-slice so that, for each half-slice of
-// rows, the states its arcs gather are spread evenly over the banks.
+// Moves states between rows so that, for each half-slice of rows, the states its
+// arcs gather are spread evenly over the banks. Two states may trade places
+// when each fits the other's slice (its arcs within that slice's arc slots), so
+// both the bank a state is gathered from and the company its row keeps are
+// free; hill climbing on the sum of squared (half-slice, bank) loads.
 // row_state[a] / x_state[a]: the state that owns the row of arc a / the state
 // whose value arc a gathers. pos: state -> slice * 64 + lane (updated).
+// deg[s]: arcs of the row of state s; room[slice]: arc slots of the slice;
+// fixed[s] != 0: the state stays where it is (hub rows).
 void balance_banks(const std::vector<int32_t>& row_state, const std::vector<int32_t>& x_state,
-                   std::vector<int32_t>* pos)
+                   const std::vector<int32_t>& deg, const std::vector<int32_t>& room,
+                   const std::vector<uint8_t>& fixed, std::vector<int32_t>* pos)
 {
     const int64_t A = (int64_t)row_state.size();
     const int32_t S = (int32_t)pos->size();
     if (A < 256 || S < 2 * kHalf) return;
     int32_t halves = 0;
     for (int32_t s = 0; s < S; ++s) halves = std::max(halves, (*pos)[s] / kHalf + 1);
-    // arcs gathered from each state, as the half-slice of their row
-    std::vector<int32_t> first(S + 1, 0);
-    for (int64_t a = 0; a < A; ++a) ++first[x_state[a] + 1];
-    for (int32_t s = 0; s < S; ++s) first[s + 1] += first[s];
-    std::vector<int32_t> half_of(A), fill(first.begin(), first.end() - 1);
-    for (int64_t a = 0; a < A; ++a) half_of[fill[x_state[a]]++] = (*pos)[row_state[a]] / kHalf;
+    // per state: the states its row gathers, and the states whose rows gather it
+    // (arcs of fixed rows are left out: a hub's arcs are dealt over a whole slice)
+    std::vector<int32_t> out_first(S + 1, 0), in_first(S + 1, 0);
+    for (int64_t a = 0; a < A; ++a)
+        if (!fixed[row_state[a]]) {
+            ++out_first[row_state[a] + 1];
+            ++in_first[x_state[a] + 1];
+        }
+    for (int32_t s = 0; s < S; ++s) {
+        out_first[s + 1] += out_first[s];
+        in_first[s + 1] += in_first[s];
+    }
+    std::vector<int32_t> out_of(out_first[S]), in_of(in_first[S]);
+    {
+        std::vector<int32_t> fo(out_first.begin(), out_first.end() - 1),
+            fi(in_first.begin(), in_first.end() - 1);
+        for (int64_t a = 0; a < A; ++a)
+            if (!fixed[row_state[a]]) {
+                out_of[fo[row_state[a]]++] = x_state[a];
+                in_of[fi[x_state[a]]++] = row_state[a];
+            }
+    }
     std::vector<int32_t> load((size_t)halves * kBanks, 0);
     for (int32_t s = 0; s < S; ++s)
-        for (int32_t i = first[s]; i < first[s + 1]; ++i)
-            ++load[(size_t)half_of[i] * kBanks + (*pos)[s] % kBanks];
-    // members of each half-slice
-    std::vector<std::vector<int32_t>> members(halves);
-    for (int32_t s = 0; s < S; ++s) members[(*pos)[s] / kHalf].push_back(s);
+        for (int32_t i = out_first[s]; i < out_first[s + 1]; ++i)
+            ++load[(size_t)((*pos)[s] / kHalf) * kBanks + (*pos)[out_of[i]] % kBanks];
 
+    int64_t delta = 0;
+    auto add = [&](int32_t half, int32_t bank, int k) {
+        int32_t& x = load[(size_t)half * kBanks + bank];
+        delta += (int64_t)(x + k) * (x + k) - (int64_t)x * x;
+        x += k;
+    };
+    // every load entry that involves u or v, taken out (k = -1) or put in (+1)
+    auto touch = [&](int32_t u, int32_t v, int k) {
+        for (int32_t st : {u, v}) {
+            const int32_t half = (*pos)[st] / kHalf;
+            for (int32_t i = out_first[st]; i < out_first[st + 1]; ++i)
+                add(half, (*pos)[out_of[i]] % kBanks, k);
+            const int32_t bank = (*pos)[st] % kBanks;
+            for (int32_t i = in_first[st]; i < in_first[st + 1]; ++i)
+                if (in_of[i] != u && in_of[i] != v)  // their rows were handled above
+                    add((*pos)[in_of[i]] / kHalf, bank, k);
+        }
+    };
     Lcg rng(0x5eed0000u + (uint64_t)A);
-    const int64_t tries = std::min<int64_t>(60 * A, 6000000);
+    const int64_t tries = std::min<int64_t>(150LL * S, 3000000);
     for (int64_t it = 0; it < tries; ++it) {
-        const int32_t u = (int32_t)rng.below((uint32_t)S);
-        const std::vector<int32_t>& m = members[(*pos)[u] / kHalf];
-        if (m.size() < 2) continue;
-        const int32_t v = m[rng.below((uint32_t)m.size())];
-        const int32_t bu = (*pos)[u] % kBanks, bv = (*pos)[v] % kBanks;
-        if (u == v || bu == bv) continue;
-        // change of sum of squares if u and v trade banks
-        int64_t delta = 0;
-        auto shift = [&](int32_t st, int32_t from, int32_t to, int sign) {
-            for (int32_t i = first[st]; i < first[st + 1]; ++i) {
-                int32_t* row = &load[(size_t)half_of[i] * kBanks];
-                delta += sign * (2 * (row[to] - row[from]) + 2);
-                --row[from];
-                ++row[to];
-            }
-        };
-        shift(u, bu, bv, 1);
-        shift(v, bv, bu, 1);
-        if (delta <= 0) {
+        const int32_t u = (int32_t)rng.below((uint32_t)S), v = (int32_t)rng.below((uint32_t)S);
+        if (u == v || fixed[u] || fixed[v]) continue;
+        const int32_t su = (*pos)[u] / kLanes, sv = (*pos)[v] / kLanes;
+        if (su != sv && (deg[u] > room[sv] || deg[v] > room[su])) continue;
+        delta = 0;
+        touch(u, v, -1);
+        std::swap((*pos)[u], (*pos)[v]);
+        touch(u, v, +1);
+        if (delta > 0) {  // undo
+            touch(u, v, -1);
             std::swap((*pos)[u], (*pos)[v]);
-        } else {  // undo
-            shift(v, bu, bv, 1);
-            shift(u, bv, bu, 1);
+            touch(u, v, +1);
         }
     }
 }
@@ -308,6 +334,114 @@ void colour_half_slice(const std::vector<int32_t>& rows, const std::vector<int32
     }
 }
 
+// Slot order of one half-slice with the fewest conflict cycles a single gather can
+// have: max(W, largest bank load). With k = largest load - W, k slots are set
+// aside in which a bank may show up twice and W - k in which it shows up once.
+// Which arcs go into the k slots is a degree-constrained subgraph: a row keeps
+// at most W - k arcs for the other slots, and so does a bank, while the k slots
+// hold at most k arcs of a row and 2k of a bank; found as a feasible flow
+// (lower bounds by the usual excess / deficit construction, augmenting paths by
+// BFS: the graph has 66 nodes). Both parts are then edge-coloured exactly.
+// Returns false when no k <= W works (a bank with more than 2W arcs).
+bool colour_balanced(const std::vector<int32_t>& rows, const std::vector<int32_t>& banks,
+                     int32_t W, std::vector<int32_t>* slot_of)
+{
+    const int32_t n = (int32_t)rows.size();
+    std::vector<int32_t> deg_r(kHalf, 0), deg_b(kBanks, 0);
+    for (int32_t i = 0; i < n; ++i) {
+        ++deg_r[rows[i]];
+        ++deg_b[banks[i]];
+    }
+    int32_t most = 0;
+    for (int b = 0; b < kBanks; ++b) most = std::max(most, deg_b[b]);
+    for (int r = 0; r < kHalf; ++r)
+        if (deg_r[r] > W) return false;
+    if (most <= W) {  // an exact colouring has no conflict at all
+        colour_half_slice(rows, banks, W, slot_of);
+        for (int32_t i = 0; i < n; ++i)
+            if ((*slot_of)[i] < 0) return false;
+        return true;
+    }
+    // nodes: 0 source, 1 sink, 2 + r rows, 2 + kHalf + b banks, then super source / sink
+    constexpr int kSrc = 0, kSnk = 1, kRow0 = 2, kBank0 = 2 + kHalf, kSS = kBank0 + kBanks,
+                  kTT = kSS + 1, kNodes = kTT + 1;
+    struct Edge { int32_t to, cap, arc; };
+    for (int32_t k = most - W; k <= W; ++k) {
+        std::vector<Edge> edges;
+        std::vector<std::vector<int32_t>> adj(kNodes);
+        auto add_edge = [&](int32_t u, int32_t v, int32_t cap, int32_t arc) {
+            adj[u].push_back((int32_t)edges.size());
+            edges.push_back({v, cap, arc});
+            adj[v].push_back((int32_t)edges.size());
+            edges.push_back({u, 0, -1});
+        };
+        std::vector<int32_t> excess(kNodes, 0);
+        bool possible = true;
+        auto bounded = [&](int32_t u, int32_t v, int32_t lo, int32_t hi) {
+            if (lo > hi) { possible = false; return; }
+            excess[v] += lo;
+            excess[u] -= lo;
+            add_edge(u, v, hi - lo, -1);
+        };
+        for (int r = 0; r < kHalf; ++r)
+            bounded(kSrc, kRow0 + r, std::max(0, deg_r[r] - (W - k)), std::min(k, deg_r[r]));
+        for (int b = 0; b < kBanks; ++b)
+            bounded(kBank0 + b, kSnk, std::max(0, deg_b[b] - (W - k)), std::min(2 * k, deg_b[b]));
+        if (!possible) continue;
+        for (int32_t i = 0; i < n; ++i) add_edge(kRow0 + rows[i], kBank0 + banks[i], 1, i);
+        add_edge(kSnk, kSrc, 1 << 28, -1);
+        int32_t need = 0;
+        for (int v = 0; v < kNodes; ++v) {
+            if (excess[v] > 0) { add_edge(kSS, v, excess[v], -1); need += excess[v]; }
+            if (excess[v] < 0) add_edge(v, kTT, -excess[v], -1);
+        }
+        int32_t flow = 0;
+        while (true) {  // shortest augmenting paths
+            std::vector<int32_t> via(kNodes, -1), queue{kSS};
+            via[kSS] = -2;
+            for (size_t q = 0; q < queue.size() && via[kTT] == -1; ++q)
+                for (int32_t e : adj[queue[q]])
+                    if (edges[e].cap > 0 && via[edges[e].to] == -1) {
+                        via[edges[e].to] = e;
+                        queue.push_back(edges[e].to);
+                    }
+            if (via[kTT] == -1) break;
+            int32_t push = 1 << 28;
+            for (int32_t v = kTT; v != kSS; v = edges[via[v] ^ 1].to) push = std::min(push, edges[via[v]].cap);
+            for (int32_t v = kTT; v != kSS; v = edges[via[v] ^ 1].to) {
+                edges[via[v]].cap -= push;
+                edges[via[v] ^ 1].cap += push;
+            }
+            flow += push;
+        }
+        if (flow != need) continue;
+        // arcs that carry flow go into the k shared slots
+        std::vector<int32_t> part(n, 0);
+        for (const Edge& e : edges)
+            if (e.arc >= 0 && e.cap == 0) part[e.arc] = 1;
+        std::vector<int32_t> sub_rows[2], sub_banks[2], sub_arc[2], col;
+        for (int32_t i = 0; i < n; ++i) {
+            sub_rows[part[i]].push_back(rows[i]);
+            sub_banks[part[i]].push_back(banks[i]);
+            sub_arc[part[i]].push_back(i);
+        }
+        slot_of->assign(n, -1);
+        bool ok = true;
+        for (int which = 0; which < 2 && ok; ++which) {
+            const int32_t width = which == 0 ? W - k : k, first = which == 0 ? 0 : W - k;
+            if (sub_arc[which].empty()) continue;
+            if (width <= 0) { ok = false; break; }
+            colour_half_slice(sub_rows[which], sub_banks[which], width, &col);
+            for (size_t i = 0; i < sub_arc[which].size(); ++i) {
+                if (col[i] < 0) ok = false;
+                (*slot_of)[sub_arc[which][i]] = first + col[i];
+            }
+        }
+        if (ok) return true;
+    }
+    return false;
+}
+
 // Chooses the slot (0 .. width - 1 inside its slice) of every arc. pos_row[a]:
 // position of the arc's row; bx[a], by[a]: banks of its two gathers, -1 for a
 // gather that cannot conflict. width[slice]: arc slots of the slice.
@@ -356,8 +490,11 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
                 rws[i] = pos_row[arcs[i]] % kHalf;
                 bks[i] = bx[arcs[i]];
             }
-            colour_half_slice(rws, bks, W, &col);
-            bool ok = true;
+            bool ok = colour_balanced(rws, bks, W, &col);
+            if (!ok) {
+                colour_half_slice(rws, bks, W, &col);
+                ok = true;
+            }
             for (int32_t i = 0; i < n; ++i) ok = ok && col[i] >= 0;
             if (ok) {
                 for (int32_t i = 0; i < n; ++i) (*nth)[arcs[i]] = col[i];
@@ -579,8 +716,12 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     if (af.num_slices * kLanes > kMaxIndex) return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {
-        balance_banks(vdst, vsrc, &af.pos);  // alpha gathers from-states in FWD numbering
-        balance_banks(vsrc, vdst, &ab.pos);  // beta gathers to-states in BWD numbering
+        std::vector<int32_t> room_f(af.slice_width), room_b(ab.slice_width);
+        for (int32_t& r : room_f) r -= closing;
+        for (int32_t& r : room_b) r -= closing;
+        // alpha gathers from-states in FWD numbering, beta to-states in BWD numbering
+        balance_banks(vdst, vsrc, indeg, room_f, hub_f, &af.pos);
+        balance_banks(vsrc, vdst, outdeg, room_b, hub_b, &ab.pos);
     }
     start_ordering(af, S, &out->ord[0]);
     start_ordering(ab, S, &out->ord[1]);
