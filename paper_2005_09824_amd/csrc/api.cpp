@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cmath>
 #include <cstring>
@@ -12,6 +13,7 @@
 #include <new>
 #include <numeric>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "kernels.h"
@@ -203,13 +205,36 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             h->max_rows_f = h->max_rows_b = h->max_rows_occ = 0;
             h->rec_hubs = false;
             *max_slots = 0;
+            // the graphs of a batch are packed independently: on several threads
+            std::vector<std::string> errs(n);
+            std::vector<char> bads(n, 0);
+            {
+                const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
+                const int workers = (int)std::max(1u, std::min({hw, 16u, (unsigned)(n / 8 + 1)}));
+                std::atomic<int32_t> next(0);
+                const int rec_w = h->rec_waves, occ_w = h->occ_waves;
+                const bool wb = h->has_wb;
+                auto work = [&]() {
+                    for (int32_t g = next.fetch_add(1); g < n; g = next.fetch_add(1)) {
+                        bool bad = false;
+                        try {
+                            errs[g] = pack_graph(arcs_of(g), num_pdfs, rec_w, occ_w, wb, tune,
+                                                 &h->packed[g], &bad);
+                        } catch (const std::bad_alloc&) {
+                            errs[g] = "host allocation failed";
+                        }
+                        bads[g] = bad ? 1 : 0;
+                    }
+                };
+                std::vector<std::thread> pool;
+                for (int t = 1; t < workers; ++t) pool.emplace_back(work);
+                work();
+                for (std::thread& t : pool) t.join();
+            }
             for (int32_t g = 0; g < n; ++g) {
-                bool bad = false;
-                std::string err = pack_graph(arcs_of(g), num_pdfs, h->rec_waves, h->occ_waves,
-                                             h->has_wb, tune, &h->packed[g], &bad);
-                if (!err.empty())
-                    return fail(bad ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
-                                (n > 1 ? "graph " + std::to_string(g) + ": " : std::string()) + err);
+                if (!errs[g].empty())
+                    return fail(bads[g] ? LFMMI_ERR_BAD_GRAPH : LFMMI_ERR_INVALID_ARG,
+                                (n > 1 ? "graph " + std::to_string(g) + ": " : std::string()) + errs[g]);
                 h->max_rows_f = std::max(h->max_rows_f, h->packed[g].ord[0].num_slices * kLanes);
                 h->max_rows_b = std::max(h->max_rows_b, h->packed[g].ord[1].num_slices * kLanes);
                 h->max_rows_occ = std::max(h->max_rows_occ, h->packed[g].ord[2].num_slices * kLanes);
