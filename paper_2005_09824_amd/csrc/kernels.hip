@@ -535,12 +535,16 @@ struct RecRegs {
             if (i == 0 || i < ypasses) {
                 if constexpr (YREP) {
                     // four adjacent words from one register: two 2-word stores (the
-                    // compiler would spend a register and an instruction per word)
+                    // compiler would spend a register and an instruction per word).
+                    // ydst points at the first or the second pair of the quad by the
+                    // parity of the pdf, the other pair follows: the 32 lanes of a
+                    // half-wave (8 quads of 4 pdfs) then put two words into every bank
+                    // per store, not four into every other pair of banks
                     const uint32_t at = ybuf + ydst[i];
-                    asm volatile("ds_write2_b32 %0, %1, %1 offset1:1\n\t"
-                                 "ds_write2_b32 %0, %1, %1 offset0:2 offset1:3"
+                    asm volatile("ds_write2_b32 %0, %2, %2 offset1:1\n\t"
+                                 "ds_write2_b32 %1, %2, %2 offset1:1"
                                  :
-                                 : "v"(at), "v"(yreg[i])
+                                 : "v"(at), "v"(at ^ 8u), "v"(yreg[i])
                                  : "memory");
                 } else {
                     lds_st(ybuf + ydst[i], yreg[i]);
@@ -820,7 +824,7 @@ struct RecRegs {
                 // threads past the row repeat the work of an earlier thread
                 const int q = (tid + i * nthreads) % units;
                 ysrc[i] = (uint32_t)(YREP ? q >> 3 : q) * 4u;
-                ydst[i] = (uint32_t)q * (YREP ? 16u : 4u);
+                ydst[i] = (uint32_t)q * (YREP ? 16u : 4u) + (YREP ? (uint32_t)((q >> 3) & 1) * 8u : 0u);
             }
         }
 
