@@ -511,7 +511,7 @@ struct RecRegs {
     float yreg[kYPass];
     uint32_t ysrc[kYPass];  // byte offset of this thread's value inside an emission row
     uint32_t ydst[kYPass];  // byte offset inside a Y buffer it is stored to
-    int ypasses;            // passes that hold any of the row
+    int ypasses;            // passes in which this wave holds any of the row (wave-uniform)
 
     // per-step pointers, moved by one frame after every step
     const float* e2;  // emission row loaded during this step (used two steps on)
@@ -525,14 +525,14 @@ struct RecRegs {
         const char* base = reinterpret_cast<const char*>(e2);
 #pragma unroll
         for (int i = 0; i < kYPass; ++i)
-            if (i == 0 || i < ypasses) yreg[i] = *reinterpret_cast<const float*>(base + ysrc[i]);
+            if (i < ypasses) yreg[i] = *reinterpret_cast<const float*>(base + ysrc[i]);
     }
 
     __device__ __forceinline__ void store_y(const uint32_t ybuf)
     {
 #pragma unroll
         for (int i = 0; i < kYPass; ++i)
-            if (i == 0 || i < ypasses) {
+            if (i < ypasses) {
                 if constexpr (YREP) {
                     // four adjacent words from one register: two 2-word stores (the
                     // compiler would spend a register and an instruction per word).
@@ -818,7 +818,9 @@ struct RecRegs {
         // where in a Y buffer it goes
         {
             const int units = YREP ? P * 8 : P;  // 16-byte quads, or single values
-            ypasses = (units + nthreads - 1) / nthreads;
+            // (a wave whose threads all lie past the row in a pass skips it; single
+            // threads past the row repeat the work of an earlier thread)
+            ypasses = max(0, (units - wave * 64 + nthreads - 1) / nthreads);
 #pragma unroll
             for (int i = 0; i < kYPass; ++i) {
                 // threads past the row repeat the work of an earlier thread
