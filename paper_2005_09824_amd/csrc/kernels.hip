@@ -120,9 +120,10 @@ __device__ __forceinline__ uint2 rec_hi(const uint4 r) { return make_uint2(r.z, 
 //        numerator graphs, where the states that matter can hold a fraction of
 //        the frame's mass far below 1e-38).
 //        Arc records are streamed from global memory / L2 every frame here;
-//        rec_run_regs below keeps them in registers.
+//        RecRegs below keeps them in registers.
 // YREP   emission row replicated across banks.
 // HAS_WB the leak target differs per state, so every arc carries w * b[from].
+// HUBS   the graph has hub slices (64 lanes that share the arcs of lane 0's row).
 //
 // Normalisation is lazy: LDS and the trellis hold the raw v_t = M vhat'_{t-1};
 // the consumer of v_t applies vhat'_t = v_t / n_t + (eps * s_t / n_t) * b with
@@ -1502,7 +1503,7 @@ const RecVariant kRecVariants[] = {
     LFMMI_REC(double, 1, 8, 1, 1024), LFMMI_REC(double, 1, 16, 1, 1024),
     LFMMI_REC(double, 1, 32, 1, 512),
     LFMMI_REC(double, 1, 16, 0, 1024), LFMMI_REC(double, 1, 32, 0, 512),
-    // hybrid: 20 slots of a wave in registers, its other slices streamed
+    // hybrid: kHybridSlots slots of a wave in registers, its other slices streamed
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true>, 1},
     {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true>, 1},
     // ... with the LDS map for up to 12288 states
