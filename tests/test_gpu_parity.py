@@ -394,20 +394,22 @@ def _with_hubs(g, rng, in_hub, out_hub):
     return g
 
 
-@pytest.mark.parametrize("kind", ["registers", "hybrid", "nonuniform_pi", "fp64"])
+@pytest.mark.parametrize("kind", ["registers", "hybrid", "nonuniform_pi", "fp64", "fp64_registers"])
 def test_hub_states_in_every_recursion_variant(kind):
     # a state with hundreds of arcs gets a slice of its own whose 64 lanes share its
     # arcs; the lanes' sums are added up where the slice ends
     rng = np.random.default_rng(21)
     if kind == "hybrid":
         g = workloads.random_den_graph(rng, 3000, 14, 60, 0.5)
+    elif kind == "fp64_registers":
+        g = workloads.random_den_graph(rng, 400, 3, 60, 0.5)
     else:
         g = workloads.random_den_graph(rng, 900, 8, 60, 0.5)
-    g = _with_hubs(g, rng, 500, 350)
-    if kind in ("nonuniform_pi", "fp64"):
+    g = _with_hubs(g, rng, *((150, 120) if kind == "fp64_registers" else (500, 350)))
+    if kind in ("nonuniform_pi", "fp64", "fp64_registers"):
         pi = rng.uniform(0.05, 1.0, g["num_states"])
         g["init_prob"] = (pi / pi.sum()).astype(np.float32)
-    if kind == "fp64":
+    if kind in ("fp64", "fp64_registers"):
         fin = g["final_prob"].copy()
         fin[rng.random(len(fin)) < 0.5] = 0.0
         fin[5] = 1.0
@@ -421,11 +423,11 @@ def test_hub_states_in_every_recursion_variant(kind):
     for o in (0, 1):
         info = binding.lfmmi_graph_ordering_info(h, 0, o)
         assert info["hub_slices"] == 1
-        if kind == "registers":
+        if kind in ("registers", "fp64_registers"):
             assert info["register_slots"] >= info["max_wave_slots"]
         if kind == "hybrid":
             assert 0 < info["register_slots"] < info["max_wave_slots"]
-    assert binding.lfmmi_graph_info(h)["fp64"] == (1 if kind == "fp64" else 0)
+    assert binding.lfmmi_graph_info(h)["fp64"] == (1 if kind.startswith("fp64") else 0)
     lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
     check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "hubs, " + kind)
     h.close()
