@@ -592,7 +592,12 @@ struct RecRegs {
                 inv = __builtin_amdgcn_rcpf(N);
                 inv = fmaf(fmaf(-N, inv, 1.f), inv, inv);  // one Newton step
             } else {
-                inv = (Real)1 / N;
+                // hardware reciprocal and two Newton steps (N is a sum of probabilities
+                // far from the ends of the fp64 range): a third of the instructions of
+                // a division, on the critical path of the short numerator steps
+                inv = __builtin_amdgcn_rcp((double)N);
+                inv = fma(fma(-N, inv, (Real)1), inv, inv);
+                inv = fma(fma(-N, inv, (Real)1), inv, inv);
             }
         }
         const Real c = eps * Sd * inv;
