@@ -123,7 +123,8 @@ void lfmmi_graph_destroy(lfmmi_graph *graph);
  *            hip_stream then waits for: all of the call's work is ordered on
  *            hip_stream as if it ran there.
  * B == 0 or T == 0 with all lengths 0 are valid. Calls on one handle must be
- * ordered on one stream (they share the handle's workspace).
+ * ordered on one stream (they share the handle's workspace). The device the
+ * graph was uploaded to must be the current one (LFMMI_ERR_INVALID_ARG if not).
  */
 lfmmi_status lfmmi_forward_backward(const lfmmi_graph *graph, const float *logits,
                                     const int32_t *lengths, int32_t B, int32_t T,

@@ -554,6 +554,15 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
             return fail(LFMMI_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, T]");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
+    {
+        // the packed graph and the workspace live on the device of the upload
+        int current = -1;
+        if ((e = hipGetDevice(&current)) != hipSuccess) return fail_hip(e, "hipGetDevice");
+        if (current != h->device)
+            return fail(LFMMI_ERR_INVALID_ARG, "the graph was uploaded to device " +
+                                                   std::to_string(h->device) + ", the current device is " +
+                                                   std::to_string(current));
+    }
 
     // ---- per-sequence descriptors and the launch order (longest first)
     std::vector<SeqDesc> seqs(B);

@@ -146,6 +146,53 @@ def test_pdf_with_many_occupancy_rows_fp32_and_fp64():
         h.close()
 
 
+@pytest.mark.parametrize("S,k,P,dist,nonuniform_pi,zero_finals,B,Tlo,Thi,expect", [
+    (3000, 14, 200, "uniform", 0, 0, 3, 10, 30, "hybrid"),     # 32 KB state vectors, replicated emission row
+    (3000, 14, 1200, "zipf", 0, 0, 3, 10, 30, "hybrid"),       # plain emission row, pdfs with many rows
+    (9000, 6, 3500, "uniform", 0, 0, 2, 8, 20, "streamed"),    # more pdfs than the staging of the register paths takes
+    (3000, 14, 100, "uniform", 1, 0, 3, 10, 30, "streamed"),   # per-arc leak factors, too many arcs for registers
+    (1500, 10, 60, "uniform", 1, 1, 3, 10, 30, "fp64"),        # fp64 with per-arc leak factors
+    (2500, 12, 90, "zipf", 0, 1, 3, 10, 30, "fp64"),           # fp64, larger
+    (5000, 3, 84, "uniform", 0, 0, 3, 10, 30, "registers"),    # sparse rows
+    (700, 30, 50, "uniform", 0, 0, 3, 10, 30, "hybrid"),       # dense rows: one wide slice per wave
+    (13000, 3, 300, "uniform", 0, 0, 2, 6, 12, "streamed"),    # more states than the fixed LDS maps hold
+    (64, 5, 7, "uniform", 0, 0, 5, 1, 9, "registers"),         # one slice, lengths from 1
+])
+def test_odd_shapes_through_every_recursion_variant(S, k, P, dist, nonuniform_pi, zero_finals,
+                                                    B, Tlo, Thi, expect):
+    rng = np.random.default_rng(1000 + S + P)
+    g = workloads.random_den_graph(rng, S, k, P, 0.5, dist)
+    if nonuniform_pi:
+        pi = rng.uniform(0.05, 1.0, S)
+        g["init_prob"] = (pi / pi.sum()).astype(np.float32)
+    if zero_finals:
+        fin = g["final_prob"].copy()
+        fin[rng.random(S) < 0.6] = 0.0
+        fin[0] = 1.0
+        g["final_prob"] = fin
+    lengths = rng.integers(Tlo, Thi + 1, B).astype(np.int32)
+    T = int(lengths.max())
+    x = rng.normal(0, 2, (B, T, P)).astype(np.float32)
+    for b in range(B):
+        x[b, lengths[b]:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    fp64 = binding.lfmmi_graph_info(h)["fp64"]
+    if expect == "fp64":
+        assert fp64 == 1
+    else:
+        assert fp64 == 0
+        if expect == "registers":
+            assert info["register_slots"] >= info["max_wave_slots"]
+        elif expect == "hybrid":
+            assert 0 < info["register_slots"] < info["max_wave_slots"]
+        else:
+            assert info["register_slots"] == 0
+    lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
+    check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "S %d P %d %s" % (S, P, expect))
+    h.close()
+
+
 def test_concurrent_buckets_do_not_change_any_bit(monkeypatch):
     # sequences are cut by length into buckets that run on streams of their own;
     # every sequence is computed the same way whichever bucket it lands in
