@@ -392,7 +392,12 @@ lfmmi_status upload(lfmmi_graph* h)
                 const size_t to = ((slot >> 1) * kLanes + lane) * 2 + (slot & 1);
                 uint32_t wbits;
                 std::memcpy(&wbits, &od.w[i], 4);
-                recs[to] = make_uint2(od.key[i], wbits);
+                uint32_t key = od.key[i];
+                // replicated emission rows: the upper half becomes the byte offset of
+                // this lane's copy of the value, 128 * pdf + 4 * (lane % 32)
+                if (o < 2 && h->rec_yrep)
+                    key = (key & 0xffffu) | (((key >> 16) * 32u + (uint32_t)(lane & 31) * 4u) << 16);
+                recs[to] = make_uint2(key, wbits);
                 if (!od.wb.empty()) wbs[to] = od.wb[i];
             }
             if (!od.wave_mask.empty())

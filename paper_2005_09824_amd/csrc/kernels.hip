@@ -85,13 +85,11 @@ __global__ void __launch_bounds__(256) k_emit(FbParams p)
 // and store vhat = leak(v) / n, n = sum(v).
 // ---------------------------------------------------------------------------
 
-// Y (emission row) index of a record: plain, or replicated 32 times so that
-// lane l always reads bank l % 32 (conflict-free; small pdf counts only).
-template <bool YREP>
-__device__ __forceinline__ uint32_t y_offset(uint32_t key, int lane)
-{
-    return YREP ? (key >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (key >> 16);
-}
+// Byte offset of a record's emission value inside a Y buffer: the upper half of
+// its key. Plain rows: 4 * pdf. Rows replicated 32 times, so that lane l always
+// reads bank l % 32 (conflict-free; small pdf counts only): 128 * pdf + 4 * (l % 32),
+// which the upload writes into the device copy of lane l's records.
+__device__ __forceinline__ uint32_t y_offset(uint32_t key) { return key >> 16; }
 
 __device__ __forceinline__ float lds_f32(const float* base, uint32_t byte_off)
 {
@@ -248,7 +246,7 @@ __device__ __forceinline__ void rec_run(const FbParams& p, const SeqDesc& sd, co
                 const float2* wp = wbp + (size_t)(o0 >> 1) * 64;
                 Real acc1 = 0, acc2 = 0;
                 auto slot = [&](const uint2 r, const float wbv) {
-                    const float e = lds_f32(Yc, y_offset<YREP>(r.x, lane));
+                    const float e = lds_f32(Yc, y_offset(r.x));
                     const Real x = lds_at(Xc, r.x & 0xffffu);
                     const float t = __uint_as_float(r.y) * e;
                     acc1 += (Real)t * x;
@@ -513,6 +511,9 @@ struct RecRegs {
     uint32_t ysrc[kYPass];  // byte offset of this thread's value inside an emission row
     uint32_t ydst[kYPass];  // byte offset inside a Y buffer it is stored to
     int ypasses;            // passes in which this wave holds any of the row (wave-uniform)
+    // hybrid: lane l holds the end (one past the last slot) of the wave's l-th streamed
+    // slice; one past the wave's last slot
+    int so_tab, stream_end;
 
     // per-step pointers, moved by one frame after every step
     const float* e2;  // emission row loaded during this step (used two steps on)
@@ -562,7 +563,7 @@ struct RecRegs {
                                          const int sl_stream, const int sl_end,
                                          const int first_streamed, const int32_t* so,
                                          const uint64_t hub_bits, const int32_t* hub,
-                                         const uint4* recs)
+                                         const uint4* recs_uniform)
     {
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
@@ -690,47 +691,104 @@ struct RecRegs {
             }
         }
         if constexpr (HYBRID) {
-            // the wave's other slices: records from L2, four (then two) slots at a time
-            // (the first of them may have begun in the registers: acc1, acc2)
-            const int lane_y = (lane & 31) * 4;
+            // The wave's other slices, their records from L2 (the first of them may
+            // have begun in the registers: acc1, acc2). Pairs of slots in a flat
+            // sequence, four pairs in registers: two are being used while the two after
+            // them load, and the eight gathers of two pairs go out before the first
+            // is waited for. Loads past the wave's last pair repeat it (in bounds,
+            // never used). Everything that steers the loop is wave-uniform.
             int i = first_streamed;  // even
-            const uint4* rp = recs + (size_t)(i >> 1) * 64;
             Real a1 = acc1, a2 = acc2;
-            for (int sl = sl_stream; sl < sl_end; ++sl) {
-                const int o1 = so[sl + 1];
-                auto slot = [&](const uint2 r) {
-                    const uint32_t ykey = r.x >> 16;
-                    const float e = lds_ld(yc + kRegY0 + (YREP ? ykey * 32u + (uint32_t)lane_y : ykey));
-                    const Real x = lds_ldr<Real>(xc + (r.x & 0xffffu));
-                    const float t = __uint_as_float(r.y) * e;
-                    a1 = fmaf(t, x, a1);
-                    a2 += t;
+            if (i < stream_end) {
+                // pair q of this lane: a wave-uniform base in scalar registers plus a
+                // 32-bit byte offset (one vector add per load, no 64-bit arithmetic)
+                typedef const __attribute__((address_space(1))) char* global_bytes_t;
+                typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+                typedef const __attribute__((address_space(1))) u32x4_t* global_u32x4_t;
+                const uint64_t rb = reinterpret_cast<uint64_t>(recs_uniform) + (uint64_t)(i >> 1) * 1024u;
+                const global_bytes_t rbase = (global_bytes_t)(
+                    ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(rb >> 32)) << 32) |
+                    (uint32_t)__builtin_amdgcn_readfirstlane((int)rb));
+                const uint32_t lane16 = (uint32_t)lane * 16u;
+                auto pair_at = [&](const int q) {
+                    const u32x4_t v = *(global_u32x4_t)(rbase + ((uint32_t)q * 1024u + lane16));
+                    return make_uint4(v.x, v.y, v.z, v.w);
                 };
-                for (; i + 4 <= o1; i += 4) {
-                    const uint4 r0 = rp[0], r1 = rp[64];
-                    rp += 128;
-                    slot(rec_lo(r0)); slot(rec_hi(r0)); slot(rec_lo(r1)); slot(rec_hi(r1));
+                const int last = ((stream_end - i) >> 1) - 1;  // index of the wave's last pair
+                int sl = sl_stream;
+                auto slice_end = [&](const int at) {  // one past the last slot of slice `at`
+                    if (at >= sl_end) return stream_end;
+                    return at - sl_stream < 64 ? __builtin_amdgcn_readlane(so_tab, at - sl_stream)
+                                               : so[at + 1];
+                };
+                int o1 = slice_end(sl);
+                auto close = [&]() {
+                    const bool hub_slice =
+                        HUBS && (sl - sl_stream < 64 ? ((hub_bits >> (sl - sl_stream)) & 1) != 0
+                                                     : hub[sl] != 0);
+                    if (hub_slice) {
+                        a1 = wave_sum_uniform(a1);
+                        a2 = wave_sum_uniform(a2);
+                    }
+                    Real v = inv * a1 + cb * a2;
+                    if (hub_slice && lane != 0) v = 0;
+                    const uint32_t at = (uint32_t)(sl * 64 + lane) * kRB;
+                    lds_st(xn + at, v);
+                    *reinterpret_cast<Real*>(tr + at) = v;
+                    n += v;
+                    a1 = 0;
+                    a2 = 0;
+                    ++sl;
+                    o1 = slice_end(sl);
+                };
+                // 64 KB + the upper half of the key in one instruction (the upper half
+                // below a 1); what else leads to the Y buffer of this parity is a
+                // constant that folds into the offset field of the read
+                static_assert(kRegY0 >= 0x10000u && yc + kRegY0 - 0x10000u < 0x10000u, "offset field");
+                auto y_of = [&](const uint32_t key) {
+                    return (yc + kRegY0 - 0x10000u) + __builtin_amdgcn_alignbit(1u, key, 16u);
+                };
+                auto two_pairs = [&](const uint4 qa, const uint4 qb, const bool b_valid) {
+                    float e0 = lds_ld(y_of(qa.x));
+                    Real x0 = lds_ldr<Real>(xc + (qa.x & 0xffffu));
+                    float e1 = lds_ld(y_of(qa.z));
+                    Real x1 = lds_ldr<Real>(xc + (qa.z & 0xffffu));
+                    float e2 = lds_ld(y_of(qb.x));
+                    Real x2 = lds_ldr<Real>(xc + (qb.x & 0xffffu));
+                    float e3 = lds_ld(y_of(qb.z));
+                    Real x3 = lds_ldr<Real>(xc + (qb.z & 0xffffu));
+                    // one wait for the eight: the first use names the value loaded last
+                    asm volatile("" : "+v"(x0), "+v"(e0), "+v"(x1), "+v"(e1), "+v"(x2), "+v"(e2)
+                                 : "v"(x3), "v"(e3));
+                    const float t0 = __uint_as_float(qa.y) * e0, t1 = __uint_as_float(qa.w) * e1;
+                    a1 = fmaf(t0, x0, a1);
+                    a2 += t0;
+                    a1 = fmaf(t1, x1, a1);
+                    a2 += t1;
+                    i += 2;
+                    if (i == o1) close();
+                    if (b_valid) {
+                        const float t2 = __uint_as_float(qb.y) * e2, t3 = __uint_as_float(qb.w) * e3;
+                        a1 = fmaf(t2, x2, a1);
+                        a2 += t2;
+                        a1 = fmaf(t3, x3, a1);
+                        a2 += t3;
+                        i += 2;
+                        if (i == o1) close();
+                    }
+                };
+                uint4 q0 = pair_at(0);
+                uint4 q1 = pair_at(min(1, last));
+                uint4 q2 = pair_at(min(2, last));
+                uint4 q3 = pair_at(min(3, last));
+                for (int pr = 0; pr <= last; pr += 4) {
+                    two_pairs(q0, q1, pr + 1 <= last);
+                    q0 = pair_at(min(pr + 4, last));
+                    q1 = pair_at(min(pr + 5, last));
+                    if (pr + 2 <= last) two_pairs(q2, q3, pr + 3 <= last);
+                    q2 = pair_at(min(pr + 6, last));
+                    q3 = pair_at(min(pr + 7, last));
                 }
-                for (; i < o1; i += 2) {  // widths are even
-                    const uint4 r0 = rp[0];
-                    rp += 64;
-                    slot(rec_lo(r0)); slot(rec_hi(r0));
-                }
-                const bool hub_slice =
-                    HUBS && (sl - sl_stream < 64 ? ((hub_bits >> (sl - sl_stream)) & 1) != 0
-                                                 : hub[sl] != 0);
-                if (hub_slice) {
-                    a1 = wave_sum_uniform(a1);
-                    a2 = wave_sum_uniform(a2);
-                }
-                Real v = inv * a1 + cb * a2;
-                if (hub_slice && lane != 0) v = 0;
-                const uint32_t at = (uint32_t)(sl * 64 + lane) * kRB;
-                lds_st(xn + at, v);
-                *reinterpret_cast<Real*>(tr + at) = v;
-                n += v;
-                a1 = 0;
-                a2 = 0;
             }
         }
         __builtin_amdgcn_s_setprio(3);  // the serial end of this step and start of the next
@@ -802,6 +860,8 @@ struct RecRegs {
             if (HUBS)  // bits for the first 64 streamed slices, a load beyond
                 for (int sl = sl_stream; sl < s1 && sl - sl_stream < 64; ++sl)
                     if (hub[sl]) hub_bits |= (uint64_t)1 << (sl - sl_stream);
+            so_tab = so[max(min(sl_stream + lane, s1 - 1), 0) + 1];
+            stream_end = so[s1];
         }
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
@@ -810,10 +870,7 @@ struct RecRegs {
             const size_t at = (size_t)((first + i) >> 1) * 128 + ((first + i) & 1);
             const uint2 r = on ? rec1[at] : make_uint2(0u, 0u);
             xa[i] = (r.x & 0xffffu) * (kRB / 4u);
-            ya[i] = kRegY0 +
-                    ((on && !closing)
-                         ? (YREP ? (r.x >> 16) * 32u + (uint32_t)(lane & 31) * 4u : (r.x >> 16))
-                         : kRegYZero);
+            ya[i] = kRegY0 + ((on && !closing) ? y_offset(r.x) : kRegYZero);
             wr[i] = __uint_as_float(r.y);
             if (HAS_WB) wbr[i] = (on && !closing) ? wb1[at] : 0.f;
             // opaque from here on: the three values stay in three registers for the
@@ -891,12 +948,12 @@ struct RecRegs {
         int k = 1;
         for (; k + 1 <= T; k += 2) {
             step<1>(k, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
-                    sl_stream, s1, first + nsl, so, hub_bits, hub, recs);
+                    sl_stream, s1, first + nsl, so, hub_bits, hub, rec_pairs(p, od, 0));
             step<0>(k + 1, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
-                    sl_stream, s1, first + nsl, so, hub_bits, hub, recs);
+                    sl_stream, s1, first + nsl, so, hub_bits, hub, rec_pairs(p, od, 0));
         }
         if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
-                    sl_stream, s1, first + nsl, so, hub_bits, hub, recs);
+                    sl_stream, s1, first + nsl, so, hub_bits, hub, rec_pairs(p, od, 0));
 
         // ---- last scalars and the closing dot product
         {
@@ -1476,7 +1533,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
 
 // ---- kernel variants ---------------------------------------------------------
 using RecKernel = void (*)(FbParams);
-constexpr int kHybridSlots = 26;
+constexpr int kHybridSlots = 22;
 
 struct RecVariant {
     int wide, nslot, yrep, has_wb, max_threads;
