@@ -503,8 +503,17 @@ struct RecRegs {
                   "every wave reaches it");
     static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
 
-    uint32_t xa[NSLOT];  // byte address of the state value inside X0
-    uint32_t ya[NSLOT];  // LDS byte address of the emission value in Y0 (absolute)
+    // Packed slots (the hybrid): both addresses of a slot in one register, taken apart
+    // again in every step by two instructions; two registers per slot instead of
+    // three keep half as many slots again out of the streamed part, where a slot
+    // costs its record's way from L2 on top of its gathers.
+    static constexpr bool kPacked = HYBRID;
+    static_assert(!kPacked || (kRegY0 & 0xffff7fffu) == 0x10000u, "see y_at()");
+    uint32_t xa[kPacked ? 1 : NSLOT];  // byte address of the state value inside X0
+    // LDS byte address of the emission value in Y0 (absolute); packed: the state
+    // value's address in the lower half, the emission value's address less 64 KB
+    // in the upper half
+    uint32_t ya[NSLOT];
     float wr[NSLOT];     // arc weight; closing slots: the row's leak-dot weight
     float wbr[HAS_WB ? NSLOT : 1];
     float yreg[kYPass];
@@ -521,6 +530,18 @@ struct RecRegs {
     Real* sN;         // where the scalars of the previous step go
     Real* sS;
     ptrdiff_t estep, tstep, sstep;
+
+    __device__ __forceinline__ uint32_t x_at(const int i) const
+    {
+        if constexpr (kPacked) return ya[i] & 0xffffu;
+        else return xa[i];
+    }
+    __device__ __forceinline__ uint32_t y_at(const int i) const
+    {
+        // the upper half of the register below a 1: 64 KB + the stored half
+        if constexpr (kPacked) return __builtin_amdgcn_alignbit(1u, ya[i], 16u);
+        else return ya[i];
+    }
 
     __device__ __forceinline__ void load_y()
     {
@@ -574,13 +595,19 @@ struct RecRegs {
         // First the LDS reads this wave waits for: the partial sums of step k - 1
         // (lanes 0-15 fetch the n partials, 16-31 the s partials) and the first
         // gathers. The scalar chain below then runs while the gathers are in flight.
+        if constexpr (kPacked) {
+            // opaque once a step: the addresses are taken out of the packed registers
+            // where they are used, not once and for all before the time loop
+#pragma unroll
+            for (int i = 0; i < NSLOT; ++i) asm volatile("" : "+v"(ya[i]));
+        }
         Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
         Real xv[kPrefetch ? kPrefetch : 1];
         float ev[kPrefetch ? kPrefetch : 1];
 #pragma unroll
         for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
-            xv[i] = lds_ldr<Real>(xc + xa[i]);
-            ev[i] = lds_ld(yc + ya[i]);
+            xv[i] = lds_ldr<Real>(xc + x_at(i));
+            ev[i] = lds_ld(yc + y_at(i));
         }
         asm volatile("" ::: "memory");  // nothing else moves ahead of these reads
         // Without per-row leak-dot weights s is a_const * n.
@@ -641,18 +668,18 @@ struct RecRegs {
             Real x0, x1;
             float e0, e1;
             if constexpr (kPrefetch == 0) {
-                x0 = lds_ldr<Real>(xc + xa[i]); e0 = lds_ld(yc + ya[i]);
-                x1 = lds_ldr<Real>(xc + xa[i + 1]); e1 = lds_ld(yc + ya[i + 1]);
+                x0 = lds_ldr<Real>(xc + x_at(i)); e0 = lds_ld(yc + y_at(i));
+                x1 = lds_ldr<Real>(xc + x_at(i + 1)); e1 = lds_ld(yc + y_at(i + 1));
             } else {
                 x0 = xv[i % (kPrefetch ? kPrefetch : 1)]; e0 = ev[i % (kPrefetch ? kPrefetch : 1)];
                 x1 = xv[(i + 1) % (kPrefetch ? kPrefetch : 1)]; e1 = ev[(i + 1) % (kPrefetch ? kPrefetch : 1)];
             }
             if (kPrefetch > 0 && i + kPrefetch < NSLOT) {
                 constexpr int kp = kPrefetch ? kPrefetch : 1;
-                xv[i % kp] = lds_ldr<Real>(xc + xa[(i + kp) % NSLOT]);
-                ev[i % kp] = lds_ld(yc + ya[(i + kp) % NSLOT]);
-                xv[(i + 1) % kp] = lds_ldr<Real>(xc + xa[(i + 1 + kp) % NSLOT]);
-                ev[(i + 1) % kp] = lds_ld(yc + ya[(i + 1 + kp) % NSLOT]);
+                xv[i % kp] = lds_ldr<Real>(xc + x_at((i + kp) % NSLOT));
+                ev[i % kp] = lds_ld(yc + y_at((i + kp) % NSLOT));
+                xv[(i + 1) % kp] = lds_ldr<Real>(xc + x_at((i + 1 + kp) % NSLOT));
+                ev[(i + 1) % kp] = lds_ld(yc + y_at((i + 1 + kp) % NSLOT));
             }
             // one wait for the pair: this names the value loaded last, so the first
             // use of any of the four comes after all of them have arrived
@@ -869,13 +896,20 @@ struct RecRegs {
             const bool closing = HAS_WB && ((mask >> i) & 1);  // holds a[row], no arc
             const size_t at = (size_t)((first + i) >> 1) * 128 + ((first + i) & 1);
             const uint2 r = on ? rec1[at] : make_uint2(0u, 0u);
-            xa[i] = (r.x & 0xffffu) * (kRB / 4u);
-            ya[i] = kRegY0 + ((on && !closing) ? y_offset(r.x) : kRegYZero);
+            const uint32_t x_addr = (r.x & 0xffffu) * (kRB / 4u);
+            const uint32_t y_addr = kRegY0 + ((on && !closing) ? y_offset(r.x) : kRegYZero);
             wr[i] = __uint_as_float(r.y);
             if (HAS_WB) wbr[i] = (on && !closing) ? wb1[at] : 0.f;
-            // opaque from here on: the three values stay in three registers for the
-            // whole time loop instead of being re-derived from the record each frame
-            asm volatile("" : "+v"(xa[i]), "+v"(ya[i]), "+v"(wr[i]));
+            // opaque from here on: the values stay in their registers for the whole
+            // time loop instead of being re-derived from the record each frame
+            if constexpr (kPacked) {
+                ya[i] = x_addr | ((y_addr - 0x10000u) << 16);
+                asm volatile("" : "+v"(ya[i]), "+v"(wr[i]));
+            } else {
+                xa[i] = x_addr;
+                ya[i] = y_addr;
+                asm volatile("" : "+v"(xa[i]), "+v"(ya[i]), "+v"(wr[i]));
+            }
         }
         // emission staging: which value of a row this thread fetches in pass i, and
         // where in a Y buffer it goes
@@ -1533,7 +1567,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
 
 // ---- kernel variants ---------------------------------------------------------
 using RecKernel = void (*)(FbParams);
-constexpr int kHybridSlots = 22;
+constexpr int kHybridSlots = 36;
 
 struct RecVariant {
     int wide, nslot, yrep, has_wb, max_threads;
