@@ -395,6 +395,60 @@ def test_profiling_levels_report_launch_durations_and_leave_results_alone():
     h.close()
 
 
+def test_raw_call_without_status_on_a_side_stream_and_argument_errors():
+    # the C entry point itself: status may be NULL, the stream is the caller's, and
+    # bad arguments come back as status codes before anything is enqueued
+    import ctypes
+    torch = _torch()
+    wl = workloads.make_workload(2, scale={"S": 300, "B": 4, "Tlo": 20, "Thi": 50}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    ref = run_gpu(h, wl["logits"], wl["lengths"], wl["leak"])
+    lib = binding.load_library()
+    x = torch.from_numpy(wl["logits"]).cuda()
+    B, T, P = x.shape
+    lens = np.ascontiguousarray(wl["lengths"], dtype=np.int32)
+    objf = torch.full((B,), 7.0, dtype=torch.float32, device="cuda")
+    grad = torch.full((B, T, P), 7.0, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    vp = ctypes.c_void_p
+
+    def call(handle=h.handle, logits=x.data_ptr(), lengths=lens, b=B, t=T, p=P, leak=wl["leak"],
+             scale=1.0, objf_ptr=objf.data_ptr(), grad_ptr=grad.data_ptr()):
+        return lib.lfmmi_forward_backward(handle, vp(logits), lengths.ctypes.data_as(vp), b, t, p,
+                                          float(leak), float(scale), 0, vp(objf_ptr), vp(grad_ptr),
+                                          vp(None), vp(side.cuda_stream))
+
+    side.wait_stream(torch.cuda.current_stream())
+    assert call() == 0
+    side.synchronize()
+    assert np.array_equal(objf.cpu().numpy(), ref[0]) and np.array_equal(grad.cpu().numpy(), ref[1])
+
+    invalid = 1
+    assert call(p=P + 1) == invalid and "num_pdfs" in binding.lfmmi_last_error()
+    assert call(b=-1) == invalid
+    assert call(leak=-1.0) == invalid and call(leak=float("nan")) == invalid
+    assert call(scale=float("nan")) == invalid
+    assert call(lengths=np.array([T + 1] * B, np.int32)) == invalid
+    assert call(lengths=np.array([-1] * B, np.int32)) == invalid
+    assert call(logits=0) == invalid and call(objf_ptr=0) == invalid and call(grad_ptr=0) == invalid
+    assert call(handle=None) == invalid
+    assert call(b=0) == 0  # an empty batch is valid and enqueues nothing
+    packed_only = binding.lfmmi_graph_pack(wl["den"])
+    assert call(handle=packed_only.handle) == invalid and "uploaded" in binding.lfmmi_last_error()
+    packed_only.close()
+    # a batch handle needs one graph per sequence
+    nums = workloads.make_workload(1, pad_value=np.nan)["num"]
+    nb = binding.lfmmi_graph_create_batch(nums)
+    with pytest.raises(binding.LfmmiError):
+        binding.lfmmi_forward_backward(nb, torch.zeros((len(nums) + 1, 4, 10), device="cuda"),
+                                       np.full(len(nums) + 1, 4, np.int32), 1e-5)
+    nb.close()
+    # the outputs of the good call were not touched by the refused ones
+    torch.cuda.synchronize()
+    assert np.array_equal(grad.cpu().numpy(), ref[1])
+    h.close()
+
+
 def test_loss_call_equals_the_two_passes_bit_for_bit_and_the_oracle():
     # Eq. 2 / Eq. 3 in one call, numerators and denominator overlapping
     torch = _torch()
