@@ -443,10 +443,14 @@ bool colour_balanced(const std::vector<int32_t>& rows, const std::vector<int32_t
 }
 
 // Chooses the slot (0 .. width - 1 inside its slice) of every arc. pos_row[a]:
-// position of the arc's row; bx[a], by[a]: banks of its two gathers, -1 for a
-// gather that cannot conflict. width[slice]: arc slots of the slice.
-void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>& bx,
-                 const std::vector<int16_t>& by, int32_t num_slices,
+// position of the arc's row; ax[a], ay[a]: the words its two gathers read (bank =
+// word % 32), -1 for a gather that cannot conflict. width[slice]: arc slots of
+// the slice. Lanes of a half-wave that read the same word do not conflict (the
+// word is broadcast), so what is balanced over the banks of a slot is the number
+// of distinct words, not of arcs: with skewed pdf-ids, or a state many arcs
+// leave, most reads of a bank are of one word.
+void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int32_t>& ax,
+                 const std::vector<int32_t>& ay, int32_t num_slices,
                  const std::vector<int32_t>& width, std::vector<int32_t>* nth)
 {
     const int64_t A = (int64_t)pos_row.size();
@@ -457,38 +461,21 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
     Lcg rng(0xb0a7u + (uint64_t)A);
     std::vector<int32_t> slot_of;      // per arc of the half-slice
     std::vector<int32_t> table;        // [row][slot] -> local arc index or -1
-    std::vector<int32_t> lx, ly;       // [slot][bank]
+    std::vector<int32_t> lx, ly;       // [slot][bank]: distinct words read there
+    std::vector<int32_t> ux, uy;       // the half-slice's distinct words, sorted
+    std::vector<int32_t> idx, idy;     // per arc: index of its word in ux / uy, or -1
+    std::vector<uint16_t> cx, cy;      // [slot][word index]: arcs that read it
     for (int32_t h = 0; h < halves; ++h) {
         const std::vector<int32_t>& arcs = arcs_of[h];
         const int32_t W = width[h / 2];
         const int32_t n = (int32_t)arcs.size();
         if (n == 0 || W == 0) continue;
-        table.assign((size_t)kHalf * W, -1);
-        lx.assign((size_t)W * kBanks, 0);
-        ly.assign((size_t)W * kBanks, 0);
-        slot_of.assign(n, -1);
-        std::vector<std::vector<int32_t>> row_arcs(kHalf);
-        for (int32_t i = 0; i < n; ++i) row_arcs[pos_row[arcs[i]] % kHalf].push_back(i);
-        auto cost_at = [&](int32_t j, int32_t i) {
-            const int32_t a = arcs[i];
-            int32_t c = 0;
-            if (bx[a] >= 0) c += lx[(size_t)j * kBanks + bx[a]];
-            if (by[a] >= 0) c += ly[(size_t)j * kBanks + by[a]];
-            return c;
-        };
-        auto place = [&](int32_t r, int32_t j, int32_t i, int sign) {
-            const int32_t a = arcs[i];
-            if (bx[a] >= 0) lx[(size_t)j * kBanks + bx[a]] += sign;
-            if (by[a] >= 0) ly[(size_t)j * kBanks + by[a]] += sign;
-            table[(size_t)r * W + j] = sign > 0 ? i : -1;
-            slot_of[i] = sign > 0 ? j : -1;
-        };
-        if (by[arcs[0]] < 0 && bx[arcs[0]] >= 0) {
+        if (ay[arcs[0]] < 0 && ax[arcs[0]] >= 0) {
             // one gather only: an edge colouring is (nearly) conflict-free by construction
             std::vector<int32_t> rws(n), bks(n), col;
             for (int32_t i = 0; i < n; ++i) {
                 rws[i] = pos_row[arcs[i]] % kHalf;
-                bks[i] = bx[arcs[i]];
+                bks[i] = ax[arcs[i]] % kBanks;
             }
             bool ok = colour_balanced(rws, bks, W, &col);
             if (!ok) {
@@ -501,6 +488,54 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
                 continue;
             }
         }
+        table.assign((size_t)kHalf * W, -1);
+        lx.assign((size_t)W * kBanks, 0);
+        ly.assign((size_t)W * kBanks, 0);
+        slot_of.assign(n, -1);
+        auto index_words = [&](const std::vector<int32_t>& word, std::vector<int32_t>* uniq,
+                               std::vector<int32_t>* id) {
+            uniq->clear();
+            for (int32_t i = 0; i < n; ++i)
+                if (word[arcs[i]] >= 0) uniq->push_back(word[arcs[i]]);
+            std::sort(uniq->begin(), uniq->end());
+            uniq->erase(std::unique(uniq->begin(), uniq->end()), uniq->end());
+            id->assign(n, -1);
+            for (int32_t i = 0; i < n; ++i)
+                if (word[arcs[i]] >= 0)
+                    (*id)[i] = (int32_t)(std::lower_bound(uniq->begin(), uniq->end(), word[arcs[i]]) -
+                                         uniq->begin());
+        };
+        index_words(ax, &ux, &idx);
+        index_words(ay, &uy, &idy);
+        const size_t mx = std::max<size_t>(ux.size(), 1), my = std::max<size_t>(uy.size(), 1);
+        cx.assign((size_t)W * mx, 0);
+        cy.assign((size_t)W * my, 0);
+        std::vector<std::vector<int32_t>> row_arcs(kHalf);
+        for (int32_t i = 0; i < n; ++i) row_arcs[pos_row[arcs[i]] % kHalf].push_back(i);
+        // what arc i would add to slot j: the load of its banks, unless its word is
+        // read there already
+        auto cost_at = [&](int32_t j, int32_t i) {
+            int32_t c = 0;
+            if (idx[i] >= 0 && cx[(size_t)j * mx + idx[i]] == 0)
+                c += lx[(size_t)j * kBanks + ux[idx[i]] % kBanks];
+            if (idy[i] >= 0 && cy[(size_t)j * my + idy[i]] == 0)
+                c += ly[(size_t)j * kBanks + uy[idy[i]] % kBanks];
+            return c;
+        };
+        auto place = [&](int32_t r, int32_t j, int32_t i, int sign) {
+            if (idx[i] >= 0) {
+                uint16_t& c = cx[(size_t)j * mx + idx[i]];
+                int32_t& l = lx[(size_t)j * kBanks + ux[idx[i]] % kBanks];
+                if (sign > 0) { if (c++ == 0) ++l; } else { if (--c == 0) --l; }
+            }
+            if (idy[i] >= 0) {
+                uint16_t& c = cy[(size_t)j * my + idy[i]];
+                int32_t& l = ly[(size_t)j * kBanks + uy[idy[i]] % kBanks];
+                if (sign > 0) { if (c++ == 0) ++l; } else { if (--c == 0) --l; }
+            }
+            table[(size_t)r * W + j] = sign > 0 ? i : -1;
+            slot_of[i] = sign > 0 ? j : -1;
+        };
         // greedy: slot by slot, rows with the fewest arcs left choose first
         std::vector<int32_t> order(kHalf);
         std::vector<std::vector<int32_t>> left = row_arcs;
@@ -523,20 +558,31 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
             }
         }
         // hill climbing on the sum of squared bank loads: move an arc of a row to
-        // another slot of that row (swapping with what is there)
-        auto sq_delta_move = [&](int32_t i, int32_t from, int32_t to) {
-            // change of sum of squares when arc i leaves slot `from` for slot `to`
-            const int32_t a = arcs[i];
-            int64_t d = 0;
-            if (bx[a] >= 0) {
-                d += -2 * lx[(size_t)from * kBanks + bx[a]] + 1;
-                d += 2 * lx[(size_t)to * kBanks + bx[a]] + 1;
+        // another slot of that row (swapping with what is there); the (slot, bank)
+        // cells a move can touch are summed before and after it
+        auto squares = [&](int32_t i, int32_t other, int32_t j1, int32_t j2) {
+            int32_t cells[8];
+            int nc = 0;
+            auto add = [&](int32_t cell) {
+                for (int q = 0; q < nc; ++q)
+                    if (cells[q] == cell) return;
+                cells[nc++] = cell;
+            };
+            int64_t sum = 0;
+            for (int which = 0; which < 2; ++which) {
+                nc = 0;
+                const std::vector<int32_t>& id = which == 0 ? idx : idy;
+                const std::vector<int32_t>& uq = which == 0 ? ux : uy;
+                const std::vector<int32_t>& ld = which == 0 ? lx : ly;
+                for (int32_t arc : {i, other}) {
+                    if (arc < 0 || id[arc] < 0) continue;
+                    const int32_t bank = uq[id[arc]] % kBanks;
+                    add(j1 * kBanks + bank);
+                    add(j2 * kBanks + bank);
+                }
+                for (int q = 0; q < nc; ++q) sum += (int64_t)ld[cells[q]] * ld[cells[q]];
             }
-            if (by[a] >= 0) {
-                d += -2 * ly[(size_t)from * kBanks + by[a]] + 1;
-                d += 2 * ly[(size_t)to * kBanks + by[a]] + 1;
-            }
-            return d;
+            return sum;
         };
         const int64_t tries = 40LL * n;
         for (int64_t it = 0; it < tries; ++it) {
@@ -546,21 +592,14 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int16_t>
             const int32_t j2 = (int32_t)rng.below((uint32_t)W);
             if (j1 == j2) continue;
             const int32_t other = table[(size_t)r * W + j2];
-            // apply, measure, keep if not worse
-            int64_t d = sq_delta_move(i, j1, j2);
+            const int64_t before = squares(i, other, j1, j2);
             place(r, j1, i, -1);
-            if (other >= 0) {
-                d += sq_delta_move(other, j2, j1);
-                place(r, j2, other, -1);
-                // the two moves interact when they share a bank
-                const int32_t a = arcs[i], o = arcs[other];
-                if (bx[a] >= 0 && bx[a] == bx[o]) d -= 2;
-                if (by[a] >= 0 && by[a] == by[o]) d -= 2;
-            }
-            if (d <= 0) {
-                place(r, j2, i, 1);
-                if (other >= 0) place(r, j1, other, 1);
-            } else {
+            if (other >= 0) place(r, j2, other, -1);
+            place(r, j2, i, 1);
+            if (other >= 0) place(r, j1, other, 1);
+            if (squares(i, other, j1, j2) > before) {  // worse: back
+                place(r, j2, i, -1);
+                if (other >= 0) place(r, j1, other, -1);
                 place(r, j1, i, 1);
                 if (other >= 0) place(r, j2, other, 1);
             }
@@ -738,14 +777,14 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
     std::vector<int32_t> prow_f(A), prow_b(A);
     {
         std::vector<int32_t> wf(af.num_slices), wb_(ab.num_slices), dealt_f(S, 0), dealt_b(S, 0);
-        std::vector<int16_t> bxf(A), bxb(A), byy(A);
+        std::vector<int32_t> bxf(A), bxb(A), byy(A);  // the words the gathers read
         for (int64_t a = 0; a < A; ++a) {
             const int32_t i = g.src[a], j = g.dst[a];
             prow_f[a] = af.pos[j] + (hub_f[j] ? dealt_f[j]++ % kLanes : 0);
             prow_b[a] = ab.pos[i] + (hub_b[i] ? dealt_b[i]++ % kLanes : 0);
-            bxf[a] = (int16_t)(af.pos[g.src[a]] % kBanks);
-            bxb[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);
-            byy[a] = tune.emission_conflicts ? (int16_t)(g.pdf[a] % kBanks) : (int16_t)-1;
+            bxf[a] = af.pos[g.src[a]];
+            bxb[a] = ab.pos[g.dst[a]];
+            byy[a] = tune.emission_conflicts ? g.pdf[a] : -1;
         }
         for (int32_t sl = 0; sl < af.num_slices; ++sl) wf[sl] = af.slice_width[sl] - closing;
         for (int32_t sl = 0; sl < ab.num_slices; ++sl) wb_[sl] = ab.slice_width[sl] - closing;
@@ -918,7 +957,7 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
         }
         std::vector<int64_t> seen(num_pdfs, 0);
         std::vector<int32_t> prow(A), nth(A), wo(ao.num_slices);
-        std::vector<int16_t> bx(A), by(A);
+        std::vector<int32_t> bx(A), by(A);  // the words the two gathers read
         for (int64_t a = 0; a < A; ++a) {
             const int32_t d = g.pdf[a];
             // the first `extra` pieces of a pdf hold base + 1 arcs, the others base
@@ -927,8 +966,8 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             const int64_t r = first_row[d] + (n < head ? n / (base + 1) : extra + (n - head) / base);
             nth[a] = (int32_t)(n < head ? n % (base + 1) : (n - head) % base);
             prow[a] = ao.pos[r];
-            bx[a] = (int16_t)(af.pos[g.src[a]] % kBanks);
-            by[a] = (int16_t)(ab.pos[g.dst[a]] % kBanks);
+            bx[a] = af.pos[g.src[a]];
+            by[a] = ab.pos[g.dst[a]];
         }
         for (int32_t sl = 0; sl < ao.num_slices; ++sl) wo[sl] = ao.slice_width[sl];
         if (tune.order_slots) order_slots(prow, bx, by, ao.num_slices, wo, &nth);
