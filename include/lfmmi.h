@@ -121,7 +121,10 @@ void lfmmi_graph_destroy(lfmmi_graph *graph);
  *            whose kernels run on streams of the handle's own (default
  *            priority) between an event recorded on hip_stream and events
  *            hip_stream then waits for: all of the call's work is ordered on
- *            hip_stream as if it ran there.
+ *            hip_stream as if it ran there. (The buckets overlap only while their
+ *            streams sit on hardware queues of their own; HIP gives a process four
+ *            by default, GPU_MAX_HW_QUEUES, and streams that share one run their
+ *            kernels one after the other. LFMMI_BUCKETS=1..4 sets the bucket count.)
  * B == 0 or T == 0 with all lengths 0 are valid. Calls on one handle must be
  * ordered on one stream (they share the handle's workspace). The device the
  * graph was uploaded to must be the current one (LFMMI_ERR_INVALID_ARG if not).
