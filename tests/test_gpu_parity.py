@@ -122,6 +122,24 @@ def test_large_graph_keeps_part_of_each_wave_in_registers_too():
     h.close()
 
 
+def test_wave_with_more_than_64_streamed_slices(monkeypatch):
+    # two waves for 141 slices: each streams about 70 slices a frame, more than the
+    # 64 whose ends (and hub flags) a wave keeps in the lanes of one register
+    monkeypatch.setenv("LFMMI_WAVES", "2")
+    rng = np.random.default_rng(4242)
+    g = workloads.random_den_graph(rng, 9000, 3, 300, 0.5, "uniform")
+    lengths = np.array([7, 12], np.int32)
+    x = rng.normal(0, 2, (2, 12, 300)).astype(np.float32)
+    x[0, 7:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    assert info["waves"] == 2 and 0 < info["register_slots"] < info["max_wave_slots"]
+    assert info["slices"] > 2 * 64 + 2
+    lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
+    check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "two waves")
+    h.close()
+
+
 def test_pdf_with_many_occupancy_rows_fp32_and_fp64():
     # one pdf on most arcs: its arc list is cut into many rows, whose sums a whole
     # wave adds up; with some final weights zero the graph runs in fp64
