@@ -53,9 +53,13 @@ typedef enum {
  * 160 KB of LDS of a compute unit): num_states <= 16384, num_pdfs <= 16384 and
  * 8 * (num_states rounded up to 64) + 8 * (num_pdfs rounded up to 64) + 128
  * <= 163840 bytes, else LFMMI_ERR_UNSUPPORTED. num_arcs may be 0.
- * When some state has final_prob == 0 (numerator-like graphs) the state
- * vectors, trellis and scales are kept in fp64 and the limit above counts 16
- * bytes per state; when every state is final they are fp32.
+ * When some state has final_prob == 0 or init_prob == 0 (left-to-right graphs:
+ * numerators, or any graph entered through one state) the state vectors, trellis
+ * and scales are kept in fp64 and the limit above counts 16 bytes per state;
+ * when every state is initial and final they are fp32. The environment variable
+ * LFMMI_PRECISION=32 or 64, read when a graph is packed, overrides that choice:
+ * it changes results (32 on a left-to-right graph can lose posterior mass to
+ * underflow, which lfmmi_forward_backward then reports in status).
  * lfmmi_graph_create packs and uploads to the current HIP device.
  * lfmmi_graph_pack only packs (no HIP call): for host-side inspection; such a
  * handle is refused by lfmmi_forward_backward until lfmmi_graph_upload.
@@ -113,7 +117,10 @@ void lfmmi_graph_destroy(lfmmi_graph *graph);
  *            denominator with (-1, 1).
  *   status   DEVICE int32 [B] or NULL: 0 ok; bit 0: zero total probability
  *            (log Z = -inf, gamma rows 0); bit 1: a non-finite logit was read
- *            (objf NaN, gamma rows 0).
+ *            (objf NaN, gamma rows 0); bit 2: the alpha pass and the beta pass
+ *            disagree on log Z by more than 1e-3, i.e. one of them lost mass to
+ *            underflow (fp32 state vectors with leak == 0, or forced by
+ *            LFMMI_PRECISION=32): objf and gamma are written but not to be trusted.
  *   hip_stream  hipStream_t (NULL = default stream). The call only enqueues
  *            work; it does not synchronise. It may allocate (and so
  *            synchronise) when the handle's cached workspace has to grow.
@@ -165,7 +172,8 @@ enum { LFMMI_ORD_FWD = 0, LFMMI_ORD_BWD = 1, LFMMI_ORD_OCC = 2 };
 /* info[0] number of graphs, [1] num_pdfs, [2] total states, [3] total arcs,
  * [4] waves per workgroup of the recursion kernel, [5] waves of the occupancy
  * kernel, [6] flags (bit 0: uploaded; bit 1: state vectors kept in fp64, which
- * is chosen when some state has final_prob 0), [7] workspace bytes held. */
+ * is chosen when some state has final_prob 0 or init_prob 0), [7] workspace
+ * bytes held. */
 lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
 
 /* Packed ordering `ord` of graph `g`: info[0] rows, [1] slices (64 rows each),
@@ -176,7 +184,9 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
  * gathers of one frame (per slot and half-wave, the largest number of distinct
  * addresses in one of the 32 banks), [9] 1 if every FWD / BWD slice ends in a
  * closing slot (packed so when init_prob is not uniform), [10] number of hub
- * slices (see below), [11] 0. */
+ * slices (see below), [11] FWD / BWD: rows (slices * 64) one state vector of the
+ * chosen recursion kernel's fixed LDS map holds, 0 when that kernel sizes its LDS
+ * by the graph (arcs streamed). The kernel is chosen so that info[1] * 64 fits. */
 lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph *graph, int32_t g,
                                        int32_t ord, int64_t info[12]);
 /* Copies the packed ordering out (any pointer may be NULL):

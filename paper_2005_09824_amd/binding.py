@@ -192,7 +192,8 @@ def lfmmi_graph_ordering_info(graph, g, ord_):
     info = np.zeros(12, dtype=np.int64)
     _check(load_library().lfmmi_graph_ordering_info(graph.handle, g, ord_, _hp(info)))
     keys = ("rows", "slices", "waves", "total_slots", "max_wave_slots", "register_slots",
-            "emission_replicated", "per_arc_leak", "gather_cycles", "closing_slots", "hub_slices")
+            "emission_replicated", "per_arc_leak", "gather_cycles", "closing_slots", "hub_slices",
+            "lds_vector_rows")
     return dict(zip(keys, (int(v) for v in info)))
 
 

@@ -20,7 +20,7 @@ def _function_class():
             x = logits.detach()
             if x.dtype != torch.float32 or not x.is_contiguous():
                 x = x.float().contiguous()
-            # numerator minus denominator (Eq. 2 / Eq. 3), the two passes overlapping
+            # numerator minus denominator (Eq. 2 / Eq. 3), one call
             objf, grad, status = binding.lfmmi_loss(num_graphs, den_graph, x, lengths, leak)
             ctx.save_for_backward(grad)
             ctx.logits_dtype = logits.dtype

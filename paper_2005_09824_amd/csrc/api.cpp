@@ -126,14 +126,19 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         h->num_pdfs = num_pdfs;
         h->total_states = state_off[n];
         h->total_arcs = arc_off[n];
-        // Every state final: the scaled alpha / beta stay comparable across the
-        // states that carry posterior mass, and fp32 holds them. Otherwise
-        // (left-to-right numerator graphs) that mass can sit tens of orders of
-        // magnitude below the frame total: fp64.
-        bool all_final = true;
+        // fp32 state vectors when every state is both initial and final: a leak then
+        // feeds every state of alpha and of beta a share of the frame's total, which
+        // bounds how far below that total a state that carries posterior mass can
+        // sit, and fp32 holds it. Otherwise (left-to-right graphs: a numerator, or any
+        // graph entered through one state) that mass can sit tens of orders of
+        // magnitude below the total: fp64. (With leak = 0 nothing bounds it in an fp32
+        // graph either; the scan then flags a sequence whose two passes disagree.)
+        bool all_final = true, all_initial = true;
         if (final_prob)
             for (int64_t s = 0; s < state_off[n]; ++s) all_final = all_final && final_prob[s] > 0.f;
-        h->wide = !all_final;
+        if (init_prob)
+            for (int64_t s = 0; s < state_off[n]; ++s) all_initial = all_initial && init_prob[s] > 0.f;
+        h->wide = !(all_final && all_initial);
         if (const char* v = std::getenv("LFMMI_PRECISION")) {
             if (std::atoi(v) == 64) h->wide = true;
             if (std::atoi(v) == 32) h->wide = false;
@@ -179,13 +184,15 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         // Pack for `waves` waves; when the arcs of a wave then fit no register-resident
         // variant of the recursion kernel, try half the waves (twice the registers per
         // lane) before settling for streamed arcs.
+        // (called once the graphs are packed: what has to fit the fixed LDS map of
+        // those kernels, 32 KB per state vector, is the padded row count of the
+        // orderings - hub slices add 63 padding rows each - not the state count;
+        // it does not depend on the number of waves)
         auto registers_possible = [&](int wv) {
             if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return false;  // staging limits
-            for (int32_t g = 0; g < n; ++g) {
-                // fixed LDS map: 32 KB per state vector
-                if (state_off[g + 1] - state_off[g] > (h->wide ? 4096 : 8192)) return false;
+            if (std::max(h->max_rows_f, h->max_rows_b) > (h->wide ? 4096 : 8192)) return false;
+            for (int32_t g = 0; g < n; ++g)
                 if ((double)(arc_off[g + 1] - arc_off[g]) / (64.0 * wv) > 48.0) return false;
-            }
             return true;
         };
         auto pack_with = [&](int wv, int* max_slots) -> lfmmi_status {
@@ -248,7 +255,13 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         {
             int max_slots = 0;
             lfmmi_status st = pack_with(waves, &max_slots);
-            h->rec_nslot = registers_possible(waves)
+            // the replicated emission row was granted on the state count; with the padded
+            // rows known it is given up when the two no longer fit LDS together (the
+            // slot order then ignores emission conflicts: slower, never wrong)
+            if (st == LFMMI_OK && h->rec_yrep &&
+                rec_lds_bytes(std::max(h->max_rows_f, h->max_rows_b), num_pdfs, h->wide, true) > kLdsBytes)
+                h->rec_yrep = false;
+            h->rec_nslot = st == LFMMI_OK && registers_possible(waves)
                                ? rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes)
                                : 0;
             if (st == LFMMI_OK && h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
@@ -264,8 +277,8 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
                 if (h->wide || h->has_wb || env_int("LFMMI_HYBRID", 1) == 0) return 0;
                 if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return 0;
                 if (rec_hybrid_slots(h->wide, h->has_wb) <= 0) return 0;
-                int64_t most = 0;
-                for (int32_t g = 0; g < n; ++g) most = std::max(most, state_off[g + 1] - state_off[g]);
+                // padded rows, not states: see registers_possible
+                const int most = std::max(h->max_rows_f, h->max_rows_b);
                 if (most <= 8192) return 1;
                 return most <= 12288 && !h->rec_yrep ? 2 : 0;
             };
@@ -279,7 +292,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             }
         }
         const int rows = std::max(h->max_rows_f, h->max_rows_b);
-        if (rec_lds_bytes(rows, num_pdfs, h->wide, false) > kLdsBytes ||
+        if (rec_lds_bytes(rows, num_pdfs, h->wide, h->rec_yrep) > kLdsBytes ||
             occ_lds_bytes(h->max_rows_f, h->max_rows_b, h->max_rows_occ, h->wide) > kLdsBytes) {
             delete h;
             return fail(LFMMI_ERR_UNSUPPORTED,
@@ -842,7 +855,10 @@ lfmmi_status lfmmi_graph_ordering_info(const lfmmi_graph* h, int32_t g, int32_t 
     info[9] = ord < 2 ? o.closing_slots : 0;
     info[10] = 0;
     for (int32_t f : o.slice_hub) info[10] += f != 0;
-    info[11] = 0;
+    // rows one state vector of the chosen recursion kernel's fixed LDS map holds
+    info[11] = ord == 2 || h->rec_nslot == 0 ? 0
+               : h->rec_hybrid == 2          ? 12288
+                                             : (h->wide ? 4096 : 8192);
     return LFMMI_OK;
 }
 

@@ -1033,6 +1033,11 @@ struct RecRegs {
 // in fp64. Called by every thread of a workgroup (at most 256 of them work);
 // scratch: 8 KB of LDS nobody else uses.
 // ---------------------------------------------------------------------------
+// Largest difference (nats) between the alpha-side and the beta-side log Z of a
+// sequence that counts as rounding: fp32 state vectors on the longest workloads
+// here differ by a few 1e-5.
+constexpr double kTotalsAgree = 1e-3;
+
 template <typename Real>
 __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scratch_raw)
 {
@@ -1072,8 +1077,14 @@ __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scr
     __syncthreads();
     const double totB = tot[1], msum = tot[2];
     const double lz = log((double)static_cast<const Real*>(p.zfin)[b]) + tot[0];
+    // the same total from the beta side: pi . beta'_0. The two agree up to rounding
+    // unless a pass lost mass to underflow (a state whose alpha is below the range
+    // of Real next to the frame's total while its beta is that much above, or the
+    // other way round): such a sequence is flagged, not returned silently wrong
+    const double lz_beta = log((double)static_cast<const Real*>(p.zfin)[p.B + b]) + totB;
     const bool nonfinite_in = !(msum == msum);
     const bool dead = !(lz > -INFINITY && lz < INFINITY) || nonfinite_in;
+    const bool lossy = !dead && !(fabs(lz - lz_beta) <= kTotalsAgree);
     double ra = work ? sa[tid] : 0.0, rb = work ? sb[tid] : 0.0;
     for (int i = i0; i < i1; ++i) {
         if (i >= 1) cfac[i] = dead ? (Real)0 : (Real)exp(ra + (totB - rb) - lz);
@@ -1084,6 +1095,7 @@ __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scr
         int st = 0;
         if (nonfinite_in) st |= 2;
         if (dead) st |= 1;
+        if (lossy) st |= 4;
         const float val = nonfinite_in ? __builtin_nanf("") : (float)(lz + msum);
         const float out = p.grad_scale * val;
         p.objf[b] = p.accumulate ? p.objf[b] + out : out;

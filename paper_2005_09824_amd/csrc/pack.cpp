@@ -749,10 +749,20 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             hub[s] = tune.hub_slices && deg[s] >= kLanes && deg[s] > 4 * usual ? 1 : 0;
         return hub;
     };
-    const std::vector<uint8_t> hub_f = hubs_of(indeg), hub_b = hubs_of(outdeg);
+    std::vector<uint8_t> hub_f = hubs_of(indeg), hub_b = hubs_of(outdeg);
     Arrangement af = arrange(indeg, rec_waves, closing, &hub_f);
     Arrangement ab = arrange(outdeg, rec_waves, closing, &hub_b);
-    if (af.num_slices * kLanes > kMaxIndex) return "too many states";
+    // A hub slice adds 63 padding rows. Row numbers of both orderings go into 16-bit
+    // key fields (index * 4): when the padded rows of either no longer fit, the
+    // graph is packed without hub slices (slower, never wrong).
+    if (af.num_slices * kLanes > kMaxIndex || ab.num_slices * kLanes > kMaxIndex) {
+        std::fill(hub_f.begin(), hub_f.end(), 0);
+        std::fill(hub_b.begin(), hub_b.end(), 0);
+        af = arrange(indeg, rec_waves, closing, &hub_f);
+        ab = arrange(outdeg, rec_waves, closing, &hub_b);
+    }
+    if (af.num_slices * kLanes > kMaxIndex || ab.num_slices * kLanes > kMaxIndex)
+        return "too many states";
     std::vector<int32_t> vsrc(g.src, g.src + A), vdst(g.dst, g.dst + A);
     if (tune.balance_banks) {
         std::vector<int32_t> room_f(af.slice_width), room_b(ab.slice_width);

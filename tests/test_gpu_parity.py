@@ -309,9 +309,9 @@ def test_sequence_result_does_not_depend_on_batch_neighbours():
     h.close()
 
 
-# ---- the five workloads at full size, in the launch configuration bench.py times.
-# The oracle recomputes a sample of sequences one by one (sequences are
-# independent); properties that hold at any size are checked on every sequence.
+# ---- the five workloads at full size, in the launch configuration bench.py times:
+# every objective and every gradient entry of the whole batch against the oracle,
+# and the properties that hold at any size on every sequence.
 def _full_size(config, sample):
     wl = workloads.make_workload(config)
     x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
@@ -336,17 +336,15 @@ def test_config2_full_size_all_sequences():
     _full_size(2, list(range(64)))
 
 
-def test_config3_full_size_sampled():
-    _full_size(3, [0, 31, 77, 127])
+def test_config3_full_size_all_sequences():
+    _full_size(3, list(range(128)))
 
 
-def test_config4_full_size_sampled():
-    wl = workloads.make_workload(4)
-    longest, shortest = int(np.argmax(wl["lengths"])), int(np.argmin(wl["lengths"]))
-    _full_size(4, sorted({longest, shortest, 5, 20}))
+def test_config4_full_size_all_sequences():
+    _full_size(4, list(range(32)))
 
 
-def test_config5_full_size_num_all_den_sampled():
+def test_config5_full_size_all_sequences():
     wl = workloads.make_workload(5)
     x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
     torch = _torch()
@@ -363,11 +361,14 @@ def test_config5_full_size_num_all_den_sampled():
     for b, Tb in enumerate(lens):   # gamma_num and gamma_den each sum to one per frame
         assert np.abs(grad[b, :Tb].sum(1)).max() <= 4e-4
         assert np.all(grad[b, Tb:] == 0.0)
-    idx = np.asarray([0, 17, 64, 127, int(np.argmax(lens))])
-    lz_d, g_d = oracle.forward_backward(wl["den"], x[idx], lens[idx], leak)
-    tol = OBJF_RTOL * np.maximum(np.maximum(np.abs(lz_n[idx]), np.abs(lz_d)), 1.0)
-    assert np.all(np.abs(objf[idx] - (lz_n[idx] - lz_d)) <= tol)
-    assert np.abs(grad[idx] - (g_n[idx] - g_d)).max() <= GRAD_ATOL
+    lz_d, g_d = oracle.forward_backward(wl["den"], x, lens, leak)
+    tol = OBJF_RTOL * np.maximum(np.maximum(np.abs(lz_n), np.abs(lz_d)), 1.0)
+    err_o = np.abs(objf - (lz_n - lz_d))
+    assert np.all(err_o <= tol)
+    err_g = np.abs(grad - (g_n - g_d)).max()
+    assert err_g <= GRAD_ATOL
+    print("config 5 full size: objf max err / tolerance %.2e, grad max abs err %.2e"
+          % ((err_o / tol).max(), err_g))
     den.close(); num.close()
 
 
@@ -468,7 +469,7 @@ def test_raw_call_without_status_on_a_side_stream_and_argument_errors():
 
 
 def test_loss_call_equals_the_two_passes_bit_for_bit_and_the_oracle():
-    # Eq. 2 / Eq. 3 in one call, numerators and denominator overlapping
+    # Eq. 2 / Eq. 3 in one call
     torch = _torch()
     for seed, scale in ((3, {"S": 400, "B": 9, "Tlo": 12, "Thi": 70}), (4, {"B": 5, "Tlo": 40, "Thi": 90})):
         wl = workloads.make_workload(5, seed=seed, scale=scale, pad_value=np.nan)
@@ -551,4 +552,107 @@ def test_hub_states_in_every_recursion_variant(kind):
     assert binding.lfmmi_graph_info(h)["fp64"] == (1 if kind.startswith("fp64") else 0)
     lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
     check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "hubs, " + kind)
+    h.close()
+
+
+def test_many_hub_slices_push_the_padded_rows_past_the_fixed_lds_map():
+    # 8000 states fit the 32 KB state vectors of the register-resident kernels, the
+    # 8000 + 9 * 63 padded rows of nine hub slices do not: the kernel is chosen by
+    # rows, and every element still matches
+    rng = np.random.default_rng(77)
+    S, P, deg = 8000, 84, 500
+    g = workloads.random_den_graph(rng, S, 9, P, 0.5)
+    src, dst = [g["src"]], [g["dst"]]
+    for hub in range(9):
+        src.append(rng.choice(S, size=deg, replace=False).astype(np.int32))
+        dst.append(np.full(deg, 100 + hub, np.int32))
+    for hub in range(2):
+        src.append(np.full(deg, 4000 + hub, np.int32))
+        dst.append(rng.choice(S, size=deg, replace=False).astype(np.int32))
+    n = 11 * deg
+    g["src"], g["dst"] = np.concatenate(src), np.concatenate(dst)
+    g["pdf"] = np.concatenate([g["pdf"], rng.integers(0, P, n).astype(np.int32)])
+    g["logw"] = np.concatenate([g["logw"], np.log(rng.uniform(0.001, 0.01, n)).astype(np.float32)])
+    lengths = np.array([14, 9, 20], np.int32)
+    x = rng.normal(0, 2, (3, 20, P)).astype(np.float32)
+    for b in range(3):
+        x[b, lengths[b]:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    assert info["hub_slices"] == 9 and info["slices"] * 64 > 8192
+    assert info["register_slots"] == 0 or info["slices"] * 64 <= info["lds_vector_rows"]
+    lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
+    check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "many hubs")
+    h.close()
+
+
+def _left_to_right(rng, n_phones, P, all_initial):
+    """The numerator topology (two states per phone, optional silence) with every
+    state final; a unique start state, or every state initial."""
+    g = workloads.phone_string_num_graph(rng.integers(1, 42, size=n_phones), P, 0.2)
+    g["final_prob"] = np.ones(g["num_states"], np.float32)
+    if all_initial:
+        g["init_prob"] = np.full(g["num_states"], 1.0 / g["num_states"], np.float32)
+    return g
+
+
+def _match_or_flagged(out, lz, gamma, lens):
+    """Every sequence either agrees with the oracle or carries a status flag."""
+    objf, grad, status = out
+    ok = 0
+    for b in range(len(lens)):
+        if status[b] != 0:
+            continue
+        assert abs(objf[b] - lz[b]) <= OBJF_RTOL * max(abs(lz[b]), 1.0), (b, objf[b], lz[b])
+        assert np.abs(grad[b].astype(np.float64) - gamma[b]).max() <= GRAD_ATOL, b
+        ok += 1
+    return ok
+
+
+def test_all_final_left_to_right_graph_without_a_leak():
+    # every state final, so the old criterion (fp32 iff all states final) would have
+    # run these in fp32; without a leak nothing bounds how far below the frame total
+    # a state that carries posterior mass can sit
+    rng = np.random.default_rng(31)
+    P, B = 84, 4
+    lens = np.array([300, 280, 150, 40], np.int32)
+    x = rng.normal(0, 2, (B, 300, P)).astype(np.float32)
+    for b in range(B):
+        x[b, lens[b]:] = np.nan
+    # a unique start state: fp64, every element matches
+    graphs = [_left_to_right(rng, 75, P, False) for _ in range(B)]
+    h = binding.lfmmi_graph_create_batch(graphs)
+    assert binding.lfmmi_graph_info(h)["fp64"] == 1
+    lz, gamma = oracle.forward_backward_per_utt(graphs, x, lens, 0.0)
+    check(*run_gpu(h, x, lens, 0.0), lz, gamma, "all final, one start state, no leak")
+    h.close()
+    # every state initial as well: fp32; with the leak it is bounded and matches,
+    # without it a sequence matches or comes back flagged
+    graphs = [_left_to_right(rng, 75, P, True) for _ in range(B)]
+    h = binding.lfmmi_graph_create_batch(graphs)
+    assert binding.lfmmi_graph_info(h)["fp64"] == 0
+    lz, gamma = oracle.forward_backward_per_utt(graphs, x, lens, 1e-5)
+    check(*run_gpu(h, x, lens, 1e-5), lz, gamma, "all final and initial, leak")
+    lz, gamma = oracle.forward_backward_per_utt(graphs, x, lens, 0.0)
+    ok = _match_or_flagged(run_gpu(h, x, lens, 0.0), lz, gamma, lens)
+    print("all final and initial, no leak, fp32: %d of %d sequences unflagged and matching" % (ok, B))
+    h.close()
+
+
+def test_forced_fp32_on_numerator_graphs_matches_or_is_flagged(monkeypatch):
+    # LFMMI_PRECISION=32 overrides the choice of fp64 for left-to-right graphs; mass
+    # that underflows then shows as a dead sequence or as passes that disagree
+    wl = workloads.make_workload(5, scale={"S": 300, "B": 12, "nlo": 20, "nhi": 120})
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    lz, gamma = oracle.forward_backward_per_utt(wl["num"], x, lens, leak)
+    monkeypatch.setenv("LFMMI_PRECISION", "32")
+    h = binding.lfmmi_graph_create_batch(wl["num"])
+    monkeypatch.delenv("LFMMI_PRECISION")
+    assert binding.lfmmi_graph_info(h)["fp64"] == 0
+    ok = _match_or_flagged(run_gpu(h, x, lens, leak), lz, gamma, lens)
+    print("numerators forced to fp32: %d of %d sequences unflagged and matching" % (ok, len(lens)))
+    h.close()
+    h = binding.lfmmi_graph_create_batch(wl["num"])
+    assert binding.lfmmi_graph_info(h)["fp64"] == 1
+    check(*run_gpu(h, x, lens, leak), lz, gamma, "numerators, fp64")
     h.close()

@@ -264,3 +264,69 @@ def test_hub_states_get_slices_of_their_own(nonuniform):
         assert od[o]["max_wave_slots"] < 64
     assert od[2]["hub_slices"] == 0
     h.close()
+
+
+def _many_hubs(S, hubs_in, hubs_out, deg=600, seed=9, k=9, P=84):
+    """Random graph plus `hubs_in` states with `deg` arcs into them and `hubs_out`
+    states with `deg` arcs out of them."""
+    rng = np.random.default_rng(seed)
+    g = workloads.random_den_graph(rng, S, k, P, 0.5)
+    src, dst = [g["src"]], [g["dst"]]
+    for h in range(hubs_in):
+        src.append(rng.choice(S, size=deg, replace=False).astype(np.int32))
+        dst.append(np.full(deg, 10 + h, np.int32))
+    for h in range(hubs_out):
+        src.append(np.full(deg, 5000 % S + h, np.int32))
+        dst.append(rng.choice(S, size=deg, replace=False).astype(np.int32))
+    n = (hubs_in + hubs_out) * deg
+    g["src"], g["dst"] = np.concatenate(src), np.concatenate(dst)
+    g["pdf"] = np.concatenate([g["pdf"], rng.integers(0, P, n).astype(np.int32)])
+    g["logw"] = np.concatenate([g["logw"], np.log(rng.uniform(0.001, 0.01, n)).astype(np.float32)])
+    return g
+
+
+@pytest.mark.parametrize("S,hubs_in,hubs_out", [
+    (8000, 8, 0),     # 8000 states fit a 32 KB state vector, 8512 padded rows do not
+    (8000, 20, 3),
+    (12200, 0, 4),    # ... nor do 12288 + 3 * 64 the 48 KB map (P > 255: plain emission rows)
+    (4000, 6, 6),     # fits: the register / hybrid kernels stay
+])
+def test_padded_rows_of_hub_slices_fit_the_chosen_kernels_lds_map(S, hubs_in, hubs_out):
+    # every hub state gets a slice of its own, i.e. 63 padding rows: what must fit
+    # the fixed LDS map of the register-resident kernels is the padded row count
+    g = _many_hubs(S, hubs_in, hubs_out, P=300 if S > 12000 else 84)
+    h = binding.lfmmi_graph_pack(g)
+    for o in (0, 1):
+        info = binding.lfmmi_graph_ordering_info(h, 0, o)
+        assert info["hub_slices"] == (hubs_in, hubs_out)[o]
+        assert info["slices"] * 64 >= S + 63 * info["hub_slices"]
+        if info["register_slots"] > 0:
+            assert info["slices"] * 64 <= info["lds_vector_rows"], info
+        else:
+            assert info["lds_vector_rows"] == 0
+    rows = max(binding.lfmmi_graph_ordering_info(h, 0, o)["slices"] * 64 for o in (0, 1))
+    resident = binding.lfmmi_graph_ordering_info(h, 0, 0)["register_slots"] > 0
+    if S == 4000:
+        assert resident and rows <= 8192
+    elif S == 8000:
+        assert rows > 8192 and not resident
+    else:
+        assert rows > 12288 and not resident
+    h.close()
+
+
+def test_hub_slices_are_given_up_when_their_padding_rows_overflow_the_key_fields():
+    # 16300 states and 5 out-degree hubs: 16640 BWD rows would not fit the 16-bit
+    # (row * 4) fields of the arc records; the graph is packed without hub slices
+    g = _many_hubs(16300, 0, 5, deg=300, k=2, P=40)
+    h = binding.lfmmi_graph_pack(g)
+    got, want, od = _unpack(h, 0, g)
+    for o in range(3):
+        assert got[o] == want, "ordering %d lost or changed arcs" % o
+        assert od[o]["hub_slices"] == 0
+    for o in (0, 1):
+        assert od[o]["slices"] * 64 <= 16384
+        assert int((od[o]["key"] & 0xFFFF).max()) // 4 < od[o]["slices"] * 64
+    # OCC keys: both fields are row numbers
+    assert int((od[2]["key"] >> 16).max()) // 4 < od[1]["slices"] * 64
+    h.close()
