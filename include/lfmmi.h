@@ -143,6 +143,35 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph *graph, const float *logit
                                     int32_t *status, void *hip_stream);
 
 /*
+ * lfmmi_forward_backward for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments,
+ * same results; the call's workspace (emission values, both trellises, per-frame
+ * scales, descriptors) lies in a static device array of
+ * LFMMI_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds from the
+ * first graph upload on that GPU until the process ends, instead of in memory the
+ * handle allocates. The call makes no hipMalloc / hipFree / hipHostMalloc, creates
+ * no stream or event and copies nothing from the host: the lengths travel as a
+ * kernel argument, all kernels run on hip_stream in one bucket, and there is no
+ * per-kernel timing (lfmmi_profile_enable does not apply).
+ * Limits: B <= LFMMI_STATIC_MAX_BATCH, and the workspace the call needs - about
+ *   4 * B * T * P + 4 * sum_b (lengths[b] + 1) * (rows_fwd + rows_bwd + 5) bytes
+ * (8 instead of 4 in the second term for fp64 graphs; rows = the padded row counts
+ * lfmmi_graph_ordering_info reports as 64 * info[1]) - must fit the array, else
+ * LFMMI_ERR_UNSUPPORTED with the two sizes in lfmmi_last_error().
+ * All calls on one GPU share that GPU's array, whatever their handle or stream:
+ * calls that overlap on one GPU race, so order them (one stream, or events).
+ * Nothing in the array has to survive between calls; what must start at zero is
+ * cleared by the call's own kernels.
+ */
+#define LFMMI_STATIC_WORKSPACE_BYTES (64u << 20)
+#define LFMMI_STATIC_MAX_BATCH 256
+lfmmi_status lfmmi_forward_backward_static(const lfmmi_graph *graph, const float *logits,
+                                           const int32_t *lengths, int32_t B, int32_t T,
+                                           int32_t P, float leak, float grad_scale,
+                                           int accumulate, float *objf, float *grad,
+                                           int32_t *status, void *hip_stream);
+
+/*
  * The whole objective of Eq. 2 and its gradient, Eq. 3, in one call:
  *   objf[b]     = log P(X_b | numerator graph b) - log P(X_b | denominator graph)
  *   grad[b,t,:] = numerator occupancies - denominator occupancies (rows t >= lengths[b]: 0)

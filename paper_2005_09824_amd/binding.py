@@ -20,7 +20,8 @@ ORD_FWD, ORD_BWD, ORD_OCC = 0, 1, 2
 EXPORTS = [
     "lfmmi_graph_create", "lfmmi_graph_pack", "lfmmi_graph_create_batch",
     "lfmmi_graph_pack_batch", "lfmmi_graph_upload", "lfmmi_graph_destroy",
-    "lfmmi_forward_backward", "lfmmi_loss", "lfmmi_last_error", "lfmmi_graph_info",
+    "lfmmi_forward_backward", "lfmmi_forward_backward_static", "lfmmi_loss", "lfmmi_last_error",
+    "lfmmi_graph_info",
     "lfmmi_graph_ordering_info", "lfmmi_graph_ordering_copy",
     "lfmmi_profile_enable", "lfmmi_profile_read",
 ]
@@ -56,6 +57,7 @@ def load_library():
     lib.lfmmi_graph_destroy.restype = None
     lib.lfmmi_forward_backward.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32,
                                            ctypes.c_int, vp, vp, vp, vp]
+    lib.lfmmi_forward_backward_static.argtypes = lib.lfmmi_forward_backward.argtypes
     lib.lfmmi_loss.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp]
     lib.lfmmi_last_error.argtypes = []
     lib.lfmmi_last_error.restype = ctypes.c_char_p
@@ -212,8 +214,23 @@ def lfmmi_graph_ordering_copy(graph, g, ord_):
                 slice_hub=slice_hub)
 
 
+STATIC_WORKSPACE_BYTES = 64 << 20   # LFMMI_STATIC_WORKSPACE_BYTES
+STATIC_MAX_BATCH = 256              # LFMMI_STATIC_MAX_BATCH
+
+
+def lfmmi_forward_backward_static(graph, logits, lengths, leak, grad_scale, accumulate,
+                                  objf, grad, status, stream=None):
+    """The entry point that allocates nothing: as lfmmi_forward_backward, with the
+    outputs passed in (this wrapper allocates nothing either) and the workspace
+    in the library's static device array."""
+    return lfmmi_forward_backward(graph, logits, lengths, leak, grad_scale, accumulate,
+                                  objf, grad, status, stream,
+                                  _entry="lfmmi_forward_backward_static")
+
+
 def lfmmi_forward_backward(graph, logits, lengths, leak, grad_scale=1.0, accumulate=False,
-                           objf=None, grad=None, status=None, stream=None):
+                           objf=None, grad=None, status=None, stream=None,
+                           _entry="lfmmi_forward_backward"):
     """logits: torch float32 CUDA tensor [B, T, P]; lengths: host int array [B].
     Returns (objf [B], grad [B, T, P], status [B]) device tensors (allocated here
     unless passed in). Enqueues on `stream` (default: torch's current stream)."""
@@ -242,7 +259,7 @@ def lfmmi_forward_backward(graph, logits, lengths, leak, grad_scale=1.0, accumul
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
     with torch.cuda.device(dev):
-        _check(load_library().lfmmi_forward_backward(
+        _check(getattr(load_library(), _entry)(
             graph.handle, ctypes.c_void_p(logits.data_ptr()), _hp(lens), B, T, P,
             float(leak), float(grad_scale), 1 if accumulate else 0,
             ctypes.c_void_p(objf.data_ptr()), ctypes.c_void_p(grad.data_ptr()),

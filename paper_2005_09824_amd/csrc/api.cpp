@@ -21,6 +21,10 @@
 
 using namespace lfmmi;
 
+static_assert(LFMMI_STATIC_WORKSPACE_BYTES == kStaticWorkspaceBytes &&
+                  LFMMI_STATIC_MAX_BATCH == kStaticMaxBatch,
+              "the header states the limits of the static workspace");
+
 namespace {
 
 thread_local std::string g_error;
@@ -326,6 +330,9 @@ lfmmi_status upload(lfmmi_graph* h)
         std::lock_guard<std::mutex> lock(mu);
         if (std::find(done.begin(), done.end(), h->device) == done.end()) {
             if ((e = configure_kernels()) != hipSuccess) return fail_hip(e, "hipFuncSetAttribute");
+            // ... and the address of this device's copy of the static workspace
+            if ((e = find_static_workspace(h->device)) != hipSuccess)
+                return fail_hip(e, "hipGetSymbolAddress");
             done.push_back(h->device);
         }
     }
@@ -471,6 +478,124 @@ lfmmi_status upload(lfmmi_graph* h)
     return LFMMI_OK;
 }
 
+// Argument checks shared by the forward-backward entry points (B == 0 is valid:
+// the caller then returns at once).
+lfmmi_status check_call(const lfmmi_graph* h, const float* logits, const int32_t* lengths,
+                        int32_t B, int32_t T, int32_t P, float leak, float grad_scale,
+                        const float* objf, const float* grad)
+{
+    if (!h) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
+    if (!h->uploaded) return fail(LFMMI_ERR_INVALID_ARG, "graph was packed but not uploaded");
+    if (B < 0 || T < 0) return fail(LFMMI_ERR_INVALID_ARG, "B and T must be >= 0");
+    if (P != h->num_pdfs) return fail(LFMMI_ERR_INVALID_ARG, "P differs from the graph's num_pdfs");
+    if (!(leak >= 0.f) || !(leak < INFINITY)) return fail(LFMMI_ERR_INVALID_ARG, "leak must be finite and >= 0");
+    if (!(grad_scale == grad_scale)) return fail(LFMMI_ERR_INVALID_ARG, "grad_scale is NaN");
+    if (h->num_graphs != 1 && h->num_graphs != B)
+        return fail(LFMMI_ERR_INVALID_ARG, "a batch handle needs one graph per sequence");
+    if (B == 0) return LFMMI_OK;
+    if (!lengths || !objf) return fail(LFMMI_ERR_INVALID_ARG, "lengths / objf is null");
+    if (T > 0 && (!logits || !grad)) return fail(LFMMI_ERR_INVALID_ARG, "logits / grad is null");
+    if (B > 32767) return fail(LFMMI_ERR_UNSUPPORTED, "B exceeds 32767");
+    for (int32_t b = 0; b < B; ++b)
+        if (lengths[b] < 0 || lengths[b] > T)
+            return fail(LFMMI_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, T]");
+    // the packed graph and the workspace live on the device of the upload
+    int current = -1;
+    const hipError_t e = hipGetDevice(&current);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (current != h->device)
+        return fail(LFMMI_ERR_INVALID_ARG, "the graph was uploaded to device " +
+                                               std::to_string(h->device) + ", the current device is " +
+                                               std::to_string(current));
+    return LFMMI_OK;
+}
+
+// Where the parts of a call's workspace lie (byte offsets): the descriptors
+// first (what a call stages from the host), then what the kernels produce.
+struct CallLayout {
+    size_t at_seqs, at_order, stage_need, at_emis, at_rowmax, at_alpha, at_beta, at_scal, at_cfac,
+        at_zfin, at_status, total;
+    int64_t scal_total;
+};
+
+// a_at / b_at: values in all alpha / beta trellises; s_at: frames + sequences.
+CallLayout layout_call(const lfmmi_graph* h, int32_t B, int32_t T, int32_t P, int64_t a_at,
+                       int64_t b_at, int64_t s_at)
+{
+    CallLayout l{};
+    size_t total = 0;
+    l.at_seqs = reserve<SeqDesc>(&total, B);
+    l.at_order = reserve<int32_t>(&total, (size_t)2 * B);
+    l.stage_need = total;
+    l.at_emis = reserve<float>(&total, (size_t)B * T * P);
+    l.at_rowmax = reserve<float>(&total, (size_t)B * T);
+    const size_t real = h->wide ? 2 : 1;  // floats per value
+    l.at_alpha = reserve<float>(&total, (size_t)a_at * real);
+    l.at_beta = reserve<float>(&total, (size_t)b_at * real);
+    l.at_scal = reserve<float>(&total, (size_t)4 * s_at * real);
+    l.at_cfac = reserve<float>(&total, (size_t)s_at * real);
+    l.at_zfin = reserve<float>(&total, (size_t)2 * B * real);
+    l.at_status = reserve<int32_t>(&total, B);
+    l.total = total;
+    l.scal_total = s_at;
+    return l;
+}
+
+void fill_params(const lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
+                 const float* logits, int32_t B, int32_t T, int32_t P, float leak,
+                 float grad_scale, int accumulate, float* objf, float* grad, int32_t* status,
+                 FbParams* out, LaunchShape* shape_out)
+{
+    FbParams& p = *out;
+    p.g = h->dg;
+    p.seqs = reinterpret_cast<const SeqDesc*>(ws + lay.at_seqs);
+    p.order = reinterpret_cast<const int32_t*>(ws + lay.at_order);
+    p.logits = logits;
+    p.emis = reinterpret_cast<float*>(ws + lay.at_emis);
+    p.rowmax = reinterpret_cast<float*>(ws + lay.at_rowmax);
+    p.alpha = ws + lay.at_alpha;
+    p.beta = ws + lay.at_beta;
+    p.scal = ws + lay.at_scal;
+    p.cfac = ws + lay.at_cfac;
+    p.zfin = ws + lay.at_zfin;
+    p.wide = h->wide ? 1 : 0;
+    p.done = reinterpret_cast<int32_t*>(ws + lay.at_status);
+    p.status_out = status;
+    p.objf = objf;
+    p.grad = grad;
+    p.scal_total = lay.scal_total;
+    p.B = B;
+    p.T = T;
+    p.P = P;
+    p.lds_rows = std::max(h->max_rows_f, h->max_rows_b);
+    p.lds_rows_occ_a = h->max_rows_f;
+    p.lds_rows_occ_b = h->max_rows_b;
+    p.lds_rows_occ = h->max_rows_occ;
+    p.accumulate = accumulate ? 1 : 0;
+    p.leak = leak;
+    p.grad_scale = grad_scale;
+
+    LaunchShape& shape = *shape_out;
+    shape.rec_threads = h->rec_waves * kLanes;
+    shape.rec_nslot = h->rec_nslot;
+    shape.rec_yrep = h->rec_yrep ? 1 : 0;
+    shape.rec_hybrid = h->rec_hybrid;
+    shape.rec_hubs = h->rec_hubs ? 1 : 0;
+    shape.profile_rec_only = h->profile == 2 ? 1 : 0;
+    shape.rec_has_wb = h->has_wb ? 1 : 0;
+    shape.occ_threads = h->occ_waves * kLanes;
+    shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
+    // the plane-layout occupancy kernel (several frames per arc record) when it fits
+    shape.occ_multi = h->wide ? 0 : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b), h->max_rows_occ);
+    {
+        const int forced = env_int("LFMMI_OCC_MULTI", -1);
+        if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;
+    }
+    // groups of frames per workgroup: with one frame per group a workgroup takes four,
+    // which spreads its start-up cost and lets it fetch the next frame's rows early
+    shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", shape.occ_multi == 1 ? 4 : 1));
+}
+
 }  // namespace
 
 extern "C" {
@@ -555,32 +680,10 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
                                     float* grad, int32_t* status, void* hip_stream)
 {
     lfmmi_graph* h = const_cast<lfmmi_graph*>(graph);  // the workspace is mutable state
-    if (!h) return fail(LFMMI_ERR_INVALID_ARG, "graph is null");
-    if (!h->uploaded) return fail(LFMMI_ERR_INVALID_ARG, "graph was packed but not uploaded");
-    if (B < 0 || T < 0) return fail(LFMMI_ERR_INVALID_ARG, "B and T must be >= 0");
-    if (P != h->num_pdfs) return fail(LFMMI_ERR_INVALID_ARG, "P differs from the graph's num_pdfs");
-    if (!(leak >= 0.f) || !(leak < INFINITY)) return fail(LFMMI_ERR_INVALID_ARG, "leak must be finite and >= 0");
-    if (!(grad_scale == grad_scale)) return fail(LFMMI_ERR_INVALID_ARG, "grad_scale is NaN");
-    if (h->num_graphs != 1 && h->num_graphs != B)
-        return fail(LFMMI_ERR_INVALID_ARG, "a batch handle needs one graph per sequence");
-    if (B == 0) return LFMMI_OK;
-    if (!lengths || !objf) return fail(LFMMI_ERR_INVALID_ARG, "lengths / objf is null");
-    if (T > 0 && (!logits || !grad)) return fail(LFMMI_ERR_INVALID_ARG, "logits / grad is null");
-    if (B > 32767) return fail(LFMMI_ERR_UNSUPPORTED, "B exceeds 32767");
-    for (int32_t b = 0; b < B; ++b)
-        if (lengths[b] < 0 || lengths[b] > T)
-            return fail(LFMMI_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, T]");
+    lfmmi_status st = check_call(h, logits, lengths, B, T, P, leak, grad_scale, objf, grad);
+    if (st != LFMMI_OK || B == 0) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
-    {
-        // the packed graph and the workspace live on the device of the upload
-        int current = -1;
-        if ((e = hipGetDevice(&current)) != hipSuccess) return fail_hip(e, "hipGetDevice");
-        if (current != h->device)
-            return fail(LFMMI_ERR_INVALID_ARG, "the graph was uploaded to device " +
-                                                   std::to_string(h->device) + ", the current device is " +
-                                                   std::to_string(current));
-    }
 
     // ---- per-sequence descriptors and the launch order (longest first)
     std::vector<SeqDesc> seqs(B);
@@ -613,21 +716,8 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
         order[(size_t)2 * i + 1] = (by_len[i] << 1) | 1;
     }
 
-    // ---- workspace layout
-    size_t total = 0;
-    const size_t at_seqs = reserve<SeqDesc>(&total, B);
-    const size_t at_order = reserve<int32_t>(&total, (size_t)2 * B);
-    const size_t stage_need = total;
-    const size_t at_emis = reserve<float>(&total, (size_t)B * T * P);
-    const size_t at_rowmax = reserve<float>(&total, (size_t)B * T);
-    const size_t real = h->wide ? 2 : 1;  // floats per value
-    const size_t at_alpha = reserve<float>(&total, (size_t)a_at * real);
-    const size_t at_beta = reserve<float>(&total, (size_t)b_at * real);
-    const size_t at_scal = reserve<float>(&total, (size_t)4 * s_at * real);
-    const size_t at_cfac = reserve<float>(&total, (size_t)s_at * real);
-    const size_t at_zfin = reserve<float>(&total, (size_t)2 * B * real);
-    const size_t at_status = reserve<int32_t>(&total, B);
-
+    const CallLayout lay = layout_call(h, B, T, P, a_at, b_at, s_at);
+    const size_t total = lay.total, stage_need = lay.stage_need;
     if (total > h->ws_bytes) {
         h->desc_lengths.clear();
         h->desc_T = -1;
@@ -672,12 +762,12 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
                 return fail_hip(e, "hipEventSynchronize");
             h->stage_pending = false;
         }
-        unsigned char* st = static_cast<unsigned char*>(h->stage);
-        std::memcpy(st + at_seqs, seqs.data(), sizeof(SeqDesc) * B);
-        std::memcpy(st + at_order, order.data(), sizeof(int32_t) * 2 * B);
+        unsigned char* stg = static_cast<unsigned char*>(h->stage);
+        std::memcpy(stg + lay.at_seqs, seqs.data(), sizeof(SeqDesc) * B);
+        std::memcpy(stg + lay.at_order, order.data(), sizeof(int32_t) * 2 * B);
         h->desc_lengths.clear();
         h->desc_T = -1;
-        if ((e = hipMemcpyAsync(ws, st, stage_need, hipMemcpyHostToDevice, stream)) != hipSuccess)
+        if ((e = hipMemcpyAsync(ws, stg, stage_need, hipMemcpyHostToDevice, stream)) != hipSuccess)
             return fail_hip(e, "hipMemcpyAsync");
         if ((e = hipEventRecord(h->stage_done, stream)) != hipSuccess)
             return fail_hip(e, "hipEventRecord");
@@ -687,53 +777,9 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
     }
 
     FbParams p{};
-    p.g = h->dg;
-    p.seqs = reinterpret_cast<const SeqDesc*>(ws + at_seqs);
-    p.order = reinterpret_cast<const int32_t*>(ws + at_order);
-    p.logits = logits;
-    p.emis = reinterpret_cast<float*>(ws + at_emis);
-    p.rowmax = reinterpret_cast<float*>(ws + at_rowmax);
-    p.alpha = ws + at_alpha;
-    p.beta = ws + at_beta;
-    p.scal = ws + at_scal;
-    p.cfac = ws + at_cfac;
-    p.zfin = ws + at_zfin;
-    p.wide = h->wide ? 1 : 0;
-    p.done = reinterpret_cast<int32_t*>(ws + at_status);
-    p.status_out = status;
-    p.objf = objf;
-    p.grad = grad;
-    p.scal_total = s_at;
-    p.B = B;
-    p.T = T;
-    p.P = P;
-    p.lds_rows = std::max(h->max_rows_f, h->max_rows_b);
-    p.lds_rows_occ_a = h->max_rows_f;
-    p.lds_rows_occ_b = h->max_rows_b;
-    p.lds_rows_occ = h->max_rows_occ;
-    p.accumulate = accumulate ? 1 : 0;
-    p.leak = leak;
-    p.grad_scale = grad_scale;
-
     LaunchShape shape;
-    shape.rec_threads = h->rec_waves * kLanes;
-    shape.rec_nslot = h->rec_nslot;
-    shape.rec_yrep = h->rec_yrep ? 1 : 0;
-    shape.rec_hybrid = h->rec_hybrid;
-    shape.rec_hubs = h->rec_hubs ? 1 : 0;
-    shape.profile_rec_only = h->profile == 2 ? 1 : 0;
-    shape.rec_has_wb = h->has_wb ? 1 : 0;
-    shape.occ_threads = h->occ_waves * kLanes;
-    shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
-    // the plane-layout occupancy kernel (several frames per arc record) when it fits
-    shape.occ_multi = h->wide ? 0 : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b), h->max_rows_occ);
-    {
-        const int forced = env_int("LFMMI_OCC_MULTI", -1);
-        if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;
-    }
-    // groups of frames per workgroup: with one frame per group a workgroup takes four,
-    // which spreads its start-up cost and lets it fetch the next frame's rows early
-    shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", shape.occ_multi == 1 ? 4 : 1));
+    fill_params(h, lay, ws, logits, B, T, P, leak, grad_scale, accumulate, objf, grad, status, &p,
+                &shape);
 
     // ---- buckets of sequences that run concurrently (longest sequences first):
     // an eighth, a quarter, a quarter and the rest, so that the bucket that ends
@@ -800,6 +846,59 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
         ev = h->ev.data() + first;
     }
     if ((e = launch_forward_backward(p, shape, stream, ev, bk)) != hipSuccess)
+        return fail_hip(e, "kernel launch");
+    return LFMMI_OK;
+}
+
+lfmmi_status lfmmi_forward_backward_static(const lfmmi_graph* graph, const float* logits,
+                                           const int32_t* lengths, int32_t B, int32_t T,
+                                           int32_t P, float leak, float grad_scale,
+                                           int accumulate, float* objf, float* grad,
+                                           int32_t* status, void* hip_stream)
+{
+    lfmmi_graph* h = const_cast<lfmmi_graph*>(graph);
+    lfmmi_status st = check_call(h, logits, lengths, B, T, P, leak, grad_scale, objf, grad);
+    if (st != LFMMI_OK || B == 0) return st;
+    if (B > LFMMI_STATIC_MAX_BATCH)
+        return fail(LFMMI_ERR_UNSUPPORTED, "B = " + std::to_string(B) + " exceeds the " +
+                                               std::to_string(LFMMI_STATIC_MAX_BATCH) +
+                                               " sequences of the allocation-free entry point");
+    int64_t a_at = 0, b_at = 0, s_at = 0;
+    int32_t t_most = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t g = h->num_graphs == 1 ? 0 : b;
+        a_at += (int64_t)h->packed[g].ord[0].num_slices * kLanes * (lengths[b] + 1);
+        b_at += (int64_t)h->packed[g].ord[1].num_slices * kLanes * (lengths[b] + 1);
+        s_at += lengths[b] + 1;
+        t_most = std::max(t_most, lengths[b]);
+    }
+    const CallLayout lay = layout_call(h, B, T, P, a_at, b_at, s_at);
+    if (lay.total > (size_t)LFMMI_STATIC_WORKSPACE_BYTES)
+        return fail(LFMMI_ERR_UNSUPPORTED,
+                    "this call needs " + std::to_string(lay.total) + " bytes of workspace, the "
+                    "allocation-free entry point holds " +
+                    std::to_string((size_t)LFMMI_STATIC_WORKSPACE_BYTES));
+    // the device's copy of the static array, looked up when the graph was uploaded
+    unsigned char* ws = static_cast<unsigned char*>(static_workspace(h->device));
+    if (!ws) return fail(LFMMI_ERR_HIP, "the static workspace of this device was not found");
+
+    FbParams p{};
+    LaunchShape shape;
+    fill_params(h, lay, ws, logits, B, T, P, leak, grad_scale, accumulate, objf, grad, status, &p,
+                &shape);
+    shape.profile_rec_only = 0;
+    Buckets bk;  // one bucket, on the caller's stream: no stream or event of the library's
+    bk.n = 1;
+    bk.first[0] = 0;
+    bk.count[0] = B;
+    bk.tmax[0] = t_most;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    // descriptors and launch order are written on the device, from the lengths
+    // passed as a kernel argument (no host-to-device copy to stage)
+    if ((e = launch_describe(p, lengths, h->num_graphs, stream)) != hipSuccess)
+        return fail_hip(e, "kernel launch");
+    if ((e = launch_forward_backward(p, shape, stream, nullptr, bk)) != hipSuccess)
         return fail_hip(e, "kernel launch");
     return LFMMI_OK;
 }

@@ -117,6 +117,20 @@ struct Buckets {
 hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
                                    hipStream_t stream, hipEvent_t* ev, const Buckets& bk);
 hipError_t configure_kernels();
+
+// The static device workspace of the allocation-free entry point: a file-scope
+// device array of kStaticWorkspaceBytes, of which every GPU holds its own copy.
+// find_static_workspace looks up the address of `device`'s copy (that device must
+// be current); static_workspace returns it afterwards (null before).
+constexpr size_t kStaticWorkspaceBytes = (size_t)64 << 20;
+constexpr int kStaticMaxBatch = 256;
+hipError_t find_static_workspace(int device);
+void* static_workspace(int device);
+// Writes the per-sequence descriptors and the launch order of a call (p.seqs,
+// p.order, both inside the workspace) on the device, from the host array
+// lengths[p.B] passed by value; p.B <= kStaticMaxBatch.
+hipError_t launch_describe(const FbParams& p, const int32_t* lengths, int num_graphs,
+                           hipStream_t stream);
 // Dynamic LDS the recursion / occupancy kernels need.
 size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
 // Register-resident slot count the recursion kernel offers for this shape (0: none).

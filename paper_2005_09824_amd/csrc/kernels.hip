@@ -1810,6 +1810,92 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     return hipSuccess;
 }
 
+// ---- the allocation-free entry point's workspace --------------------------------
+// For callers that cannot allocate (HIP graph capture, serving loops): the
+// workspace of a call sits in this array instead of in memory the handle
+// allocates. Each GPU the library runs on holds its own copy, at its own address,
+// until the process ends; the array's name is only a host-side stand-in, so host
+// code uses the address hipGetSymbolAddress returned for the device.
+namespace {
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+struct StaticLengths {
+    int32_t T[kStaticMaxBatch];
+};
+
+// One workgroup: what the host writes for the allocating entry point, computed
+// here. Sequences are launched longest first (by frames times arc slots).
+__global__ void __launch_bounds__(kStaticMaxBatch) k_describe(FbParams p, StaticLengths len,
+                                                              int num_graphs)
+{
+    __shared__ long long work[kStaticMaxBatch];
+    SeqDesc* seqs = const_cast<SeqDesc*>(p.seqs);
+    int32_t* order = const_cast<int32_t*>(p.order);
+    const int b = threadIdx.x;
+    if (b < p.B) {
+        const int g = num_graphs == 1 ? 0 : b;
+        work[b] = (long long)len.T[b] * p.g.ords[g * 3].total_slots;
+    }
+    __syncthreads();
+    if (b < p.B) {
+        int rank = 0;  // sequences that go before this one
+        for (int o = 0; o < p.B; ++o) {
+            const bool before =
+                work[o] != work[b] ? work[o] > work[b]
+                                   : (len.T[o] != len.T[b] ? len.T[o] > len.T[b] : o < b);
+            rank += before ? 1 : 0;
+        }
+        order[2 * rank] = b << 1;
+        order[2 * rank + 1] = (b << 1) | 1;
+    }
+    if (b == 0) {
+        long long a_at = 0, b_at = 0, s_at = 0;
+        for (int i = 0; i < p.B; ++i) {
+            const int g = num_graphs == 1 ? 0 : i;
+            SeqDesc sd;
+            sd.alpha_at = a_at;
+            sd.beta_at = b_at;
+            sd.T = len.T[i];
+            sd.graph = g;
+            sd.scal_at = (int32_t)s_at;
+            sd.pad = 0;
+            seqs[i] = sd;
+            a_at += (long long)p.g.ords[g * 3 + 0].num_slices * 64 * (len.T[i] + 1);
+            b_at += (long long)p.g.ords[g * 3 + 1].num_slices * 64 * (len.T[i] + 1);
+            s_at += len.T[i] + 1;
+        }
+    }
+}
+}  // namespace
+
+hipError_t find_static_workspace(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = ptr;
+    return hipSuccess;
+}
+
+void* static_workspace(int device)
+{
+    return device >= 0 && device < kMaxDevices ? g_scratch_ptr[device] : nullptr;
+}
+
+hipError_t launch_describe(const FbParams& p, const int32_t* lengths, int num_graphs,
+                           hipStream_t stream)
+{
+    if (p.B < 1 || p.B > kStaticMaxBatch) return hipErrorInvalidValue;
+    StaticLengths len;
+    for (int b = 0; b < kStaticMaxBatch; ++b) len.T[b] = b < p.B ? lengths[b] : 0;
+    hipLaunchKernelGGL(k_describe, dim3(1), dim3(kStaticMaxBatch), 0, stream, p, len, num_graphs);
+    return hipGetLastError();
+}
+
 hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
                                    hipStream_t stream, hipEvent_t* ev, const Buckets& bk)
 {

@@ -1,0 +1,119 @@
+"""The entry point that allocates nothing (lfmmi_forward_backward_static) against
+lfmmi_forward_backward, through the C ABI: same arguments, the workspace in the
+library's static device array. Two calls in a row, the second with a smaller
+input, then the limits."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2005_09824_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+OBJF_RTOL = 1e-4
+GRAD_ATOL = 1e-4
+
+
+def _raw(entry, handle, x, lens, leak, scale, accumulate, objf, grad, status, stream):
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+    B, T, P = x.shape
+    lens = np.ascontiguousarray(lens, dtype=np.int32)
+    return getattr(lib, entry)(handle, vp(x.data_ptr()), lens.ctypes.data_as(vp), B, T, P,
+                               float(leak), float(scale), int(accumulate), vp(objf.data_ptr()),
+                               vp(grad.data_ptr()), vp(status.data_ptr()), vp(stream))
+
+
+def _both(handle, logits, lens, leak, scale=1.0):
+    """(static entry point's outputs, allocating entry point's outputs), as numpy."""
+    import torch
+    x = torch.from_numpy(np.ascontiguousarray(logits)).cuda()
+    B, T, P = x.shape
+    outs = []
+    stream = torch.cuda.current_stream().cuda_stream
+    for entry in ("lfmmi_forward_backward_static", "lfmmi_forward_backward"):
+        objf = torch.full((B,), 7.0, dtype=torch.float32, device="cuda")
+        grad = torch.full((B, T, P), -3.0, dtype=torch.float32, device="cuda")
+        status = torch.full((B,), 9, dtype=torch.int32, device="cuda")
+        rc = _raw(entry, handle.handle, x, lens, leak, scale, 0, objf, grad, status, stream)
+        assert rc == 0, (entry, binding.lfmmi_last_error())
+        torch.cuda.synchronize()
+        outs.append((objf.cpu().numpy(), grad.cpu().numpy(), status.cpu().numpy()))
+    return outs
+
+
+def _same(got, want, lens):
+    objf, grad, status = got
+    objf_w, grad_w, status_w = want
+    assert np.array_equal(status, status_w) and np.all(status == 0)
+    assert np.all(np.abs(objf - objf_w) <= OBJF_RTOL * np.abs(objf_w))
+    assert np.abs(grad - grad_w).max() <= GRAD_ATOL
+    for b, Tb in enumerate(lens):
+        assert np.all(grad[b, Tb:] == 0.0)
+    # every sequence is computed by the same kernels in the same way
+    assert np.array_equal(objf, objf_w) and np.array_equal(grad, grad_w)
+
+
+def test_static_entry_point_equals_the_allocating_one_twice_in_a_row():
+    # the first call: the metric's graph, ragged lengths, NaN in the padding frames;
+    # the second, smaller one finds the first call's contents in the shared array
+    wl = workloads.make_workload(2, scale={"B": 7, "Tlo": 30, "Thi": 120}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    got, want = _both(h, wl["logits"], wl["lengths"], wl["leak"])
+    _same(got, want, wl["lengths"])
+    small = workloads.make_workload(2, seed=99, scale={"B": 3, "Tlo": 5, "Thi": 40}, pad_value=np.nan)
+    got, want = _both(h, small["logits"], small["lengths"], small["leak"], scale=-1.0)
+    _same(got, want, small["lengths"])
+    h.close()
+
+
+def test_static_entry_point_numerator_batch_accumulate_and_limits():
+    import torch
+    # one graph per sequence (fp64 state vectors), then the denominator accumulated
+    # on top: Eq. 2 / Eq. 3 through the static entry point alone
+    wl = workloads.make_workload(5, scale={"S": 300, "B": 5, "nlo": 5, "nhi": 20}, pad_value=np.nan)
+    x = torch.from_numpy(wl["logits"]).cuda()
+    lens, leak = wl["lengths"], wl["leak"]
+    B, T, P = x.shape
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    den = binding.lfmmi_graph_create(wl["den"])
+    stream = torch.cuda.current_stream().cuda_stream
+    res = []
+    for entry in ("lfmmi_forward_backward_static", "lfmmi_forward_backward"):
+        objf = torch.empty(B, dtype=torch.float32, device="cuda")
+        grad = torch.empty((B, T, P), dtype=torch.float32, device="cuda")
+        status = torch.empty(B, dtype=torch.int32, device="cuda")
+        assert _raw(entry, num.handle, x, lens, leak, 1.0, 0, objf, grad, status, stream) == 0
+        assert _raw(entry, den.handle, x, lens, leak, -1.0, 1, objf, grad, status, stream) == 0
+        torch.cuda.synchronize()
+        res.append((objf.cpu().numpy(), grad.cpu().numpy(), status.cpu().numpy()))
+    assert np.all(res[0][2] == 0) and np.array_equal(res[0][2], res[1][2])
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+
+    # limits: a clear error, nothing enqueued, outputs untouched
+    unsupported = 5
+    objf = torch.full((B,), 7.0, dtype=torch.float32, device="cuda")
+    big_B = binding.STATIC_MAX_BATCH + 1
+    xb = torch.zeros((big_B, 2, P), dtype=torch.float32, device="cuda")
+    ob = torch.zeros(big_B, dtype=torch.float32, device="cuda")
+    gb = torch.zeros((big_B, 2, P), dtype=torch.float32, device="cuda")
+    sb = torch.zeros(big_B, dtype=torch.int32, device="cuda")
+    rc = _raw("lfmmi_forward_backward_static", den.handle, xb, np.full(big_B, 2, np.int32), leak,
+              1.0, 0, ob, gb, sb, stream)
+    assert rc == unsupported and "sequences" in binding.lfmmi_last_error()
+    # a workspace beyond the static array: 40 sequences of 2,000 frames on 320 + 320 rows
+    Tl = 2000
+    xl = torch.zeros((40, Tl, P), dtype=torch.float32, device="cuda")
+    ol = torch.full((40,), 7.0, dtype=torch.float32, device="cuda")
+    gl = torch.full((40, Tl, P), 7.0, dtype=torch.float32, device="cuda")
+    sl = torch.zeros(40, dtype=torch.int32, device="cuda")
+    rc = _raw("lfmmi_forward_backward_static", den.handle, xl, np.full(40, Tl, np.int32), leak,
+              1.0, 0, ol, gl, sl, stream)
+    assert rc == unsupported and "workspace" in binding.lfmmi_last_error()
+    torch.cuda.synchronize()
+    assert float(ol.min()) == 7.0 and float(gl.min()) == 7.0
+    # the same handle still works through both entry points afterwards
+    got, want = _both(den, wl["logits"], lens, leak)
+    _same(got, want, lens)
+    num.close(); den.close()
