@@ -20,20 +20,22 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 128 B/clk LDS x 2.4 GHz
+# MI355X: 256 CUs x 128 B/clk LDS x 2.4 GHz (4-byte reads; the datasheet formula)
 LDS_PEAK_GBPS = 256 * 128 * 2.4
+# ... and what `lfmmi_microbench lds` measures over the whole chip for conflict-free 4-byte
+# reads, at the 2.13 GHz the shader clock settles at under that load (profiles/lds_peak.txt)
+LDS_PEAK_MEASURED_GBPS = 68800.0
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes of the recursion kernel per step (all its launches), from rocprofv3 FETCH_SIZE /
-# WRITE_SIZE scaled by a plain copy of known size (profiles/hbm_traffic_wsj_mono_2k.txt); other
-# workloads: not measured
-REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6}
+# WRITE_SIZE scaled by a plain copy of known size (profiles/hbm_traffic_<workload>.txt)
+REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6, "biphone_10k": 4245.5e6, "long_unequal_5k": 1224.1e6}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 is the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -105,6 +107,17 @@ def main():
         print("bench.py: a sequence was flagged", file=sys.stderr)
         return 1
 
+    # Outside the timed region: single calls bracketed by HIP events on the stream
+    # the call is ordered on (torch's current stream), for the median and the spread
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(max(20, min(args.steps, 50)))]
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    call_ms = sorted(a.elapsed_time(b) for a, b in evs)
+
     # For reference, outside the timed region: the same work with the whole batch
     # as one bucket, i.e. one recursion launch over all 2B workgroups and nothing
     # overlapping it. The library reads LFMMI_BUCKETS at every call.
@@ -135,6 +148,12 @@ def main():
     rec_s = kern["rec"] * 1e-3
     achieved = rec_bytes / rec_s / 1e9
     info = binding.lfmmi_graph_info(den)
+    # the whole call against the same peak: the recursion's bytes of all launches of a
+    # step, and the bytes of the whole path (forward, backward and occupancy: 24 per
+    # arc and 28 per state and frame), over the time of a step
+    step_s = dt / args.steps
+    rec_step_gbps = frames * (16.0 * A + 24.0 * S) / step_s / 1e9
+    path_step_gbps = frames * (24.0 * A + 28.0 * S) / step_s / 1e9
     out = {
         "metric": "LF-MMI forward-backward frames/sec (loss+grad), 2k-state den graph, B=64",
         "value": fps,
@@ -153,6 +172,17 @@ def main():
                    "numerators": num is not None},
         "roofline": {"bound": "lds", "kernel": "k_rec", "achieved": achieved,
                      "peak": LDS_PEAK_GBPS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBPS,
+                     "peak_measured": LDS_PEAK_MEASURED_GBPS,
+                     "frac_of_measured_peak": achieved / LDS_PEAK_MEASURED_GBPS,
+                     # not per launch: all launches of a step over the time of a step
+                     "whole_call": {"recursion_bytes": {"achieved": rec_step_gbps,
+                                                        "frac": rec_step_gbps / LDS_PEAK_GBPS,
+                                                        "frac_of_measured_peak":
+                                                            rec_step_gbps / LDS_PEAK_MEASURED_GBPS},
+                                    "path_bytes": {"achieved": path_step_gbps,
+                                                   "frac": path_step_gbps / LDS_PEAK_GBPS,
+                                                   "frac_of_measured_peak":
+                                                       path_step_gbps / LDS_PEAK_MEASURED_GBPS}},
                      "traffic": (REC_TRAFFIC_BYTES[wl["name"]] / launches_per_call
                                  if wl["name"] in REC_TRAFFIC_BYTES else None),
                      "kernel_ms": kern["rec"], "launches_per_step": launches_per_call,
@@ -169,6 +199,9 @@ def main():
                                     "frac": frames * (16.0 * A + 24.0 * S) / (one["rec"] * 1e-3) / 1e9
                                             / LDS_PEAK_GBPS}},
         "kernels_ms": {k: kern[k] for k in ("emit", "rec", "scan", "occ")},
+        # single calls between HIP events, outside the timed region
+        "call_ms_hip_events": {"calls": len(call_ms), "median": call_ms[len(call_ms) // 2],
+                               "min": call_ms[0], "max": call_ms[-1]},
         "arc_updates_per_s": 2.0 * A * fps,
         "workspace_bytes": info["workspace_bytes"],
     }
