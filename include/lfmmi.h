@@ -201,8 +201,11 @@ enum { LFMMI_ORD_FWD = 0, LFMMI_ORD_BWD = 1, LFMMI_ORD_OCC = 2 };
 /* info[0] number of graphs, [1] num_pdfs, [2] total states, [3] total arcs,
  * [4] waves per workgroup of the recursion kernel, [5] waves of the occupancy
  * kernel, [6] flags (bit 0: uploaded; bit 1: state vectors kept in fp64, which
- * is chosen when some state has final_prob 0 or init_prob 0), [7] workspace
- * bytes held. */
+ * is chosen when some state has final_prob 0 or init_prob 0; bit 2: every arc
+ * carries the pdf-id of the state it enters - graphs expanded from HMMs whose
+ * states emit, Section 4.2 - and the recursion runs without an emission gather per
+ * arc: alpha multiplies a row by its emission once, beta folds the emission into
+ * the stored vector), [7] workspace bytes held. */
 lfmmi_status lfmmi_graph_info(const lfmmi_graph *graph, int64_t info[8]);
 
 /* Packed ordering `ord` of graph `g`: info[0] rows, [1] slices (64 rows each),

@@ -187,6 +187,7 @@ def lfmmi_graph_info(graph):
     out = dict(zip(keys, (int(v) for v in info)))
     out["uploaded"] = out["flags"] & 1
     out["fp64"] = (out["flags"] >> 1) & 1
+    out["emission_by_state"] = (out["flags"] >> 2) & 1
     return out
 
 

@@ -68,6 +68,8 @@ struct lfmmi_graph {
     int rec_hybrid = 0;  // 1, 2: rec_nslot slots of a wave in registers, its others streamed
                          // (2: LDS map for up to 12288 states)
     bool has_wb = false;  // arcs carry a per-arc leak factor (some init_prob is not uniform)
+    bool rec_grouped = false;  // every arc takes the pdf of the state it enters and the
+                               // recursion runs the variant without an emission gather
 
     // device copy
     bool uploaded = false;
@@ -265,7 +267,24 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             if (st == LFMMI_OK && h->rec_yrep &&
                 rec_lds_bytes(std::max(h->max_rows_f, h->max_rows_b), num_pdfs, h->wide, true) > kLdsBytes)
                 h->rec_yrep = false;
-            h->rec_nslot = st == LFMMI_OK && registers_possible(waves)
+            // Graphs whose arcs all take the pdf of the state they enter: the variant
+            // without an emission gather, when every wave's arcs fit its registers
+            // (two per slot), the workgroup's threads can stage an emission value per row
+            // in the passes that variant has, and the rows leave the last slice of the
+            // LDS map to the zero word.
+            auto grouped_slots = [&]() {
+                if (env_int("LFMMI_GROUPED", 1) == 0 || h->rec_hubs) return 0;
+                const int rows_most = std::max(h->max_rows_f, h->max_rows_b);
+                if (rows_most > (h->wide ? 4096 : 8192) - kLanes) return 0;
+                if (rows_most > rec_grouped_max_rows(waves * kLanes)) return 0;
+                for (int32_t g = 0; g < n; ++g)
+                    if (!h->packed[g].pdf_by_dst) return 0;
+                return rec_grouped_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
+            };
+            const int gslots = st == LFMMI_OK ? grouped_slots() : 0;
+            h->rec_grouped = gslots > 0;
+            h->rec_nslot = gslots > 0 ? gslots
+                           : st == LFMMI_OK && registers_possible(waves)
                                ? rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes)
                                : 0;
             if (st == LFMMI_OK && h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
@@ -387,6 +406,7 @@ lfmmi_status upload(lfmmi_graph* h)
     const size_t at_va = reserve<float>(&total, n_vec);
     const size_t at_vb = reserve<float>(&total, n_vec);
     const size_t at_vfin = reserve<float>(&total, n_vec);
+    const size_t at_rowpdfs = reserve<int32_t>(&total, n_vec);
     const size_t at_rowpdf = reserve<int32_t>(&total, n_rowpdf);
     const size_t at_pfirst = reserve<int32_t>(&total, n_pfirst);
     const size_t at_ords = reserve<OrdDesc>(&total, h->ords.size());
@@ -440,6 +460,9 @@ lfmmi_status upload(lfmmi_graph* h)
                 std::memcpy(host.data() + at_va + (size_t)d.vec_at * 4, pg.va[o].data(), nrow * 4);
                 std::memcpy(host.data() + at_vb + (size_t)d.vec_at * 4, pg.vb[o].data(), nrow * 4);
                 std::memcpy(host.data() + at_vfin + (size_t)d.vec_at * 4, pg.vfin[o].data(), nrow * 4);
+                if (pg.row_pdf[o].size() == nrow)
+                    std::memcpy(host.data() + at_rowpdfs + (size_t)d.vec_at * 4, pg.row_pdf[o].data(),
+                                nrow * 4);
             } else {
                 const PackedGraph& pg = h->packed[g];
                 std::memcpy(host.data() + at_rowpdf + (size_t)d.vec_at * 4, pg.row_slot.data(),
@@ -471,6 +494,7 @@ lfmmi_status upload(lfmmi_graph* h)
     h->dg.va = reinterpret_cast<const float*>(base + at_va);
     h->dg.vb = reinterpret_cast<const float*>(base + at_vb);
     h->dg.vfin = reinterpret_cast<const float*>(base + at_vfin);
+    h->dg.row_pdf = reinterpret_cast<const int32_t*>(base + at_rowpdfs);
     h->dg.row_slot = reinterpret_cast<const int32_t*>(base + at_rowpdf);
     h->dg.pdf_first = reinterpret_cast<const int32_t*>(base + at_pfirst);
     h->dg.ords = reinterpret_cast<const OrdDesc*>(base + at_ords);
@@ -581,6 +605,7 @@ void fill_params(const lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
     shape.rec_yrep = h->rec_yrep ? 1 : 0;
     shape.rec_hybrid = h->rec_hybrid;
     shape.rec_hubs = h->rec_hubs ? 1 : 0;
+    shape.rec_grouped = h->rec_grouped ? 1 : 0;
     shape.profile_rec_only = h->profile == 2 ? 1 : 0;
     shape.rec_has_wb = h->has_wb ? 1 : 0;
     shape.occ_threads = h->occ_waves * kLanes;
@@ -930,7 +955,7 @@ lfmmi_status lfmmi_graph_info(const lfmmi_graph* h, int64_t info[8])
     info[3] = h->total_arcs;
     info[4] = h->rec_waves;
     info[5] = h->occ_waves;
-    info[6] = (h->uploaded ? 1 : 0) | (h->wide ? 2 : 0);
+    info[6] = (h->uploaded ? 1 : 0) | (h->wide ? 2 : 0) | (h->rec_grouped ? 4 : 0);
     info[7] = (int64_t)h->ws_bytes;
     return LFMMI_OK;
 }

@@ -38,6 +38,8 @@ struct DeviceGraph {
     const float* va;
     const float* vb;
     const float* vfin;
+    const int32_t* row_pdf;     // FWD/BWD, graphs whose arcs take the pdf of the entered state:
+                                // that pdf per row (indexed like vinit), else zeros
     const int32_t* pdf_first;   // OCC: the sums of pdf d's rows are words pdf_first[d] ..
                                 // pdf_first[d + 1] - 1 of a frame's row sums
     const int32_t* row_slot;    // OCC: the word the sum of row (slice * 64 + lane) goes to
@@ -90,6 +92,7 @@ struct LaunchShape {
     int profile_rec_only;  // of the four events per bucket record only those around k_rec
     int rec_hybrid;    // 1: only the first slots of a wave are register-resident;
                        // 2: the same, with the LDS map for up to 12288 states
+    int rec_grouped = 0;  // arcs take the emission of the entered state: no emission gather
     int occ_threads;   // workgroup size of the occupancy kernel
     int occ_frames;    // frames per occupancy workgroup (frame-at-a-time kernel)
     int occ_multi;     // frames per record of the plane-layout occupancy kernel (0: not used)
@@ -138,6 +141,10 @@ int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
 // Slots of the hybrid variant (a wave's leading slices in registers, the others
 // streamed) for this kind of graph, 0 if there is none.
 int rec_hybrid_slots(bool wide, bool has_wb);
+// Slots of the variant for graphs whose arcs take the pdf of the entered state
+// (0: none for this shape), and the rows it stages emissions for with this many threads.
+int rec_grouped_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
+int rec_grouped_max_rows(int threads);
 size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide);
 int occ_plane_frames(int rows, int occ_rows);
 size_t occ_plane_lds_bytes(int rows, int occ_rows, int frames);

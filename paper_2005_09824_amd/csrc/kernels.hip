@@ -1026,6 +1026,374 @@ struct RecRegs {
 };
 
 // ---------------------------------------------------------------------------
+// The register-resident recursion for graphs whose arcs all take the emission of
+// the state they enter (PackedGraph::pdf_by_dst; graphs expanded from HMMs whose
+// states emit, Section 4.2): no emission gather per arc.
+//   alpha (rows = to-states): the emission is a function of the row,
+//       v_t[j] = e_t[pdf_j] * ((1/n) sum_a w_a v[from_a] + (eps s / n) sum_a w_a b[from_a]),
+//     one gather per arc and one multiply where a slice ends (normalisation is lazy
+//     as in RecRegs; the second sum does not depend on the frame).
+//   beta (rows = from-states): the emission is a function of the gathered state, so
+//     it is folded into the stored vector: after the barrier that ends a step every
+//     lane rewrites its own rows, u[j] = e[pdf_j] * (v[j] / n + eps s / n), a second
+//     barrier follows, then v_new[i] = sum_a w_a u[to_a], one gather per arc.
+// What is staged per step is the emission per row, EY[row] = e[pdf_row] (thread i
+// fetches the values of rows i, i + threads, ... two steps ahead and stores them
+// one step ahead), not a replicated emission row.
+// LDS map: X0 [0, 32K)  X1 [32K, 64K)  EY0 [64K, 96K)  EY1 [96K, 128K)  partial sums.
+// The last value of each X buffer is a zero nobody writes: closing slots gather it
+// (rows <= capacity - 64 is checked on the host).
+// ---------------------------------------------------------------------------
+constexpr int kGroupedPasses = 4;  // rows <= kGroupedPasses * threads in this variant
+
+template <typename Real, bool HAS_WB, int NSLOT, int NT>
+struct RecGrouped {
+    static constexpr uint32_t kRB = sizeof(Real);
+    static constexpr int kYPass = kGroupedPasses;
+    static constexpr int kChunk = 4;  // beta: slices whose rows are folded at a time
+    static constexpr int kPrefetch = NT >= 1024 ? 2 : 4;
+    static constexpr int kTailSlots = 4;
+    static constexpr int kStageAt = NSLOT - kTailSlots > 4 ? 4 : 0;
+    static constexpr uint32_t kZeroX = kRegX1 - kRB;  // byte offset of the zero inside an X buffer
+    static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
+
+    uint32_t xa[NSLOT];  // byte address of the gathered state value inside X0
+    float wr[NSLOT];     // arc weight; closing slots: the row's leak-dot weight
+    float wbr[HAS_WB ? NSLOT : 1];
+    float yreg[kYPass];     // emission values of rows tid + i * threads, two steps ahead
+    uint32_t ysrc[kYPass];  // byte offset of such a row's pdf inside an emission row
+    uint32_t ydst[kYPass];  // byte offset of the row inside an EY buffer
+    int ypasses;            // passes in which this wave holds any row (wave-uniform)
+    int nslices;            // slices this wave owns (wave-uniform)
+
+    const float* e2;
+    Real* trow;
+    Real* sN;
+    Real* sS;
+    ptrdiff_t estep, tstep, sstep;
+
+    __device__ __forceinline__ void load_y()
+    {
+        const char* base = reinterpret_cast<const char*>(e2);
+#pragma unroll
+        for (int i = 0; i < kYPass; ++i)
+            if (i < ypasses) yreg[i] = *reinterpret_cast<const float*>(base + ysrc[i]);
+    }
+
+    __device__ __forceinline__ void store_y(const uint32_t eybuf)
+    {
+#pragma unroll
+        for (int i = 0; i < kYPass; ++i)
+            if (i < ypasses) lds_st(eybuf + ydst[i], yreg[i]);
+    }
+
+    // DIR 0: alpha, 1: beta. PAR = k & 1 as in RecRegs.
+    template <int PAR, int DIR>
+    __device__ __forceinline__ void step(const int k, const int T, const int tid, const int lane,
+                                         const Real eps, const Real aconst, const Real bconst,
+                                         const uint64_t mask, const uint32_t row4_first,
+                                         const uint32_t ey_first, const uint32_t part_at,
+                                         const int nsl)
+    {
+        constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
+        constexpr uint32_t eyc = PAR ? kRegY0 : kRegY1, eyn = PAR ? kRegY1 : kRegY0;
+        constexpr uint32_t pc = kRegPart + (PAR ? 0u : 32u * kRB), pn = kRegPart + (PAR ? 32u * kRB : 0u);
+        constexpr int kp = kPrefetch;
+
+        Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
+        Real xv[kp];
+        Real own[DIR == 1 ? kChunk : 1];
+        float eown[DIR == 1 ? kChunk : 1];
+        float e_close = 0.f;  // alpha: emission of the row whose slice ends next
+        if constexpr (DIR == 0) {
+#pragma unroll
+            for (int i = 0; i < kp && i < NSLOT; ++i) xv[i] = lds_ldr<Real>(xc + xa[i]);
+            e_close = lds_ld(eyc + ey_first);
+        } else {
+            // this lane's own rows of the vector the last step wrote, and their
+            // emissions: the first kChunk slices now, with the partial sums
+#pragma unroll
+            for (int q = 0; q < kChunk; ++q)
+                if (q < nslices) {
+                    own[q] = lds_ldr<Real>(xc + row4_first + (uint32_t)q * 64u * kRB);
+                    eown[q] = lds_ld(eyc + ey_first + (uint32_t)q * 256u);
+                }
+        }
+        asm volatile("" ::: "memory");
+        pv = row16_allsum(pv);
+        const Real N = lane_value(pv, 0);
+        const Real Sd = HAS_WB ? lane_value(pv, 16) : aconst * N;
+        Real inv = 0;
+        if (N > 0) {
+            if constexpr (sizeof(Real) == 4) {
+                inv = __builtin_amdgcn_rcpf(N);
+                inv = fmaf(fmaf(-N, inv, 1.f), inv, inv);
+            } else {
+                inv = __builtin_amdgcn_rcp((double)N);
+                inv = fma(fma(-N, inv, (Real)1), inv, inv);
+                inv = fma(fma(-N, inv, (Real)1), inv, inv);
+            }
+        }
+        const Real c = eps * Sd * inv;
+        const Real cb = HAS_WB ? c : c * bconst;
+        if constexpr (DIR == 1) {
+            // fold normalisation, leak and emission into the stored vector, in place
+#pragma unroll
+            for (int q = 0; q < kChunk; ++q)
+                if (q < nslices)
+                    lds_st(xc + row4_first + (uint32_t)q * 64u * kRB,
+                           (Real)eown[q] * (own[q] * inv + cb));
+            for (int q0 = kChunk; q0 < nslices; q0 += kChunk) {  // a wave with many slices
+#pragma unroll
+                for (int q = 0; q < kChunk; ++q)
+                    if (q0 + q < nslices) {
+                        own[q] = lds_ldr<Real>(xc + row4_first + (uint32_t)(q0 + q) * 64u * kRB);
+                        eown[q] = lds_ld(eyc + ey_first + (uint32_t)(q0 + q) * 256u);
+                    }
+#pragma unroll
+                for (int q = 0; q < kChunk; ++q)
+                    if (q0 + q < nslices)
+                        lds_st(xc + row4_first + (uint32_t)(q0 + q) * 64u * kRB,
+                               (Real)eown[q] * (own[q] * inv + cb));
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kp && i < NSLOT; ++i) xv[i] = lds_ldr<Real>(xc + xa[i]);
+            asm volatile("" ::: "memory");
+        }
+
+        Real acc1 = 0, acc2 = 0, n = 0, s = 0;
+        uint64_t left = mask;
+        int next_close = left ? __builtin_ctzll(left) : 64;
+        uint32_t row4 = row4_first;  // byte offset of this lane's row in a state vector
+        uint32_t ey4 = ey_first;     // ... and in an EY buffer
+        char* const tr = reinterpret_cast<char*>(trow);
+#pragma unroll
+        for (int i = 0; i < NSLOT; i += 2) {
+            if (i > 0 && i >= NSLOT - kTailSlots) {
+                int count = nsl;
+                asm volatile("" : "+s"(count));
+                if (i >= count) break;
+            }
+            if (i == 0) __builtin_amdgcn_s_setprio(2);
+            else if (i == (NSLOT / 6) * 2) __builtin_amdgcn_s_setprio(1);
+            else if (i == (NSLOT / 3) * 2) __builtin_amdgcn_s_setprio(0);
+            if (i == kStageAt) {
+                // emission values of step k + 1 (loaded a step ago) into the other EY
+                // buffer, the loads for step k + 2, and the scalars of step k - 1
+                store_y(eyn);
+                load_y();
+                if (tid == 0) {
+                    *sN = N;
+                    *sS = Sd;
+                }
+            }
+            Real x0 = xv[i % kp], x1 = xv[(i + 1) % kp];
+            if (i + kp < NSLOT) {
+                xv[i % kp] = lds_ldr<Real>(xc + xa[(i + kp) % NSLOT]);
+                xv[(i + 1) % kp] = lds_ldr<Real>(xc + xa[(i + 1 + kp) % NSLOT]);
+            }
+            asm volatile("" : "+v"(x0) : "v"(x1));  // one wait for the pair
+            if constexpr (sizeof(Real) == 4) {
+                acc1 = fmaf(wr[i], x0, acc1);
+                acc1 = fmaf(wr[i + 1], x1, acc1);
+            } else {
+                acc1 += (Real)wr[i] * x0;
+                acc1 += (Real)wr[i + 1] * x1;
+            }
+            if constexpr (DIR == 0)  // the leak's share of the row: frame-independent
+                acc2 += HAS_WB ? (Real)(wbr[HAS_WB ? i : 0] + wbr[HAS_WB ? i + 1 : 0])
+                               : (Real)(wr[i] + wr[i + 1]);
+            if (__builtin_expect(i + 1 == next_close, 0)) {  // wave-uniform: a slice ends
+                Real v;
+                if constexpr (DIR == 0) v = (Real)e_close * (inv * acc1 + cb * acc2);
+                else v = acc1;
+                lds_st(xn + row4, v);
+                *reinterpret_cast<Real*>(tr + row4) = v;
+                n += v;
+                if (HAS_WB) s += (Real)wr[i + 1] * v;  // the closing slot's w is a[row]
+                acc1 = 0;
+                acc2 = 0;
+                row4 += 64 * kRB;
+                ey4 += 256u;
+                left &= left - 1;
+                next_close = left ? __builtin_ctzll(left) : 64;
+                // (past the wave's last slice this reads a word nobody uses)
+                if constexpr (DIR == 0) e_close = lds_ld(eyc + ey4);
+            }
+        }
+        __builtin_amdgcn_s_setprio(3);
+        if constexpr (HAS_WB) {
+            const Real ns = half_wave_sums(n, s);
+            if ((lane & 31) == 31) lds_st(pn + part_at, ns);
+        } else {
+            const Real ns = wave_sum_lane63(n);
+            if (lane == 63) lds_st(pn + part_at, ns);
+        }
+        if (k + 2 < T) e2 += estep;
+        trow += tstep;
+        sN += sstep;
+        sS += sstep;
+        __syncthreads();
+    }
+
+    template <int DIR>
+    __device__ __forceinline__ void loop(const int T, const int tid, const int lane, const Real eps,
+                                         const Real aconst, const Real bconst, const uint64_t mask,
+                                         const uint32_t row4_first, const uint32_t ey_first,
+                                         const uint32_t part_at, const int nsl)
+    {
+        int k = 1;
+        for (; k + 1 <= T; k += 2) {
+            step<1, DIR>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, ey_first, part_at, nsl);
+            step<0, DIR>(k + 1, T, tid, lane, eps, aconst, bconst, mask, row4_first, ey_first, part_at, nsl);
+        }
+        if (k <= T)
+            step<1, DIR>(k, T, tid, lane, eps, aconst, bconst, mask, row4_first, ey_first, part_at, nsl);
+    }
+
+    __device__ __forceinline__ void run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
+                                        const int b, const int dir)
+    {
+        const int tid = threadIdx.x;
+        const int lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int nthreads = blockDim.x;
+        const int T = sd.T;
+        const int P = p.P;
+        const int rows = od.num_slices * 64;
+        Real* trel = static_cast<Real*>(dir == 0 ? p.alpha : p.beta) +
+                     (dir == 0 ? sd.alpha_at : sd.beta_at);
+        Real* scalN = static_cast<Real*>(p.scal) + (size_t)(dir * 2) * p.scal_total + sd.scal_at;
+        Real* scalS = scalN + p.scal_total;
+        const uint2* rec1 = reinterpret_cast<const uint2*>(rec_pairs(p, od, lane));
+        const float* wb1 = reinterpret_cast<const float*>(wb_pairs(p, od, lane));
+        const int32_t* so = p.g.slice_off + od.slice_off_at;
+        const Real eps = (Real)p.leak;
+        const Real aconst = (Real)od.a_const;
+        const Real bconst = (Real)od.b_const;
+        const float* erows = p.emis + (size_t)b * p.T * P;
+
+        int s0 = 0, s1 = 0;
+        uint64_t mask = 0;
+        if (wave < od.num_waves) {
+            s0 = p.g.wave_first[od.wave_first_at + wave];
+            s1 = p.g.wave_first[od.wave_first_at + wave + 1];
+            mask = p.g.wave_mask[od.mask_at + wave];
+        }
+        const int first = so[s0];
+        const int nsl = so[s1] - first;
+        nslices = s1 - s0;
+#pragma unroll
+        for (int i = 0; i < NSLOT; ++i) {
+            const bool on = i < nsl;
+            const bool closing = HAS_WB && ((mask >> i) & 1);  // holds a[row], no arc
+            const size_t at = (size_t)((first + i) >> 1) * 128 + ((first + i) & 1);
+            const uint2 r = on ? rec1[at] : make_uint2(0u, 0u);
+            xa[i] = (on && !closing) ? (r.x & 0xffffu) * (kRB / 4u) : kZeroX;
+            wr[i] = __uint_as_float(r.y);
+            if (HAS_WB) wbr[i] = (on && !closing) ? wb1[at] : 0.f;
+            asm volatile("" : "+v"(xa[i]), "+v"(wr[i]));
+        }
+        // emission staging: row tid + i * threads in pass i (rows <= kYPass * threads is
+        // checked on the host; a wave whose threads all lie past the rows skips the pass)
+        ypasses = min(kYPass, max(0, (rows - wave * 64 + nthreads - 1) / nthreads));
+#pragma unroll
+        for (int i = 0; i < kYPass; ++i) {
+            const int row = min(tid + i * nthreads, rows - 1);
+            ysrc[i] = (uint32_t)p.g.row_pdf[od.vec_at + row] * 4u;
+            ydst[i] = (uint32_t)row * 4u;
+            yreg[i] = 0.f;
+        }
+        if (tid == 0) {
+            lds_st(kZeroX, (Real)0);
+            lds_st(kRegX1 + kZeroX, (Real)0);
+        }
+        if (tid < 64) lds_st(kRegPart + tid * kRB, (Real)0);
+        __syncthreads();
+
+        const uint32_t row4_first = (uint32_t)(s0 * 64 + lane) * kRB;
+        const uint32_t ey_first = (uint32_t)(s0 * 64 + lane) * 4u;
+        // ---- step 0: v_0 = init into X0, partials into slot set 0
+        {
+            Real n = 0, s = 0;
+            const int ti = dir == 0 ? 0 : T;
+            for (int sl = s0; sl < s1; ++sl) {
+                const int row = sl * 64 + lane;
+                const Real v = (Real)p.g.vinit[od.vec_at + row];
+                lds_st(row * kRB, v);
+                trel[(size_t)ti * rows + row] = v;
+                n += v;
+                s += (Real)p.g.va[od.vec_at + row] * v;
+            }
+            n = wave_sum_uniform(n);
+            s = wave_sum_uniform(s);
+            if (lane == 0) {
+                lds_st(kRegPart + wave * kRB, n);
+                lds_st(kRegPart + (16 + wave) * kRB, s);
+            }
+            auto frame_of = [&](int k) {  // FWD k - 1, BWD T - k, kept inside the sequence
+                const int fr = dir == 0 ? k - 1 : T - k;
+                return max(0, min(fr, T - 1));
+            };
+            if (T > 0) {
+                e2 = erows + (size_t)frame_of(1) * P;
+                load_y();
+                store_y(kRegY0);
+                e2 = erows + (size_t)frame_of(2) * P;
+                load_y();
+                e2 = erows + (size_t)frame_of(3) * P;
+            }
+            __syncthreads();
+        }
+        estep = dir == 0 ? (ptrdiff_t)P : -(ptrdiff_t)P;
+        tstep = dir == 0 ? (ptrdiff_t)rows : -(ptrdiff_t)rows;
+        sstep = dir == 0 ? 1 : -1;
+        trow = trel + (size_t)(dir == 0 ? 1 : T - 1) * rows;
+        sN = scalN + (dir == 0 ? 0 : T);
+        sS = scalS + (dir == 0 ? 0 : T);
+        const uint32_t part_at = ((uint32_t)wave + (HAS_WB && lane >= 32 ? 16u : 0u)) * kRB;
+        if (dir == 0) loop<0>(T, tid, lane, eps, aconst, bconst, mask, row4_first, ey_first, part_at, nsl);
+        else loop<1>(T, tid, lane, eps, aconst, bconst, mask, row4_first, ey_first, part_at, nsl);
+
+        // ---- last scalars and the closing dot product (the vector of step T is raw:
+        // beta's in-place folding happens at the start of a step that does not come)
+        {
+            const uint32_t xc = (T & 1) ? kRegX1 : 0u;
+            const uint32_t pc = kRegPart + ((T & 1) ? 32u * kRB : 0u);
+            Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
+            pv = row16_allsum(pv);
+            const Real N = lane_value(pv, 0);
+            const Real Sd = HAS_WB ? lane_value(pv, 16) : aconst * N;
+            const Real inv = N > 0 ? (Real)1 / N : (Real)0;
+            const Real c = eps * Sd * inv;
+            if (tid == 0) {
+                const int tp = dir == 0 ? T : 0;
+                scalN[tp] = N;
+                scalS[tp] = Sd;
+            }
+            Real z = 0;
+            for (int sl = s0; sl < s1; ++sl) {
+                const int row = sl * 64 + lane;
+                const Real v = lds_ldr<Real>(xc + row * kRB) * inv +
+                               c * (Real)p.g.vb[od.vec_at + row];
+                z += (Real)p.g.vfin[od.vec_at + row] * v;
+            }
+            z = wave_sum_uniform(z);
+            __syncthreads();
+            if (lane == 0) lds_st(kRegPart + (64 + wave) * kRB, z);
+            __syncthreads();
+            if (tid == 0) {
+                Real Z = 0;
+                for (int w = 0; w < (nthreads >> 6); ++w)
+                    Z += lds_ldr<Real>(kRegPart + (64 + w) * kRB);
+                static_cast<Real*>(p.zfin)[(size_t)dir * p.B + b] = Z;
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
 // Scales of one sequence, once both of its recursions are done:
 //   log Z_b = log(zfin) + sum_t log n_t (+ the frame maxima), and the factor that
 //   turns ahat_{t-1} * w * e_t * bhat_t into an occupancy,
@@ -1104,7 +1472,7 @@ __device__ void scan_sequence(const FbParams& p, const int b, unsigned char* scr
 }
 
 template <typename Real, int NSLOT, bool YREP, bool HAS_WB, int NT, bool HYBRID = false,
-          bool BIG = false, bool HUBS = false>
+          bool BIG = false, bool HUBS = false, bool GROUPED = false>
 __global__ void __launch_bounds__(NT) k_rec(FbParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -1112,7 +1480,11 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     const int b = code >> 1, dir = code & 1;
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
-    if constexpr (NSLOT > 0) {
+    if constexpr (GROUPED) {
+        static_assert(NSLOT > 0 && !YREP && !HYBRID && !BIG && !HUBS, "grouped: resident arcs only");
+        RecGrouped<Real, HAS_WB, NSLOT, NT> r;
+        r.run(p, sd, od, b, dir);
+    } else if constexpr (NSLOT > 0) {
         RecRegs<Real, YREP, HAS_WB, NSLOT, NT, HYBRID, BIG, HUBS> r;
         r.run(p, sd, od, b, dir, lds_raw);
     } else {
@@ -1586,7 +1958,11 @@ struct RecVariant {
     RecKernel fn;
     int hybrid = 0;  // 1: hybrid, 2: hybrid with the large LDS map
     int hubs = 0;    // handles hub slices
+    int grouped = 0; // emission by entered state: no emission gather (RecGrouped)
 };
+#define LFMMI_REC_GROUPED(REAL, WIDE, NSLOT, WB, NT)                                             \
+    {WIDE, NSLOT, 0, WB, NT, k_rec<REAL, NSLOT, false, (WB != 0), NT, false, false, false, true>, \
+     0, 0, 1}
 
 #define LFMMI_REC(REAL, WIDE, NSLOT, WB, NT)                                                    \
     {WIDE, NSLOT, 0, WB, NT, k_rec<REAL, NSLOT, false, (WB != 0), NT>},                         \
@@ -1620,14 +1996,23 @@ const RecVariant kRecVariants[] = {
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, false, true>, 1, 1},
     {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true, false, true>, 1, 1},
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, true, true>, 2, 1},
+    // emission by entered state (two registers per slot: more slots fit)
+    LFMMI_REC_GROUPED(float, 0, 16, 0, 1024), LFMMI_REC_GROUPED(float, 0, 24, 0, 1024),
+    LFMMI_REC_GROUPED(float, 0, 32, 0, 1024), LFMMI_REC_GROUPED(float, 0, 48, 0, 512),
+    LFMMI_REC_GROUPED(float, 0, 16, 1, 1024), LFMMI_REC_GROUPED(float, 0, 24, 1, 1024),
+    LFMMI_REC_GROUPED(double, 1, 8, 1, 1024), LFMMI_REC_GROUPED(double, 1, 16, 1, 512),
+    LFMMI_REC_GROUPED(double, 1, 16, 0, 1024),
 };
 #undef LFMMI_REC
+#undef LFMMI_REC_GROUPED
 
-const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, int hybrid, bool hubs)
+const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, int hybrid, bool hubs,
+                           bool grouped)
 {
     for (const RecVariant& v : kRecVariants)
-        if (v.wide == (wide ? 1 : 0) && v.nslot == nslot && v.yrep == (yrep ? 1 : 0) &&
-            v.has_wb == (has_wb ? 1 : 0) && v.hybrid == hybrid && v.hubs == (hubs ? 1 : 0))
+        if (v.wide == (wide ? 1 : 0) && v.nslot == nslot && v.has_wb == (has_wb ? 1 : 0) &&
+            v.grouped == (grouped ? 1 : 0) &&
+            (grouped || (v.yrep == (yrep ? 1 : 0) && v.hybrid == hybrid && v.hubs == (hubs ? 1 : 0))))
             return &v;
     return nullptr;
 }
@@ -1639,10 +2024,23 @@ int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
     int best = 0;
     for (const RecVariant& v : kRecVariants)
         if (v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) && v.nslot > 0 && !v.hybrid &&
+            !v.grouped &&
             v.nslot >= max_wave_slots && threads <= v.max_threads && (best == 0 || v.nslot < best))
             best = v.nslot;
     return best;
 }
+
+int rec_grouped_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
+{
+    int best = 0;
+    for (const RecVariant& v : kRecVariants)
+        if (v.grouped && v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) &&
+            v.nslot >= max_wave_slots && threads <= v.max_threads && (best == 0 || v.nslot < best))
+            best = v.nslot;
+    return best;
+}
+
+int rec_grouped_max_rows(int threads) { return kGroupedPasses * threads; }
 
 int rec_hybrid_slots(bool wide, bool has_wb)
 {
@@ -1725,12 +2123,12 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
     const bool wide = sizeof(Real) == 8;
     const RecVariant* rv =
         find_rec(wide, shape.rec_nslot, shape.rec_yrep != 0, shape.rec_has_wb != 0,
-                 shape.rec_hybrid, shape.rec_hubs != 0);
+                 shape.rec_hybrid, shape.rec_hubs != 0, shape.rec_grouped != 0);
     if (!rv || shape.rec_threads > rv->max_threads) return hipErrorInvalidConfiguration;
     if (bk.n > 1 && (e = hipEventRecord(bk.fork, stream)) != hipSuccess) return e;
 
     int rec_threads = shape.rec_threads;
-    if (shape.rec_nslot > 0) {
+    if (shape.rec_nslot > 0 && !shape.rec_grouped) {
         // enough threads to stage one emission row in the variant's passes; waves
         // beyond the graph's own hold no arcs
         const int units = shape.rec_yrep ? p.P * 8 : p.P;

@@ -845,6 +845,24 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
                 }
         fill_wave_mask(&o);
     }
+    // ---- is the pdf-id of an arc a function of the state it enters?
+    {
+        std::vector<int32_t> pdf_of(S, -1);
+        bool by_dst = true;
+        for (int64_t a = 0; a < A && by_dst; ++a) {
+            int32_t& q = pdf_of[g.dst[a]];
+            if (q < 0) q = g.pdf[a];
+            else by_dst = q == g.pdf[a];
+        }
+        out->pdf_by_dst = by_dst;
+        for (int d = 0; d < 2; ++d) {
+            out->row_pdf[d].clear();
+            if (!by_dst) continue;
+            const Arrangement& ar = d == 0 ? af : ab;
+            out->row_pdf[d].assign((size_t)ar.num_slices * kLanes, 0);
+            for (int32_t s = 0; s < S; ++s) out->row_pdf[d][ar.pos[s]] = std::max(pdf_of[s], 0);
+        }
+    }
     // leak target: BWD adds the same amount to every state; FWD adds pi, which
     // is one constant when pi is uniform. Otherwise (or when another graph of
     // the same handle needs it) every arc carries the factor w * b[from]

@@ -63,6 +63,13 @@ struct PackedGraph {
     //   init: start vector (FWD pi, BWD final)      fin: closing dot (FWD final, BWD pi)
     //   a:    leak dot weights (FWD 1, BWD pi)      b:   leak target (FWD pi, BWD 1)
     std::vector<float> vinit[2], va[2], vb[2], vfin[2];
+    // Emission by entered state: true when all arcs into a state carry one pdf-id
+    // (graphs expanded from HMMs whose states emit, Section 4.2: the emission of an
+    // arc is then a function of its to-state). row_pdf[d][row]: that pdf-id for the
+    // state that owns the row in direction d's numbering (0 on padding rows and for
+    // states nothing enters); filled only when the flag is set.
+    bool pdf_by_dst = false;
+    std::vector<int32_t> row_pdf[2];
     // OCC: a frame's row sums are stored sorted by pdf: the sum of row position
     // slice * 64 + lane is word row_slot[position]; pdf d owns words pdf_first[d] ..
     // pdf_first[d + 1] - 1, added up in that order (padding rows: the words after)

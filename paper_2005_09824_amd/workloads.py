@@ -31,6 +31,7 @@ CONFIG_NAMES = {
     3: "biphone_10k",
     4: "long_unequal_5k",
     5: "e2e_num_den",
+    6: "hmm_den_2k",   # not one of the five named workloads: see make_workload
 }
 
 
@@ -147,6 +148,55 @@ def phone_string_num_graph(phones, num_pdfs, sil_prob=0.2):
     }
 
 
+def hmm_den_graph(rng, num_phones=42, successors=24, dirichlet=0.5):
+    """Denominator-like graph expanded from two-state phone HMMs whose states emit
+    (the topology of Section 4.2 without its skip): one pair of states (a, b) per
+    allowed phone pair (previous phone h, phone k); arcs a->a, a->b, b->b, and from
+    b of (h, k) to a of (k, k') for every allowed successor k' of k. Every arc
+    carries the pdf-id of the state it enters (a-state of phone k: 2k, b-state:
+    2k + 1), so the pdf-id is a function of the to-state. Each phone has
+    `successors` allowed successors drawn without replacement; the out-weights of
+    a state are one Dirichlet(dirichlet) draw floored at 1e-30. Uniform initial
+    probability, every state final."""
+    K, m = int(num_phones), int(successors)
+    succ = [np.sort(rng.choice(K, size=m, replace=False)) for _ in range(K)]
+    pair_id = {}
+    for h in range(K):
+        for k in succ[h]:
+            pair_id[(h, int(k))] = len(pair_id)
+    S = 2 * len(pair_id)
+    src, dst, pdf = [], [], []
+    for (h, k), i in pair_id.items():
+        a, b = 2 * i, 2 * i + 1
+        src += [a, a, b]
+        dst += [a, b, b]
+        pdf += [2 * k, 2 * k + 1, 2 * k + 1]
+        for k2 in succ[k]:
+            src.append(b)
+            dst.append(2 * pair_id[(k, int(k2))])
+            pdf.append(2 * int(k2))
+    src = np.asarray(src, dtype=np.int32)
+    dst = np.asarray(dst, dtype=np.int32)
+    w = np.empty(len(src), dtype=np.float64)
+    order = np.argsort(src, kind="stable")
+    counts = np.bincount(src, minlength=S)
+    at = 0
+    for s_ in range(S):
+        n = int(counts[s_])
+        w[order[at:at + n]] = np.maximum(rng.dirichlet(np.full(n, float(dirichlet))), 1e-30)
+        at += n
+    return {
+        "num_states": S,
+        "num_pdfs": 2 * K,
+        "src": src,
+        "dst": dst,
+        "pdf": np.asarray(pdf, dtype=np.int32),
+        "logw": np.log(w).astype(np.float32),
+        "init_prob": np.full(S, 1.0 / S, dtype=np.float32),
+        "final_prob": np.ones(S, dtype=np.float32),
+    }
+
+
 def random_logits(rng, lengths, num_pdfs, sigma, pad_value=None):
     """float32 N(0, sigma) logits [B, max(lengths), P]. If pad_value is given
     the rows at and after each sequence's length are overwritten with it (the
@@ -178,7 +228,7 @@ def spike_frames(rng, logits, lengths, fraction=0.01, magnitude=30.0):
 
 
 def make_workload(config, seed=None, scale=None, pad_value=None):
-    """Build config 1..5.
+    """Build config 1..5 (the named workloads) or 6 (see below).
 
     `scale` (dict) overrides sizes for reduced parity cases that keep the
     structure of the named config: keys S, k, P, B, Tlo, Thi, nlo, nhi.
@@ -230,8 +280,18 @@ def make_workload(config, seed=None, scale=None, pad_value=None):
             phones = rng.integers(1, 42, size=int(n))
             num.append(phone_string_num_graph(phones, P, 0.2))
         logits = random_logits(rng, lengths, P, 2.0, pad_value)
+    elif config == 6:
+        # Beyond the five named workloads: the shape of config 2 (about 2,000 states,
+        # 84 pdfs, B = 64, T in [100, 500] sorted, N(0, 2) logits) on a graph expanded
+        # from phone HMMs, where every arc carries the pdf-id of the state it enters.
+        den = hmm_den_graph(rng, sc.get("phones", 42), sc.get("succ", 24), 0.5)
+        P = den["num_pdfs"]
+        B = sc.get("B", 64)
+        lengths = rng.integers(sc.get("Tlo", 100), sc.get("Thi", 500) + 1, size=B)
+        lengths = np.sort(lengths)[::-1].astype(np.int32)
+        logits = random_logits(rng, lengths, P, 2.0, pad_value)
     else:
-        raise ValueError("config must be 1..5")
+        raise ValueError("config must be 1..6")
     return {
         "name": name,
         "config": config,

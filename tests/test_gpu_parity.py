@@ -656,3 +656,72 @@ def test_forced_fp32_on_numerator_graphs_matches_or_is_flagged(monkeypatch):
     assert binding.lfmmi_graph_info(h)["fp64"] == 1
     check(*run_gpu(h, x, lens, leak), lz, gamma, "numerators, fp64")
     h.close()
+
+
+# ---- graphs whose arcs carry the pdf-id of the state they enter: the recursion
+# variant without an emission gather (alpha multiplies a row by its emission once,
+# beta folds the emission into the stored vector)
+def _emission_by_state(handle):
+    return binding.lfmmi_graph_info(handle)["emission_by_state"]
+
+
+@pytest.mark.parametrize("kind", ["uniform_pi", "nonuniform_pi", "small", "leaks"])
+def test_hmm_expanded_graph_every_element(kind, monkeypatch):
+    scale = {"B": 5, "Tlo": 20, "Thi": 70}
+    if kind == "small":
+        scale.update(phones=9, succ=4)        # 72 states: two slices, ragged
+    if kind == "nonuniform_pi":
+        scale.update(succ=12)                 # 1,008 states: three registers per slot fit
+    wl = workloads.make_workload(6, scale=scale, pad_value=np.nan)
+    g = wl["den"]
+    if kind == "nonuniform_pi":               # per-arc leak factors and closing slots
+        rng = np.random.default_rng(3)
+        pi = rng.uniform(0.05, 1.0, g["num_states"])
+        g["init_prob"] = (pi / pi.sum()).astype(np.float32)
+        g["final_prob"] = rng.uniform(0.2, 1.0, g["num_states"]).astype(np.float32)
+    h = binding.lfmmi_graph_create(g)
+    assert _emission_by_state(h) == 1 and binding.lfmmi_graph_info(h)["fp64"] == 0
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    assert info["register_slots"] >= info["max_wave_slots"]
+    leaks = (0.0, 1e-5, 0.3) if kind == "leaks" else (wl["leak"],)
+    for leak in leaks:
+        lz, gamma = oracle.forward_backward(g, wl["logits"], wl["lengths"], leak)
+        out = run_gpu(h, wl["logits"], wl["lengths"], leak)
+        check(*out, lz, gamma, "hmm graph, %s, leak %g" % (kind, leak))
+        for b, Tb in enumerate(wl["lengths"]):
+            assert np.all(out[1][b, Tb:] == 0.0)
+    h.close()
+    # the same graph through the kernels that gather the emission per arc
+    monkeypatch.setenv("LFMMI_GROUPED", "0")
+    h0 = binding.lfmmi_graph_create(g)
+    monkeypatch.delenv("LFMMI_GROUPED")
+    assert _emission_by_state(h0) == 0
+    lz, gamma = oracle.forward_backward(g, wl["logits"], wl["lengths"], wl["leak"])
+    check(*run_gpu(h0, wl["logits"], wl["lengths"], wl["leak"]), lz, gamma, "hmm graph, per-arc gather")
+    h0.close()
+
+
+def test_hmm_expanded_graph_full_size_all_sequences():
+    wl = workloads.make_workload(6)
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    den = binding.lfmmi_graph_create(wl["den"])
+    assert _emission_by_state(den) == 1
+    objf, grad, status = run_gpu(den, x, lens, leak)
+    lz, gamma = oracle.forward_backward(wl["den"], x, lens, leak)
+    rel, err = check(objf, grad, status, lz, gamma, "hmm_den_2k")
+    print("hmm_den_2k full size: objf max rel err %.2e, grad max abs err %.2e" % (rel, err))
+    den.close()
+
+
+def test_numerator_graphs_take_the_emission_by_state_variant_in_fp64():
+    # the phone-string numerators carry the pdf-id of the entered state; a unique start
+    # state makes them fp64 with per-arc leak factors
+    wl = workloads.make_workload(5, scale={"S": 300, "B": 9, "nlo": 5, "nhi": 110})
+    x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    info = binding.lfmmi_graph_info(num)
+    assert info["fp64"] == 1 and info["emission_by_state"] == 1
+    for lk in (leak, 0.0, 0.05):
+        lz, gamma = oracle.forward_backward_per_utt(wl["num"], x, lens, lk)
+        check(*run_gpu(num, x, lens, lk), lz, gamma, "numerators, emission by state, leak %g" % lk)
+    num.close()

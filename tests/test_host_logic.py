@@ -330,3 +330,37 @@ def test_hub_slices_are_given_up_when_their_padding_rows_overflow_the_key_fields
     # OCC keys: both fields are row numbers
     assert int((od[2]["key"] >> 16).max()) // 4 < od[1]["slices"] * 64
     h.close()
+
+
+def test_packer_finds_graphs_whose_pdf_is_a_function_of_the_entered_state():
+    wl6 = workloads.make_workload(6, scale={"B": 2, "Tlo": 3, "Thi": 4})
+    g = wl6["den"]
+    pdf_of = {}
+    for d, p in zip(g["dst"].tolist(), g["pdf"].tolist()):
+        assert pdf_of.setdefault(d, p) == p       # the generator's own promise
+    h = binding.lfmmi_graph_pack(g)
+    assert binding.lfmmi_graph_info(h)["emission_by_state"] == 1
+    h.close()
+    g2 = dict(g)
+    pdf = g["pdf"].copy()
+    pdf[5] = (pdf[5] + 1) % g["num_pdfs"]         # one arc breaks it
+    g2["pdf"] = pdf
+    h = binding.lfmmi_graph_pack(g2)
+    assert binding.lfmmi_graph_info(h)["emission_by_state"] == 0
+    h.close()
+    # random pdf-ids per arc (the five named workloads' denominators): never
+    h = binding.lfmmi_graph_pack(workloads.make_workload(2, scale={"S": 200, "B": 2})["den"])
+    assert binding.lfmmi_graph_info(h)["emission_by_state"] == 0
+    h.close()
+    # phone-string numerators: yes; a batch with one graph that is not: no
+    wl5 = workloads.make_workload(5, scale={"S": 100, "B": 3, "nlo": 3, "nhi": 6})
+    h = binding.lfmmi_graph_pack_batch(wl5["num"])
+    assert binding.lfmmi_graph_info(h)["emission_by_state"] == 1
+    h.close()
+    mixed = list(wl5["num"])
+    bad = dict(mixed[1])
+    bad["pdf"] = (mixed[1]["pdf"] + np.arange(len(mixed[1]["pdf"]))) % 84
+    mixed[1] = bad
+    h = binding.lfmmi_graph_pack_batch(mixed)
+    assert binding.lfmmi_graph_info(h)["emission_by_state"] == 0
+    h.close()
