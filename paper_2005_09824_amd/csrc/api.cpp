@@ -272,8 +272,14 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             // (two per slot), the workgroup's threads can stage an emission value per row
             // in the passes that variant has, and the rows leave the last slice of the
             // LDS map to the zero word.
+            // It pays from about a dozen slots per wave on: what it saves grows with the
+            // arcs, what beta's second barrier costs does not (the 128 numerator graphs
+            // of the e2e workload, 4 slots per wave: 366 us with it, 314 us without).
+            // LFMMI_GROUPED=0 never takes it, 2 takes it whenever it applies.
             auto grouped_slots = [&]() {
-                if (env_int("LFMMI_GROUPED", 1) == 0 || h->rec_hubs) return 0;
+                const int want = env_int("LFMMI_GROUPED", 1);
+                if (want == 0 || h->rec_hubs) return 0;
+                if (want != 2 && max_slots < 16) return 0;
                 const int rows_most = std::max(h->max_rows_f, h->max_rows_b);
                 if (rows_most > (h->wide ? 4096 : 8192) - kLanes) return 0;
                 if (rows_most > rec_grouped_max_rows(waves * kLanes)) return 0;

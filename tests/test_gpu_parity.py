@@ -674,6 +674,8 @@ def test_hmm_expanded_graph_every_element(kind, monkeypatch):
         scale.update(succ=12)                 # 1,008 states: three registers per slot fit
     wl = workloads.make_workload(6, scale=scale, pad_value=np.nan)
     g = wl["den"]
+    if kind in ("small", "nonuniform_pi"):    # few slots per wave: not taken unless asked for
+        monkeypatch.setenv("LFMMI_GROUPED", "2")
     if kind == "nonuniform_pi":               # per-arc leak factors and closing slots
         rng = np.random.default_rng(3)
         pi = rng.uniform(0.05, 1.0, g["num_states"])
@@ -713,12 +715,18 @@ def test_hmm_expanded_graph_full_size_all_sequences():
     den.close()
 
 
-def test_numerator_graphs_take_the_emission_by_state_variant_in_fp64():
+def test_numerator_graphs_through_the_emission_by_state_variant_in_fp64(monkeypatch):
     # the phone-string numerators carry the pdf-id of the entered state; a unique start
-    # state makes them fp64 with per-arc leak factors
+    # state makes them fp64 with per-arc leak factors. With their few slots per wave
+    # the variant is slower and not taken by default: asked for here
     wl = workloads.make_workload(5, scale={"S": 300, "B": 9, "nlo": 5, "nhi": 110})
     x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
     num = binding.lfmmi_graph_create_batch(wl["num"])
+    assert binding.lfmmi_graph_info(num)["emission_by_state"] == 0
+    num.close()
+    monkeypatch.setenv("LFMMI_GROUPED", "2")
+    num = binding.lfmmi_graph_create_batch(wl["num"])
+    monkeypatch.delenv("LFMMI_GROUPED")
     info = binding.lfmmi_graph_info(num)
     assert info["fp64"] == 1 and info["emission_by_state"] == 1
     for lk in (leak, 0.0, 0.05):
