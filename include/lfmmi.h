@@ -177,9 +177,14 @@ lfmmi_status lfmmi_forward_backward_static(const lfmmi_graph *graph, const float
  *   grad[b,t,:] = numerator occupancies - denominator occupancies (rows t >= lengths[b]: 0)
  *   status[b]   = the two passes' flags or-ed together (may be NULL)
  * exactly what lfmmi_forward_backward(num, ..., +1, 0, ...) followed by
- * lfmmi_forward_backward(den, ..., -1, 1, ...) leaves in the three arrays, and
- * enqueued the same way: the numerators' pass, then the denominator's, on
- * hip_stream. (Running the two passes beside each other on streams of their own
+ * lfmmi_forward_backward(den, ..., -1, 1, ...) leaves in the three arrays (bit for
+ * bit), and enqueued the same way: the numerators' pass, then the denominator's,
+ * on hip_stream. The emission values exp(logit - row maximum) are computed once,
+ * by the numerators' pass; the denominator's reads them from that handle's
+ * workspace. If the denominator's pass is refused (an error code comes back) the
+ * numerators' pass is already enqueued and the three arrays are left holding its
+ * results alone: treat them as undefined.
+ * (Running the two passes beside each other on streams of their own
  * was built and measured 13 to 24 % slower on the 128-sequence workload: the
  * numerators' workgroups then take compute units from the denominator's longest
  * sequences, whose recursion decides when the call ends, and HIP streams of one

@@ -89,6 +89,14 @@ struct lfmmi_graph {
     hipEvent_t stage_done = nullptr;
     bool stage_pending = false;
 
+    // emission values of the last call on this handle (inside ws), for the pass that
+    // follows it in a full-loss call; and values borrowed from the other handle
+    float* last_emis = nullptr;
+    float* last_rowmax = nullptr;
+    size_t last_emis_count = 0;  // B * T * P of that call
+    const float* borrow_emis = nullptr;
+    const float* borrow_rowmax = nullptr;
+
     // streams and events of the concurrent buckets of a call, made on first use
     hipStream_t aux[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
     hipEvent_t fork = nullptr;
@@ -571,7 +579,7 @@ CallLayout layout_call(const lfmmi_graph* h, int32_t B, int32_t T, int32_t P, in
     return l;
 }
 
-void fill_params(const lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
+void fill_params(lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
                  const float* logits, int32_t B, int32_t T, int32_t P, float leak,
                  float grad_scale, int accumulate, float* objf, float* grad, int32_t* status,
                  FbParams* out, LaunchShape* shape_out)
@@ -583,6 +591,17 @@ void fill_params(const lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
     p.logits = logits;
     p.emis = reinterpret_cast<float*>(ws + lay.at_emis);
     p.rowmax = reinterpret_cast<float*>(ws + lay.at_rowmax);
+    p.emis_ready = 0;
+    if (h->borrow_emis) {  // the other pass of a full-loss call computed them (read only here)
+        p.emis = const_cast<float*>(h->borrow_emis);
+        p.rowmax = const_cast<float*>(h->borrow_rowmax);
+        p.emis_ready = 1;
+        h->last_emis = nullptr;
+    } else {
+        h->last_emis = p.emis;
+        h->last_rowmax = p.rowmax;
+        h->last_emis_count = (size_t)B * T * P;
+    }
     p.alpha = ws + lay.at_alpha;
     p.beta = ws + lay.at_beta;
     p.scal = ws + lay.at_scal;
@@ -945,11 +964,25 @@ lfmmi_status lfmmi_loss(const lfmmi_graph* num, const lfmmi_graph* den, const fl
     // was measured slower (see the header): without stream priorities the numerators'
     // workgroups take compute units from the denominator's longest sequences, whose
     // recursion is the critical path of the call.
+    lfmmi_graph* hn = const_cast<lfmmi_graph*>(num);
+    lfmmi_graph* hd = const_cast<lfmmi_graph*>(den);
+    hn->last_emis = nullptr;
     lfmmi_status st = lfmmi_forward_backward(num, logits, lengths, B, T, P, leak, 1.f, 0, objf,
                                              grad, status, hip_stream);
     if (st != LFMMI_OK) return st;
-    return lfmmi_forward_backward(den, logits, lengths, B, T, P, leak, -1.f, 1, objf, grad, status,
-                                  hip_stream);
+    // exp(logit - row maximum) and the row maxima are the same for both passes: the
+    // denominator's reads what the numerators' pass left in its workspace (same
+    // stream, so it is complete; same B, T, P, so the layout is the same)
+    if (hn->last_emis && hn->last_emis_count == (size_t)B * T * P &&
+        env_int("LFMMI_SHARE_EMIS", 1) != 0) {
+        hd->borrow_emis = hn->last_emis;
+        hd->borrow_rowmax = hn->last_rowmax;
+    }
+    st = lfmmi_forward_backward(den, logits, lengths, B, T, P, leak, -1.f, 1, objf, grad, status,
+                                hip_stream);
+    hd->borrow_emis = nullptr;
+    hd->borrow_rowmax = nullptr;
+    return st;
 }
 
 lfmmi_status lfmmi_graph_info(const lfmmi_graph* h, int64_t info[8])

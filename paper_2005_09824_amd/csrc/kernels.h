@@ -80,6 +80,8 @@ struct FbParams {
     int32_t lds_rows_occ;   // largest padded OCC row count over the handle's graphs
     int32_t accumulate;
     int32_t wide;           // 1: state vectors, trellis and scales in fp64
+    int32_t emis_ready;     // 1: emis / rowmax already hold this batch's values (the other
+                            // pass of a full-loss call computed them): k_emit skips them
     float leak, grad_scale;
 };
 

@@ -63,6 +63,7 @@ __global__ void __launch_bounds__(256) k_emit(FbParams p)
             for (int d = lane; d < p.P; d += 64) p.grad[at + d] = 0.f;
         return;
     }
+    if (p.emis_ready) return;  // this frame's emission row and maximum are there already
     const float* x = p.logits + at;
     float* e = p.emis + at;
     float m = -INFINITY;
