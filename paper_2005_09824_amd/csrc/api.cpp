@@ -297,31 +297,43 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
             };
             const int gslots = st == LFMMI_OK ? grouped_slots() : 0;
             h->rec_grouped = gslots > 0;
-            h->rec_nslot = gslots > 0 ? gslots
-                           : st == LFMMI_OK && registers_possible(waves)
-                               ? rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes)
-                               : 0;
-            if (st == LFMMI_OK && h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
-                registers_possible(waves / 2) &&
-                rec_register_slots(h->wide, h->has_wb, 2 * max_slots, waves / 2 * kLanes) != 0) {
-                waves /= 2;
-                st = pack_with(waves, &max_slots);
-                h->rec_nslot = rec_register_slots(h->wide, h->has_wb, max_slots, waves * kLanes);
-            }
+            auto resident = [&](int slots, int wv) {
+                return rec_register_slots(h->wide, h->has_wb, h->rec_yrep, h->rec_hubs, slots,
+                                          wv * kLanes);
+            };
             // too many arcs for the registers: keep the first slots of every wave there
             // and stream the others, where the fixed LDS map of that kernel holds the graph
             auto hybrid_possible = [&]() {  // 0: no; 1: 32 KB state vectors; 2: 48 KB
                 if (h->wide || h->has_wb || env_int("LFMMI_HYBRID", 1) == 0) return 0;
                 if (h->rec_yrep ? num_pdfs > 255 : num_pdfs > 3072) return 0;
-                if (rec_hybrid_slots(h->wide, h->has_wb) <= 0) return 0;
                 // padded rows, not states: see registers_possible
                 const int most = std::max(h->max_rows_f, h->max_rows_b);
-                if (most <= 8192) return 1;
-                return most <= 12288 && !h->rec_yrep ? 2 : 0;
+                const int map = most <= 8192 ? 1 : (most <= 12288 && !h->rec_yrep ? 2 : 0);
+                return map != 0 && rec_hybrid_slots(h->wide, h->has_wb, h->rec_yrep, h->rec_hubs,
+                                                    map) > 0
+                           ? map
+                           : 0;
             };
-            if (st == LFMMI_OK && h->rec_nslot == 0 && hybrid_possible() != 0) {
-                h->rec_nslot = rec_hybrid_slots(h->wide, h->has_wb);
-                h->rec_hybrid = hybrid_possible();
+            // Not every combination of slot count, replicated emission row and hub code
+            // is built (some would spill registers): when nothing fits with the
+            // replicated row, the choice is made again with plain emission rows.
+            for (int attempt = 0; attempt < 2 && st == LFMMI_OK; ++attempt) {
+                h->rec_nslot = gslots > 0 ? gslots
+                               : registers_possible(waves) ? resident(max_slots, waves)
+                                                           : 0;
+                if (h->rec_nslot == 0 && !h->wide && forced <= 0 && waves > 8 &&
+                    registers_possible(waves / 2) && resident(2 * max_slots, waves / 2) != 0) {
+                    waves /= 2;
+                    st = pack_with(waves, &max_slots);
+                    h->rec_nslot = st == LFMMI_OK ? resident(max_slots, waves) : 0;
+                }
+                if (st == LFMMI_OK && h->rec_nslot == 0 && hybrid_possible() != 0) {
+                    h->rec_hybrid = hybrid_possible();
+                    h->rec_nslot = rec_hybrid_slots(h->wide, h->has_wb, h->rec_yrep, h->rec_hubs,
+                                                    h->rec_hybrid);
+                }
+                if (h->rec_nslot != 0 || !h->rec_yrep) break;
+                h->rec_yrep = false;
             }
             if (st != LFMMI_OK) {
                 delete h;

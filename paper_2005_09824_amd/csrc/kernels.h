@@ -139,10 +139,11 @@ hipError_t launch_describe(const FbParams& p, const int32_t* lengths, int num_gr
 // Dynamic LDS the recursion / occupancy kernels need.
 size_t rec_lds_bytes(int lds_rows, int P, bool wide, bool yrep);
 // Register-resident slot count the recursion kernel offers for this shape (0: none).
-int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
+int rec_register_slots(bool wide, bool has_wb, bool yrep, bool hubs, int max_wave_slots,
+                       int threads);
 // Slots of the hybrid variant (a wave's leading slices in registers, the others
 // streamed) for this kind of graph, 0 if there is none.
-int rec_hybrid_slots(bool wide, bool has_wb);
+int rec_hybrid_slots(bool wide, bool has_wb, bool yrep, bool hubs, int map /* 1: 32 KB, 2: 48 KB */);
 // Slots of the variant for graphs whose arcs take the pdf of the entered state
 // (0: none for this shape), and the rows it stages emissions for with this many threads.
 int rec_grouped_slots(bool wide, bool has_wb, int max_wave_slots, int threads);

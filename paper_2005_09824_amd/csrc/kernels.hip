@@ -1977,13 +1977,19 @@ const RecVariant kRecVariants[] = {
     // register-resident arcs, 16 waves (128 VGPRs per lane)
     LFMMI_REC(float, 0, 16, 0, 1024), LFMMI_REC(float, 0, 20, 0, 1024),
     LFMMI_REC(float, 0, 24, 0, 1024), LFMMI_REC(float, 0, 26, 0, 1024),
-    LFMMI_REC(float, 0, 28, 0, 1024),
+    // (28 slots with hub code and a replicated emission row would spill a register)
+    {0, 28, 0, 0, 1024, k_rec<float, 28, false, false, 1024>},
+    {0, 28, 1, 0, 1024, k_rec<float, 28, true, false, 1024>},
+    {0, 28, 0, 0, 1024, k_rec<float, 28, false, false, 1024, false, false, true>, 0, 1},
     LFMMI_REC(float, 0, 16, 1, 1024),
     // register-resident arcs, 12 waves (168 VGPRs per lane)
     LFMMI_REC(float, 0, 32, 0, 768), LFMMI_REC(float, 0, 36, 0, 768),
     // register-resident arcs, 8 waves (256 VGPRs per lane)
     LFMMI_REC(float, 0, 32, 0, 512), LFMMI_REC(float, 0, 48, 0, 512),
-    LFMMI_REC(float, 0, 32, 1, 512), LFMMI_REC(float, 0, 48, 1, 512),
+    LFMMI_REC(float, 0, 32, 1, 512),
+    // (48 slots with per-arc leak factors: plain emission rows only, no spill)
+    {0, 48, 0, 1, 512, k_rec<float, 48, false, true, 512>},
+    {0, 48, 0, 1, 512, k_rec<float, 48, false, true, 512, false, false, true>, 0, 1},
     // fp64 state vectors (graphs with non-final states: numerators are small)
     LFMMI_REC(double, 1, 8, 1, 1024), LFMMI_REC(double, 1, 16, 1, 1024),
     LFMMI_REC(double, 1, 32, 1, 512),
@@ -1994,8 +2000,8 @@ const RecVariant kRecVariants[] = {
     // ... with the LDS map for up to 12288 states
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, true>, 2},
     // ... and the three for graphs with hub slices
+    // (with a replicated emission row the hub code would spill a register: plain rows)
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, false, true>, 1, 1},
-    {0, kHybridSlots, 1, 0, 1024, k_rec<float, kHybridSlots, true, false, 1024, true, false, true>, 1, 1},
     {0, kHybridSlots, 0, 0, 1024, k_rec<float, kHybridSlots, false, false, 1024, true, true, true>, 2, 1},
     // emission by entered state (two registers per slot: more slots fit)
     LFMMI_REC_GROUPED(float, 0, 16, 0, 1024), LFMMI_REC_GROUPED(float, 0, 24, 0, 1024),
@@ -2020,12 +2026,13 @@ const RecVariant* find_rec(bool wide, int nslot, bool yrep, bool has_wb, int hyb
 
 }  // namespace
 
-int rec_register_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
+int rec_register_slots(bool wide, bool has_wb, bool yrep, bool hubs, int max_wave_slots,
+                       int threads)
 {
     int best = 0;
     for (const RecVariant& v : kRecVariants)
         if (v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) && v.nslot > 0 && !v.hybrid &&
-            !v.grouped &&
+            !v.grouped && v.yrep == (yrep ? 1 : 0) && v.hubs == (hubs ? 1 : 0) &&
             v.nslot >= max_wave_slots && threads <= v.max_threads && (best == 0 || v.nslot < best))
             best = v.nslot;
     return best;
@@ -2043,9 +2050,13 @@ int rec_grouped_slots(bool wide, bool has_wb, int max_wave_slots, int threads)
 
 int rec_grouped_max_rows(int threads) { return kGroupedPasses * threads; }
 
-int rec_hybrid_slots(bool wide, bool has_wb)
+int rec_hybrid_slots(bool wide, bool has_wb, bool yrep, bool hubs, int map)
 {
-    return (!wide && !has_wb) ? kHybridSlots : 0;
+    for (const RecVariant& v : kRecVariants)
+        if (v.hybrid == map && v.wide == (wide ? 1 : 0) && v.has_wb == (has_wb ? 1 : 0) &&
+            v.yrep == (yrep ? 1 : 0) && v.hubs == (hubs ? 1 : 0))
+            return v.nslot;
+    return 0;
 }
 
 hipError_t configure_kernels()

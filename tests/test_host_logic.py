@@ -308,8 +308,9 @@ def test_padded_rows_of_hub_slices_fit_the_chosen_kernels_lds_map(S, hubs_in, hu
     resident = binding.lfmmi_graph_ordering_info(h, 0, 0)["register_slots"] > 0
     if S == 4000:
         assert resident and rows <= 8192
-    elif S == 8000:
-        assert rows > 8192 and not resident
+    elif S == 8000:   # the map with 48 KB state vectors (plain emission rows), or streamed arcs
+        assert rows > 8192
+        assert not resident or binding.lfmmi_graph_ordering_info(h, 0, 0)["lds_vector_rows"] == 12288
     else:
         assert rows > 12288 and not resident
     h.close()
