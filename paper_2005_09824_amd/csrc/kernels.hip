@@ -1479,6 +1479,9 @@ __global__ void __launch_bounds__(NT) k_rec(FbParams p)
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int code = p.order[2 * p.seq_first + blockIdx.x];
     const int b = code >> 1, dir = code & 1;
+#ifdef LFMMI_ONLY_DIR  // timing builds only: one of the two recursions (results are not valid)
+    if (dir != LFMMI_ONLY_DIR) return;
+#endif
     const SeqDesc sd = p.seqs[b];
     const OrdDesc od = p.g.ords[sd.graph * 3 + dir];
     if constexpr (GROUPED) {
