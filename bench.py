@@ -28,7 +28,9 @@ LDS_PEAK_MEASURED_GBPS = 68800.0
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes of the recursion kernel per step (all its launches), from rocprofv3 FETCH_SIZE /
 # WRITE_SIZE scaled by a plain copy of known size (profiles/hbm_traffic_<workload>.txt)
-REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6, "biphone_10k": 4245.5e6, "long_unequal_5k": 1224.1e6}
+# (e2e_num_den: the denominator's recursion, the kernel the roofline object describes)
+REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6, "biphone_10k": 4245.5e6, "long_unequal_5k": 1224.1e6,
+                     "e2e_num_den": 641.8e6, "hmm_den_2k": 345.6e6}
 
 
 def main():
@@ -36,7 +38,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 is the metric)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload 1..5 (2 is the metric), or 6: the HMM-expanded graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run plain device-to-device copies of BYTES (to calibrate the "
