@@ -45,8 +45,9 @@ def test_config1_denominator_numerators_and_full_loss():
     x, lens, leak = wl["logits"], wl["lengths"], wl["leak"]
     lz_d, g_d = oracle.forward_backward(wl["den"], x, lens, leak)
     lz_n, g_n = oracle.forward_backward_per_utt(wl["num"], x, lens, leak)
-    check(*run_gpu(den, x, lens, leak), lz_d, g_d, "den")
-    check(*run_gpu(num, x, lens, leak), lz_n, g_n, "num")
+    rel_d, err_d = check(*run_gpu(den, x, lens, leak), lz_d, g_d, "den")
+    rel_n, err_n = check(*run_gpu(num, x, lens, leak), lz_n, g_n, "num")
+    print("config 1: objf max rel err %.2e, grad max abs err %.2e" % (max(rel_d, rel_n), max(err_d, err_n)))
     # Eq. 2 / Eq. 3: numerators with (+1, overwrite), denominator with (-1, accumulate)
     torch = _torch()
     xd = torch.from_numpy(x).cuda()
