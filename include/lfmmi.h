@@ -125,7 +125,7 @@ void lfmmi_graph_destroy(lfmmi_graph *graph);
  *            work; it does not synchronise. It may allocate (and so
  *            synchronise) when the handle's cached workspace has to grow.
  *            Internally the sequences are cut by length into up to four buckets
- *            whose kernels run on streams of the handle's own (default
+ *            whose kernels run on three streams the library keeps per device (default
  *            priority) between an event recorded on hip_stream and events
  *            hip_stream then waits for: all of the call's work is ordered on
  *            hip_stream as if it ran there. (The buckets overlap only while their

@@ -98,7 +98,6 @@ struct lfmmi_graph {
     const float* borrow_rowmax = nullptr;
 
     // streams and events of the concurrent buckets of a call, made on first use
-    hipStream_t aux[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
     hipEvent_t fork = nullptr;
     hipEvent_t join[Buckets::kMax] = {nullptr, nullptr, nullptr, nullptr};  // [0] unused
 
@@ -106,6 +105,7 @@ struct lfmmi_graph {
     int profile = 0;  // 0 off, 1 events around every kernel, 2 around the recursion only
     std::vector<hipEvent_t> ev;
     std::vector<int32_t> ev_buckets;  // bucket count of each profiled call
+    std::vector<hipEvent_t> ev_free;  // events of calls already read, used again
 };
 
 namespace {
@@ -528,6 +528,31 @@ lfmmi_status upload(lfmmi_graph* h)
     return LFMMI_OK;
 }
 
+// Streams of the buckets 1 .. 3 of a call: one set per device for the whole process,
+// made on first use and kept until the process ends. All handles share them, so
+// that a process holds the caller's stream plus three - HIP gives it four hardware
+// queues, and streams that share a queue run their kernels one after the other.
+// Plain streams (default priority) that do not synchronise with stream 0. The order
+// of a call's work is given by its own fork / join events, so calls on different
+// handles may share the streams.
+hipError_t bucket_stream(int device, int q, hipStream_t* out)
+{
+    static std::mutex mu;
+    static std::vector<hipStream_t> pool;  // [device * kMax + q]
+    std::lock_guard<std::mutex> lock(mu);
+    const size_t at = (size_t)device * Buckets::kMax + (size_t)q;
+    if (pool.size() <= at) pool.resize(at + 1, nullptr);
+    if (!pool[at]) {
+        const hipError_t e = hipStreamCreateWithFlags(&pool[at], hipStreamNonBlocking);
+        if (e != hipSuccess) {
+            pool[at] = nullptr;
+            return e;
+        }
+    }
+    *out = pool[at];
+    return hipSuccess;
+}
+
 // Argument checks shared by the forward-backward entry points (B == 0 is valid:
 // the caller then returns at once).
 lfmmi_status check_call(const lfmmi_graph* h, const float* logits, const int32_t* lengths,
@@ -727,8 +752,8 @@ void lfmmi_graph_destroy(lfmmi_graph* h)
         if (h->stage) (void)hipHostFree(h->stage);
         if (h->stage_done) (void)hipEventDestroy(h->stage_done);
         for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
+        for (hipEvent_t e : h->ev_free) (void)hipEventDestroy(e);
         for (int q = 1; q < Buckets::kMax; ++q) {
-            if (h->aux[q]) (void)hipStreamDestroy(h->aux[q]);
             if (h->join[q]) (void)hipEventDestroy(h->join[q]);
         }
         if (h->fork) (void)hipEventDestroy(h->fork);
@@ -789,12 +814,20 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
             h->ws = nullptr;
             h->ws_bytes = 0;
         }
-        if ((e = hipMalloc(&h->ws, total)) != hipSuccess) {
+        // an eighth more than asked for: batches whose lengths vary a little from call to
+        // call (the usual training loop) then settle after a few calls instead of
+        // synchronising and reallocating at every new maximum
+        size_t want = total + total / 8;
+        if ((e = hipMalloc(&h->ws, want)) != hipSuccess) {
+            want = total;
+            e = hipMalloc(&h->ws, want);
+        }
+        if (e != hipSuccess) {
             h->ws = nullptr;
             return fail(LFMMI_ERR_OOM, "workspace of " + std::to_string(total) +
                                            " bytes: " + hipGetErrorString(e));
         }
-        h->ws_bytes = total;
+        h->ws_bytes = want;
     }
     // descriptors depend on the lengths and T only: a call with the same ones as
     // the last finds them on the device already
@@ -881,13 +914,13 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
                 return fail_hip(e, "hipEventCreate");
             for (int q = 1; q < want; ++q) {
                 // plain streams (default priority) that do not synchronise with stream 0
-                if (!h->aux[q] &&
-                    (e = hipStreamCreateWithFlags(&h->aux[q], hipStreamNonBlocking)) != hipSuccess)
+                hipStream_t aux = nullptr;
+                if ((e = bucket_stream(h->device, q, &aux)) != hipSuccess)
                     return fail_hip(e, "hipStreamCreate");
                 if (!h->join[q] &&
                     (e = hipEventCreateWithFlags(&h->join[q], hipEventDisableTiming)) != hipSuccess)
                     return fail_hip(e, "hipEventCreate");
-                bk.streams[q] = h->aux[q];
+                bk.streams[q] = aux;
                 bk.join[q] = h->join[q];
             }
             bk.fork = h->fork;
@@ -899,7 +932,10 @@ lfmmi_status lfmmi_forward_backward(const lfmmi_graph* graph, const float* logit
         const size_t first = h->ev.size(), count = 4 * (size_t)bk.n;
         h->ev.resize(first + count, nullptr);
         for (size_t i = first; i < first + count; ++i)
-            if ((e = hipEventCreate(&h->ev[i])) != hipSuccess) {
+            if (!h->ev_free.empty()) {
+                h->ev[i] = h->ev_free.back();
+                h->ev_free.pop_back();
+            } else if ((e = hipEventCreate(&h->ev[i])) != hipSuccess) {
                 for (size_t j = first; j < i; ++j) (void)hipEventDestroy(h->ev[j]);
                 h->ev.resize(first);
                 return fail_hip(e, "hipEventCreate");
@@ -1098,7 +1134,7 @@ lfmmi_status lfmmi_profile_read(lfmmi_graph* h, float ms[4], int32_t* calls, int
         }
         at += 4 * (size_t)h->ev_buckets[c];
     }
-    for (hipEvent_t x : h->ev) (void)hipEventDestroy(x);
+    h->ev_free.insert(h->ev_free.end(), h->ev.begin(), h->ev.end());  // kept for the next calls
     h->ev.clear();
     h->ev_buckets.clear();
     if (st == LFMMI_OK) {

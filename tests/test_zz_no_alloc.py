@@ -117,3 +117,48 @@ def test_static_entry_point_numerator_batch_accumulate_and_limits():
     got, want = _both(den, wl["logits"], lens, leak)
     _same(got, want, lens)
     num.close(); den.close()
+
+
+def test_static_entry_point_under_hip_graph_capture():
+    # the caller it is for: one call captured into a HIP graph (kernel launches only, on
+    # the capturing stream) and replayed, with the program's own eager work and
+    # synchronisations between the replays; every replay against the eager result
+    import torch
+    wl = workloads.make_workload(2, scale={"B": 6, "Tlo": 20, "Thi": 80}, pad_value=np.nan)
+    h = binding.lfmmi_graph_create(wl["den"])
+    lens, leak = wl["lengths"], wl["leak"]
+    x = torch.from_numpy(wl["logits"]).cuda()
+    B, T, P = x.shape
+    objf = torch.zeros(B, device="cuda")
+    grad = torch.zeros((B, T, P), device="cuda")
+    status = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ref = binding.lfmmi_forward_backward(h, x, lens, leak)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # once eagerly (first-use work stays out of the capture)
+        binding.lfmmi_forward_backward_static(h, x, lens, leak, 1.0, False, objf, grad, status)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert torch.equal(objf, ref[0]) and torch.equal(grad, ref[1])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.lfmmi_forward_backward_static(h, x, lens, leak, 1.0, False, objf, grad, status)
+    for _ in range(3):
+        objf.fill_(7.0)
+        grad.fill_(7.0)
+        float((x[:, :5] * 2).nan_to_num().sum().item())   # eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(objf, ref[0]) and torch.equal(grad, ref[1])
+        assert int(status.abs().sum().item()) == 0
+    # other values in the same buffers: the replay reads them
+    x2 = x.clone()
+    x2[:, :10] *= 0.5
+    ref2 = binding.lfmmi_forward_backward(h, x2, lens, leak)
+    torch.cuda.synchronize()
+    x.copy_(x2)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(objf, ref2[0]) and torch.equal(grad, ref2[1])
+    del graph
+    h.close()
