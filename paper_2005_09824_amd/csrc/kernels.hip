@@ -496,6 +496,12 @@ struct RecRegs {
     // cover 8 * P <= kYPass * NT quads. Plain rows: one value per thread and pass.
     static constexpr int kYPass = stage_passes(YREP, NT);
     static constexpr int kPrefetch = NT >= 1024 ? 2 : (NT >= 768 ? 4 : 6);
+    // Slots whose gathers go out at the start of a step, before the partial sums are
+    // turned into this step's scalars: with one pair ahead in the slot loop (the depth
+    // that measured best) the LDS pipe would run dry during that serial chain, so a
+    // second pair is issued there and the loop falls back to one pair ahead.
+    static constexpr int kBurst =
+        (kPrefetch == 2 && NSLOT >= 8 && NSLOT <= 26 && !HYBRID) ? 4 : kPrefetch;
     static constexpr int kTailSlots = 4;
     // slot before which a step does its global memory work; every wave must get
     // there, also one that leaves the slot loop early
@@ -603,10 +609,10 @@ struct RecRegs {
             for (int i = 0; i < NSLOT; ++i) asm volatile("" : "+v"(ya[i]));
         }
         Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
-        Real xv[kPrefetch ? kPrefetch : 1];
-        float ev[kPrefetch ? kPrefetch : 1];
+        Real xv[kBurst ? kBurst : 1];
+        float ev[kBurst ? kBurst : 1];
 #pragma unroll
-        for (int i = 0; i < kPrefetch && i < NSLOT; ++i) {
+        for (int i = 0; i < kBurst && i < NSLOT; ++i) {
             xv[i] = lds_ldr<Real>(xc + x_at(i));
             ev[i] = lds_ld(yc + y_at(i));
         }
@@ -672,15 +678,17 @@ struct RecRegs {
                 x0 = lds_ldr<Real>(xc + x_at(i)); e0 = lds_ld(yc + y_at(i));
                 x1 = lds_ldr<Real>(xc + x_at(i + 1)); e1 = lds_ld(yc + y_at(i + 1));
             } else {
-                x0 = xv[i % (kPrefetch ? kPrefetch : 1)]; e0 = ev[i % (kPrefetch ? kPrefetch : 1)];
-                x1 = xv[(i + 1) % (kPrefetch ? kPrefetch : 1)]; e1 = ev[(i + 1) % (kPrefetch ? kPrefetch : 1)];
+                x0 = xv[i % (kBurst ? kBurst : 1)]; e0 = ev[i % (kBurst ? kBurst : 1)];
+                x1 = xv[(i + 1) % (kBurst ? kBurst : 1)]; e1 = ev[(i + 1) % (kBurst ? kBurst : 1)];
             }
-            if (kPrefetch > 0 && i + kPrefetch < NSLOT) {
+            // the slots kPrefetch ahead; those of the opening burst are in flight already
+            if (kPrefetch > 0 && i + kPrefetch < NSLOT && i + kPrefetch >= kBurst) {
                 constexpr int kp = kPrefetch ? kPrefetch : 1;
-                xv[i % kp] = lds_ldr<Real>(xc + x_at((i + kp) % NSLOT));
-                ev[i % kp] = lds_ld(yc + y_at((i + kp) % NSLOT));
-                xv[(i + 1) % kp] = lds_ldr<Real>(xc + x_at((i + 1 + kp) % NSLOT));
-                ev[(i + 1) % kp] = lds_ld(yc + y_at((i + 1 + kp) % NSLOT));
+                constexpr int kr = kBurst ? kBurst : 1;
+                xv[(i + kp) % kr] = lds_ldr<Real>(xc + x_at((i + kp) % NSLOT));
+                ev[(i + kp) % kr] = lds_ld(yc + y_at((i + kp) % NSLOT));
+                xv[(i + 1 + kp) % kr] = lds_ldr<Real>(xc + x_at((i + 1 + kp) % NSLOT));
+                ev[(i + 1 + kp) % kr] = lds_ld(yc + y_at((i + 1 + kp) % NSLOT));
             }
             // one wait for the pair: this names the value loaded last, so the first
             // use of any of the four comes after all of them have arrived
@@ -1053,6 +1061,7 @@ struct RecGrouped {
     static constexpr int kYPass = kGroupedPasses;
     static constexpr int kChunk = 4;  // beta: slices whose rows are folded at a time
     static constexpr int kPrefetch = NT >= 1024 ? 2 : 4;  // (twice the depth measured no faster)
+    static constexpr int kBurst = (kPrefetch == 2 && NSLOT >= 8) ? 4 : kPrefetch;  // see RecRegs
     static constexpr int kTailSlots = 4;
     static constexpr int kStageAt = NSLOT - kTailSlots > 4 ? 4 : 0;
     static constexpr uint32_t kZeroX = kRegX1 - kRB;  // byte offset of the zero inside an X buffer
@@ -1099,16 +1108,16 @@ struct RecGrouped {
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
         constexpr uint32_t eyc = PAR ? kRegY0 : kRegY1, eyn = PAR ? kRegY1 : kRegY0;
         constexpr uint32_t pc = kRegPart + (PAR ? 0u : 32u * kRB), pn = kRegPart + (PAR ? 32u * kRB : 0u);
-        constexpr int kp = kPrefetch;
+        constexpr int kp = kPrefetch, kr = kBurst;
 
         Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
-        Real xv[kp];
+        Real xv[kr];
         Real own[DIR == 1 ? kChunk : 1];
         float eown[DIR == 1 ? kChunk : 1];
         float e_close = 0.f;  // alpha: emission of the row whose slice ends next
         if constexpr (DIR == 0) {
 #pragma unroll
-            for (int i = 0; i < kp && i < NSLOT; ++i) xv[i] = lds_ldr<Real>(xc + xa[i]);
+            for (int i = 0; i < kr && i < NSLOT; ++i) xv[i] = lds_ldr<Real>(xc + xa[i]);
             e_close = lds_ld(eyc + ey_first);
         } else {
             // this lane's own rows of the vector the last step wrote, and their
@@ -1159,7 +1168,7 @@ struct RecGrouped {
             }
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < kp && i < NSLOT; ++i) xv[i] = lds_ldr<Real>(xc + xa[i]);
+            for (int i = 0; i < kr && i < NSLOT; ++i) xv[i] = lds_ldr<Real>(xc + xa[i]);
             asm volatile("" ::: "memory");
         }
 
@@ -1189,10 +1198,10 @@ struct RecGrouped {
                     *sS = Sd;
                 }
             }
-            Real x0 = xv[i % kp], x1 = xv[(i + 1) % kp];
-            if (i + kp < NSLOT) {
-                xv[i % kp] = lds_ldr<Real>(xc + xa[(i + kp) % NSLOT]);
-                xv[(i + 1) % kp] = lds_ldr<Real>(xc + xa[(i + 1 + kp) % NSLOT]);
+            Real x0 = xv[i % kr], x1 = xv[(i + 1) % kr];
+            if (i + kp < NSLOT && i + kp >= kr) {  // (the opening burst is in flight already)
+                xv[(i + kp) % kr] = lds_ldr<Real>(xc + xa[(i + kp) % NSLOT]);
+                xv[(i + 1 + kp) % kr] = lds_ldr<Real>(xc + xa[(i + 1 + kp) % NSLOT]);
             }
             asm volatile("" : "+v"(x0) : "v"(x1));  // one wait for the pair
             if constexpr (sizeof(Real) == 4) {
