@@ -734,3 +734,25 @@ def test_numerator_graphs_through_the_emission_by_state_variant_in_fp64(monkeypa
         lz, gamma = oracle.forward_backward_per_utt(wl["num"], x, lens, lk)
         check(*run_gpu(num, x, lens, lk), lz, gamma, "numerators, emission by state, leak %g" % lk)
     num.close()
+
+
+def test_hmm_expanded_graph_very_short_sequences():
+    # lengths 0, 1, 2, 3: the emission values of a row are fetched two steps ahead and
+    # must stay inside the sequence; beta folds them in before its first gather
+    wl = workloads.make_workload(6, scale={"B": 6, "Tlo": 4, "Thi": 9}, pad_value=np.nan)
+    g = wl["den"]
+    lens = np.array([0, 1, 2, 3, 9, 4], np.int32)
+    x = np.random.default_rng(8).normal(0, 2, (6, 9, g["num_pdfs"])).astype(np.float32)
+    for b in range(6):
+        x[b, lens[b]:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    assert _emission_by_state(h) == 1
+    for leak in (1e-5, 0.2):
+        lz, gamma = oracle.forward_backward(g, x, lens, leak)
+        objf, grad, status = run_gpu(h, x, lens, leak)
+        # the empty sequence: log Z = log(1 + leak), next to 0 with the default leak, where
+        # the fp32 sum of the 2,016 initial probabilities decides the relative error
+        assert abs(float(objf[0]) - lz[0]) <= 1e-6 and np.all(grad[0] == 0.0) and status[0] == 0
+        check(objf[1:], grad[1:], status[1:], lz[1:], gamma[1:],
+              "hmm graph, short sequences, leak %g" % leak)
+    h.close()

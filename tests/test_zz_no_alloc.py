@@ -119,6 +119,27 @@ def test_static_entry_point_numerator_batch_accumulate_and_limits():
     num.close(); den.close()
 
 
+def test_static_entry_point_largest_batch_and_empty_sequences():
+    # 256 sequences (the limit), unsorted lengths with zeros among them: descriptors
+    # and launch order are written on the device from the lengths
+    rng = np.random.default_rng(12)
+    g = workloads.random_den_graph(rng, 150, 4, 20, 0.5)
+    h = binding.lfmmi_graph_create(g)
+    B = binding.STATIC_MAX_BATCH
+    lens = rng.integers(0, 13, B).astype(np.int32)
+    lens[[0, 17, 255]] = 0
+    x = rng.normal(0, 2, (B, 12, 20)).astype(np.float32)
+    for b in range(B):
+        x[b, lens[b]:] = np.nan
+    got, want = _both(h, x, lens, 1e-4)
+    assert np.array_equal(got[2], want[2]) and np.all(got[2] == 0)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+    # T == 0: nothing to read, log Z of the empty sequence
+    got, want = _both(h, np.zeros((3, 0, 20), np.float32), np.zeros(3, np.int32), 1e-4)
+    assert np.array_equal(got[0], want[0]) and np.all(np.isfinite(got[0]))
+    h.close()
+
+
 def test_static_entry_point_under_hip_graph_capture():
     # the caller it is for: one call captured into a HIP graph (kernel launches only, on
     # the capturing stream) and replayed, with the program's own eager work and
