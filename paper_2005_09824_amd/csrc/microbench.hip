@@ -9,6 +9,8 @@
 //                               memory (the per-frame exchange a recursion split over
 //                               several compute units would need): same XCD (one L2)
 //                               and different XCDs, several protocols
+//   lfmmi_microbench cluster    the same for 2 or 4 workgroups that keep a 5,056-row state
+//                               vector between them, with a stand-in for their work
 //
 // Every wait in the exchange kernels is bounded: a workgroup that does not see its
 // partner within kSpinLimit polls sets an error flag and both leave the loop, so
@@ -368,11 +370,139 @@ static void run_exchange()
     CK(hipFree(x.clocks));
 }
 
+// ---------------------------------------------------------------------------
+// A cluster of C workgroups that keep one state vector of `rows` values between
+// them, as a recursion split over C compute units would: each step every member
+// publishes its share of the rows (rows / C values, 8-byte words that carry the
+// step number, relaxed agent-scope atomic stores) and imports everybody else's
+// (polling each word until its step number is there), writes them into its LDS,
+// and meets at a workgroup barrier; `work` dependent multiply-adds per thread stand
+// for the member's share of the recursion step. Members are workgroups
+// first, first + stride, ...: stride 8 keeps a cluster inside one XCD.
+// ---------------------------------------------------------------------------
+struct ClusterBuffers {
+    unsigned long long* rows;  // [clusters][2 parities][rows]
+    unsigned int* info;        // [0] waits that ran out, [1] wrong values
+};
+
+__global__ void __launch_bounds__(1024) k_cluster(ClusterBuffers x, int C, int stride, int rows,
+                                                  int steps, int work, int clusters)
+{
+    extern __shared__ float lds_dyn[];
+    // workgroup id -> (cluster, member): cluster c holds ids c % stride + stride * (C * (c / stride) + m)
+    const int id = blockIdx.x;
+    const int lane_of = id % stride, group = id / stride;
+    const int member = group % C, cluster = (group / C) * stride + lane_of;
+    if (cluster >= clusters) return;
+    const int tid = threadIdx.x;
+    const int share = (rows + C - 1) / C;
+    const int own0 = member * share, own1 = min(own0 + share, rows);
+    unsigned long long* buf = x.rows + (size_t)cluster * 2 * rows;
+    int my_stop = 0, stop = 0, bad = 0;
+    float carry = 1.0f;
+    for (int k = 1; k <= steps; ++k) {
+        unsigned long long* cur = buf + (size_t)(k & 1) * rows;
+        // the member's share of the step
+        float acc = carry;
+        for (int u = 0; u < work; ++u) {
+            acc = fmaf(acc, 0.999f, 0.001f);
+            asm volatile("" : "+v"(acc));
+        }
+        carry = acc;
+        // publish own rows: value = row + step (checked by the importers)
+        for (int r = own0 + tid; r < own1; r += blockDim.x) {
+            const float v = (float)(r + k);
+            __hip_atomic_store(cur + r, ((unsigned long long)(unsigned)k << 32) | __float_as_uint(v),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            lds_st((uint32_t)r * 4u, v);
+        }
+        // import the others' rows: up to 8 per thread in flight, polled until all are there
+        for (int r0 = tid; r0 < rows; r0 += 8 * blockDim.x) {
+            unsigned pending = 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + u * blockDim.x;
+                if (r < rows && (r < own0 || r >= own1)) pending |= 1u << u;
+            }
+            int spins = 0;
+            while (pending) {
+                unsigned long long w[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (pending & (1u << u))
+                        w[u] = __hip_atomic_load(cur + r0 + u * blockDim.x, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if ((pending & (1u << u)) && (unsigned)(w[u] >> 32) == (unsigned)k) {
+                        const int r = r0 + u * blockDim.x;
+                        const float v = __uint_as_float((unsigned)w[u]);
+                        bad += v != (float)(r + k);
+                        lds_st((uint32_t)r * 4u, v);
+                        pending &= ~(1u << u);
+                    }
+                if (pending && ++spins > kSpinLimit) {
+                    my_stop = 1;
+                    break;
+                }
+            }
+        }
+        stop = __syncthreads_or(my_stop);
+        if (stop) break;
+    }
+    if (tid == 0 && stop) atomicAdd(x.info, 1u);
+    if (bad) atomicAdd(x.info + 1, (unsigned)bad);
+    if (tid == 0) lds_dyn[0] = carry;  // keeps the arithmetic
+}
+
+static void run_cluster()
+{
+    const int rows = 5056;  // the 5,000-state graph's padded rows
+    const int max_clusters = 64;
+    ClusterBuffers x;
+    CK(hipMalloc(&x.rows, (size_t)max_clusters * 2 * rows * 8));
+    CK(hipMalloc(&x.info, 8 * 4));
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    const int steps = 4000;
+    std::printf("%-10s %-8s %-8s %-9s %-8s %10s %6s %6s\n", "clusters", "members", "stride", "rows", "work",
+                "ns/step", "stuck", "bad");
+    for (int clusters : {1, 16, 64})
+        for (int C : {2, 4})
+            for (int stride : {8, 1})
+                for (int work : {0, 400}) {
+                    if (clusters * C > 256) continue;
+                    CK(hipMemset(x.rows, 0, (size_t)max_clusters * 2 * rows * 8));
+                    CK(hipMemset(x.info, 0, 8 * 4));
+                    // a grid that covers whole groups of `stride` clusters
+                    const int groups = (clusters + stride - 1) / stride;
+                    const int grid = groups * C * stride;
+                    CK(hipDeviceSynchronize());
+                    CK(hipEventRecord(e0));
+                    hipLaunchKernelGGL(k_cluster, dim3(grid), dim3(1024), 32768, 0, x, C, stride, rows, steps,
+                                       work, clusters);
+                    CK(hipGetLastError());
+                    CK(hipEventRecord(e1));
+                    CK(hipDeviceSynchronize());
+                    float ms;
+                    CK(hipEventElapsedTime(&ms, e0, e1));
+                    unsigned info[8];
+                    CK(hipMemcpy(info, x.info, sizeof(info), hipMemcpyDeviceToHost));
+                    std::printf("%-10d %-8d %-8d %-9d %-8d %10.0f %6u %6u\n", clusters, C, stride, rows, work,
+                                ms * 1e6 / steps, info[0], info[1]);
+                    std::fflush(stdout);
+                }
+    CK(hipFree(x.rows));
+    CK(hipFree(x.info));
+}
+
 int main(int argc, char** argv)
 {
     const char* what = argc > 1 ? argv[1] : "all";
     CK(hipSetDevice(0));
     if (!std::strcmp(what, "lds") || !std::strcmp(what, "all")) run_lds(0);
     if (!std::strcmp(what, "exchange") || !std::strcmp(what, "all")) run_exchange();
+    if (!std::strcmp(what, "cluster") || !std::strcmp(what, "all")) run_cluster();
     return 0;
 }
