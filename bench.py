@@ -39,7 +39,8 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2,
-                    help="workload 1..5 (2 is the metric), or 6: the HMM-expanded graph")
+                    help="workload 1..5 (2 is the metric); 6: the HMM-expanded graph; "
+                         "7: the paper's own denominator size and batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run plain device-to-device copies of BYTES (to calibrate the "

@@ -32,6 +32,7 @@ CONFIG_NAMES = {
     4: "long_unequal_5k",
     5: "e2e_num_den",
     6: "hmm_den_2k",   # not one of the five named workloads: see make_workload
+    7: "wsj_den_7398",  # likewise: the paper's own denominator size and batch
 }
 
 
@@ -228,7 +229,7 @@ def spike_frames(rng, logits, lengths, fraction=0.01, magnitude=30.0):
 
 
 def make_workload(config, seed=None, scale=None, pad_value=None):
-    """Build config 1..5 (the named workloads) or 6 (see below).
+    """Build config 1..5 (the named workloads) or 6, 7 (see below).
 
     `scale` (dict) overrides sizes for reduced parity cases that keep the
     structure of the named config: keys S, k, P, B, Tlo, Thi, nlo, nhi.
@@ -290,8 +291,20 @@ def make_workload(config, seed=None, scale=None, pad_value=None):
         lengths = rng.integers(sc.get("Tlo", 100), sc.get("Thi", 500) + 1, size=B)
         lengths = np.sort(lengths)[::-1].astype(np.int32)
         logits = random_logits(rng, lengths, P, 2.0, pad_value)
+    elif config == 7:
+        # Beyond the five named workloads: the sizes Section 4.4 gives for the paper's own
+        # run - a denominator graph of 7,398 states, 128 sequences per batch (946,944
+        # (sequence, state) pairs per time step), 84 pdfs - with what it does not give
+        # filled in as in config 2: a self-loop plus 9 random out-arcs per state,
+        # Dirichlet(0.5) weights, pdf-ids uniform per arc, T uniform in [100, 500].
+        S, k, P = sc.get("S", 7398), sc.get("k", 9), sc.get("P", 84)
+        den = random_den_graph(rng, S, k, P, 0.5)
+        B = sc.get("B", 128)
+        lengths = rng.integers(sc.get("Tlo", 100), sc.get("Thi", 500) + 1,
+                               size=B).astype(np.int32)
+        logits = random_logits(rng, lengths, P, 2.0, pad_value)
     else:
-        raise ValueError("config must be 1..6")
+        raise ValueError("config must be 1..7")
     return {
         "name": name,
         "config": config,

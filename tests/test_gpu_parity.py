@@ -756,3 +756,10 @@ def test_hmm_expanded_graph_very_short_sequences():
         check(objf[1:], grad[1:], status[1:], lz[1:], gamma[1:],
               "hmm graph, short sequences, leak %g" % leak)
     h.close()
+
+
+def test_paper_sized_denominator_full_size_all_sequences():
+    # 7,398 states and 128 sequences, the sizes of the paper's own run (Section 4.4):
+    # 7,424 padded rows in the 32 KB state vectors, part of every wave's arcs streamed
+    wl = _full_size(7, list(range(128)))
+    assert wl["den"]["num_states"] * 128 == 946944
