@@ -679,8 +679,13 @@ void fill_params(lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
         if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;
     }
     // groups of frames per workgroup: with one frame per group a workgroup takes four,
-    // which spreads its start-up cost and lets it fetch the next frame's rows early
-    shape.occ_groups = std::max(1, env_int("LFMMI_OCC_GROUPS", shape.occ_multi == 1 ? 4 : 1));
+    // with two frames of large planes two, which spreads its start-up cost and lets it
+    // fetch the next group's rows early (the variants with small planes do not: two of
+    // their workgroups share a compute unit and cover each other's loads)
+    const bool large_planes = std::max(h->max_rows_f, h->max_rows_b) * 4 > 16384;
+    shape.occ_groups = std::max(
+        1, env_int("LFMMI_OCC_GROUPS",
+                   shape.occ_multi == 1 ? 4 : (shape.occ_multi == 2 && large_planes ? 2 : 1)));
 }
 
 }  // namespace

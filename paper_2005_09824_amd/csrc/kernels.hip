@@ -1651,7 +1651,15 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 template <int F, int STRIDE>
 __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_wg)
 {
-    static_assert((2 * F - 1) * STRIDE <= 65535, "plane offsets must fit the ds immediate");
+    // Plane offsets ride in the 16-bit immediate of the ds instruction. Where the XB
+    // planes lie beyond 64 KB (two frames of 32 KB planes), the record's XB offset is
+    // taken out of its upper half together with a 1 above it (64 KB + offset, one
+    // instruction as the shift would be) and the immediate holds the rest.
+    constexpr bool kBHigh = (2 * F - 1) * STRIDE > 65535;
+    static_assert((F - 1) * STRIDE <= 65535, "XA plane offsets must fit the ds immediate");
+    static_assert(!kBHigh || (F * STRIDE >= 65536 && (2 * F - 1) * STRIDE - 65536 <= 65535),
+                  "XB plane offsets less 64 KB must fit the ds immediate");
+    constexpr uint32_t kBBase = kBHigh ? 65536u : 0u;
     constexpr uint32_t kRowSum = 2u * F * STRIDE;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -1718,25 +1726,32 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             hv_r1[k] = pdf_first[hv_d[k] + 1];
         }
     }
-    // ... and the rows of the next frame are fetched while this frame's arcs are
-    // gathered: kStageRows of each side per thread (uniform leak target only)
-    constexpr int kStageRows = F == 1 ? STRIDE / 4096 : 1;
+    // ... and the rows of the next group are fetched while this group's arcs are
+    // gathered: kStageRows of each side and frame per thread (large planes, where one
+    // workgroup has a compute unit to itself; uniform leak target only)
+    constexpr bool kAhead = F == 1 || (F == 2 && STRIDE == 32768);
+    constexpr int kStageRows = kAhead ? STRIDE / 4096 : 1;
     const int rows_most = max(rows_f, rows_b);
-    const bool ahead = F == 1 && !odf.has_wb && nthreads * kStageRows >= rows_most;
-    float next_a[kStageRows], next_b[kStageRows];
-    auto fetch_rows = [&](const int t) {  // alpha of frame t - 1, beta of frame t, as stored
+    const bool ahead = kAhead && !odf.has_wb && nthreads * kStageRows >= rows_most;
+    float next_a[kAhead ? F : 1][kStageRows], next_b[kAhead ? F : 1][kStageRows];
+    // alpha of frames t - 1 .., beta of frames t .., as stored (zeros past the sequence)
+    auto fetch_rows = [&](const int t) {
 #pragma unroll
-        for (int u = 0; u < kStageRows; ++u) {
-            int r = u * nthreads + tid;
-            asm volatile("" : "+v"(r));  // recomputed here: no address registers held per row
-            next_a[u] = r < rows_f ? alpha[(size_t)(t - 1) * rows_f + r] : 0.f;
-            next_b[u] = r < rows_b ? beta[(size_t)t * rows_b + r] : 0.f;
+        for (int f = 0; f < (kAhead ? F : 1); ++f) {
+            const bool live = t + f <= T;
+#pragma unroll
+            for (int u = 0; u < kStageRows; ++u) {
+                int r = u * nthreads + tid;
+                asm volatile("" : "+v"(r));  // recomputed here: no address registers held per row
+                next_a[f][u] = (live && r < rows_f) ? alpha[(size_t)(t + f - 1) * rows_f + r] : 0.f;
+                next_b[f][u] = (live && r < rows_b) ? beta[(size_t)(t + f) * rows_b + r] : 0.f;
+            }
         }
     };
 
     const int t_begin = blockIdx.x * groups_per_wg * F + 1;
     const int t_end = min(t_begin + groups_per_wg * F - 1, p.T);
-    if constexpr (F == 1)
+    if constexpr (kAhead)
         if (ahead && t_begin <= min(t_end, T)) fetch_rows(t_begin);
     for (int t0 = t_begin; t0 <= t_end; t0 += F) {
         if (t0 > T) {  // nothing but padding rows from here on
@@ -1767,16 +1782,22 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
         // staging: two rows per thread and side in flight, all loads (alpha and beta)
         // issued before any is used
         const int rows_max = ahead ? 0 : rows_most;
-        if constexpr (F == 1)
+        if constexpr (kAhead)
             if (ahead) {
-                const float la = ca[0] * odf.b_const, lb = cb[0] * odb.b_const;
 #pragma unroll
-                for (int u = 0; u < kStageRows; ++u) {
-                    int r = u * nthreads + tid;
-                    asm volatile("" : "+v"(r));
-                    if (r < rows_f) lds_st((uint32_t)r * 4u, fmaf(next_a[u], inva[0], la));
-                    if (r < rows_b)
-                        lds_st((uint32_t)STRIDE + (uint32_t)r * 4u, fmaf(next_b[u], invb[0], lb));
+                for (int f = 0; f < F; ++f) {
+                    const float la = ca[f] * odf.b_const, lb = cb[f] * odb.b_const;
+#pragma unroll
+                    for (int u = 0; u < kStageRows; ++u) {
+                        int r = u * nthreads + tid;
+                        asm volatile("" : "+v"(r));
+                        if (r < rows_f)
+                            lds_st((uint32_t)(f * STRIDE) + (uint32_t)r * 4u,
+                                   fmaf(next_a[f][u], inva[f], la));
+                        if (r < rows_b)
+                            lds_st((uint32_t)((F + f) * STRIDE) + (uint32_t)r * 4u,
+                                   fmaf(next_b[f][u], invb[f], lb));
+                    }
                 }
             }
         for (int r0 = 0; r0 < rows_max; r0 += 2 * nthreads) {
@@ -1808,16 +1829,17 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             }
         }
         __syncthreads();
-        if constexpr (F == 1)
-            if (ahead && t0 + 1 <= min(t_end, T)) fetch_rows(t0 + 1);
+        if constexpr (kAhead)
+            if (ahead && t0 + F <= min(t_end, T)) fetch_rows(t0 + F);
 
         auto one_slot = [&](const uint2 r, float* acc) {
-            const uint32_t xa = r.x & 0xffffu, xb = r.x >> 16;
+            const uint32_t xa = r.x & 0xffffu;
+            const uint32_t xb = kBHigh ? __builtin_amdgcn_alignbit(1u, r.x, 16u) : r.x >> 16;
             const float w = __uint_as_float(r.y);
 #pragma unroll
             for (int f = 0; f < F; ++f) {
                 const float a = lds_ld(xa + (uint32_t)(f * STRIDE));
-                const float bt = lds_ld(xb + (uint32_t)((F + f) * STRIDE));
+                const float bt = lds_ld(xb + ((uint32_t)((F + f) * STRIDE) - kBBase));
                 acc[f] = fmaf(w * bt, a, acc[f]);
             }
         };
@@ -2093,6 +2115,7 @@ hipError_t configure_kernels()
                          reinterpret_cast<const void*>(k_occ<double>),
                          reinterpret_cast<const void*>(k_occ_planes<4, 8192>),
                          reinterpret_cast<const void*>(k_occ_planes<2, 16384>),
+                         reinterpret_cast<const void*>(k_occ_planes<2, 32768>),
                          reinterpret_cast<const void*>(k_occ_planes<1, 32768>),
                          reinterpret_cast<const void*>(k_occ_planes<1, 49152>)};
     for (const void* f : fns) {
@@ -2120,7 +2143,9 @@ size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide)
 // state rows and frames per record (one frame: a wider plane for large graphs).
 static int occ_plane_stride(int rows, int frames)
 {
-    return frames == 1 && rows * 4 > 32768 ? 49152 : 32768 / frames;
+    if (frames == 1) return rows * 4 > 32768 ? 49152 : 32768;
+    if (frames == 2) return rows * 4 > 16384 ? 32768 : 16384;
+    return 32768 / frames;
 }
 
 // Frames per record of the plane-layout occupancy kernel for this many state
@@ -2128,7 +2153,7 @@ static int occ_plane_stride(int rows, int frames)
 int occ_plane_frames(int rows, int occ_rows)
 {
     for (int f : {4, 2, 1})
-        if (rows * 4 <= (f == 1 ? 49152 : 32768 / f) &&
+        if (rows * 4 <= (f == 1 ? 49152 : (f == 2 ? 32768 : 8192)) &&
             occ_plane_lds_bytes(rows, occ_rows, f) <= 160 * 1024)
             return f;
     return 0;
@@ -2199,7 +2224,8 @@ static hipError_t launch_typed(const FbParams& p, const LaunchShape& shape, hipS
                 dim3 grid((tq + per_wg - 1) / per_wg, nb);
                 void (*fn)(FbParams, int) =
                     F == 4   ? k_occ_planes<4, 8192>
-                    : F == 2 ? k_occ_planes<2, 16384>
+                    : F == 2 ? (occ_plane_stride(p.lds_rows, 2) == 16384 ? k_occ_planes<2, 16384>
+                                                                         : k_occ_planes<2, 32768>)
                     : occ_plane_stride(p.lds_rows, 1) == 32768 ? k_occ_planes<1, 32768>
                                                                : k_occ_planes<1, 49152>;
                 hipLaunchKernelGGL(fn, grid, dim3(shape.occ_threads),

@@ -123,6 +123,27 @@ def test_large_graph_keeps_part_of_each_wave_in_registers_too():
     h.close()
 
 
+@pytest.mark.parametrize("frames,groups", [(1, 1), (1, 4), (2, 1), (2, 2), (2, 3)])
+def test_occupancy_kernel_with_one_or_two_frames_per_arc_record(frames, groups, monkeypatch):
+    # config 4's graph (5,056 padded rows: 32 KB planes in LDS): one frame per arc record, or
+    # two with the second pair of planes beyond 64 KB; odd lengths leave the last group half
+    # empty, and a length of 1 leaves a workgroup's later groups without any frame
+    monkeypatch.setenv("LFMMI_OCC_MULTI", str(frames))
+    monkeypatch.setenv("LFMMI_OCC_GROUPS", str(groups))
+    wl = workloads.make_workload(4, scale={"B": 5, "Tlo": 40, "Thi": 40})
+    lengths = np.array([37, 1, 24, 9, 40], dtype=wl["lengths"].dtype)
+    logits = wl["logits"].copy()
+    for b, Tb in enumerate(lengths):
+        logits[b, Tb:] = np.nan
+    h = binding.lfmmi_graph_create(wl["den"])
+    lz, gamma = oracle.forward_backward(wl["den"], logits, lengths, wl["leak"])
+    out = run_gpu(h, logits, lengths, wl["leak"])
+    check(*out, lz, gamma, "occupancy, %d frame(s) per record, %d group(s)" % (frames, groups))
+    for b, Tb in enumerate(lengths):
+        assert np.all(out[1][b, Tb:] == 0.0)
+    h.close()
+
+
 def test_wave_with_more_than_64_streamed_slices(monkeypatch):
     # two waves for 141 slices: each streams about 70 slices a frame, more than the
     # 64 whose ends (and hub flags) a wave keeps in the lanes of one register
