@@ -188,6 +188,7 @@ lfmmi_status pack_all(int32_t n, int32_t num_pdfs, const int64_t* state_off,
         tune.balance_banks = !h->wide && env_int("LFMMI_BALANCE", 1) != 0;
         tune.order_slots = !h->wide && env_int("LFMMI_ORDER", 1) != 0;
         tune.hub_slices = env_int("LFMMI_HUBS", 1) != 0;
+        tune.deal_occ = env_int("LFMMI_DEAL", 1) != 0;
 
         int waves = 1;
         for (int32_t g = 0; g < n; ++g)

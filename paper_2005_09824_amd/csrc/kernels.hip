@@ -1726,6 +1726,29 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             hv_r1[k] = pdf_first[hv_d[k] + 1];
         }
     }
+    // Where the sums of this lane's rows go among the row sums (a pdf's rows side by
+    // side), one place per slice of the wave: the variants with large planes (one
+    // workgroup per compute unit whatever they add to their LDS) keep the table behind
+    // the row sums, the others keep the wave's first kSlotsKept slices in registers
+    // and fetch the place of a later slice when it ends.
+    // lane l: one past the last slot of the wave's l-th slice (its last slice's from there
+    // on); the wave's first slot and one past its last
+    const int so_tab = s0 < s1 ? so[min(s0 + 1 + lane, s1)] : 0;
+    const int w0 = s0 < s1 ? so[s0] : 0, w1 = s0 < s1 ? so[s1] : 0;
+    constexpr bool kSlotsInLds = STRIDE >= 32768;
+    constexpr int kSlotsKept = kSlotsInLds ? 1 : 4;
+    const uint32_t slot_tab = kRowSum + (uint32_t)(F * occ_rows) * 4u;
+    uint32_t slot_r[kSlotsKept];
+    if constexpr (kSlotsInLds) {
+        slot_r[0] = 0;
+        for (int sl = s0; sl < s1; ++sl)  // read back by this wave only
+            lds_st(slot_tab + (uint32_t)(sl * 64 + lane) * 4u,
+                   __uint_as_float((uint32_t)row_slot[sl * 64 + lane]));
+    } else {
+#pragma unroll
+        for (int q = 0; q < kSlotsKept; ++q)
+            slot_r[q] = s0 < s1 ? (uint32_t)row_slot[min(s0 + q, s1 - 1) * 64 + lane] : 0u;
+    }
     // ... and the rows of the next group are fetched while this group's arcs are
     // gathered: kStageRows of each side and frame per thread (large planes, where one
     // workgroup has a compute unit to itself; uniform leak target only)
@@ -1832,17 +1855,6 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
         if constexpr (kAhead)
             if (ahead && t0 + F <= min(t_end, T)) fetch_rows(t0 + F);
 
-        auto one_slot = [&](const uint2 r, float* acc) {
-            const uint32_t xa = r.x & 0xffffu;
-            const uint32_t xb = kBHigh ? __builtin_amdgcn_alignbit(1u, r.x, 16u) : r.x >> 16;
-            const float w = __uint_as_float(r.y);
-#pragma unroll
-            for (int f = 0; f < F; ++f) {
-                const float a = lds_ld(xa + (uint32_t)(f * STRIDE));
-                const float bt = lds_ld(xb + ((uint32_t)((F + f) * STRIDE) - kBBase));
-                acc[f] = fmaf(w * bt, a, acc[f]);
-            }
-        };
         // emission value and frame scale of this thread's gradient entry, in flight
         // during the gathers
         const size_t group_at = ((size_t)b * p.T + (t0 - 1)) * P;
@@ -1856,44 +1868,101 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             more_e[j] = d < P ? p.emis[group_at + d] : 0.f;
         }
 
-        for (int sl = s0; sl < s1; ++sl) {
-            const int o0 = so[sl], o1 = so[sl + 1];
-            const uint32_t slot = (uint32_t)row_slot[sl * 64 + lane];  // where this row's sum goes
+        if (s0 < s1) {
+            // The wave's slices as one flat sequence of record pairs (slices are an even
+            // number of slots wide, so a pair never straddles two): kChunk pairs are being
+            // used while the kChunk after them load, across slice ends, so that a slice
+            // does not start with an exposed trip to L2. A load past the wave's last pair
+            // fetches that pair again, unused (a conditional 16-byte load would be split
+            // into four 4-byte ones). The gathers of kBatch pairs (16 reads) go out
+            // together and are waited for once; left to itself the compiler waits for
+            // every slot's reads before it issues the next slot's. Where a slice ends,
+            // the lane's sums go to its row's place among the row sums. Everything that
+            // steers the loop is wave-uniform and sits in scalar registers.
+            constexpr int kChunk = 4;
+            constexpr int kBatch = F == 1 ? 4 : (F == 2 ? 2 : 1);  // pairs per batch of gathers
+            static_assert(kBatch * 4 * F == 16 && kChunk % kBatch == 0, "16 reads per batch");
+            // (the end of the wave's k-th slice: out of a lane of so_tab, no memory access)
+            auto slice_end = [&](const int k) {
+                return k < 64 ? __builtin_amdgcn_readlane(so_tab, __builtin_amdgcn_readfirstlane(k))
+                              : so[min(s0 + k + 1, s1)];
+            };
+            const int q_last = (w1 >> 1) - 1;
+            int sl = s0;
+            int o_end = slice_end(0);
             float acc[F];
 #pragma unroll
             for (int f = 0; f < F; ++f) acc[f] = 0.f;
-            // chunks of kChunk record pairs, the next chunk loading while this one is used
-            // (a load past the end of the slice fetches its last pair again, unused:
-            // a conditional 16-byte load would be split into four 4-byte ones)
-            constexpr int kChunk = 4;
-            const int q_last = (o1 >> 1) - 1;
             uint4 cur[kChunk], nxt[kChunk];
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) cur[u] = recs[(size_t)min((o0 >> 1) + u, q_last) * 64];
-            for (int i = o0; i < o1; i += 2 * kChunk) {
+            for (int u = 0; u < kChunk; ++u) cur[u] = recs[(size_t)min((w0 >> 1) + u, q_last) * 64];
+            for (int i = w0; i < w1; i += 2 * kChunk) {
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u)
                     nxt[u] = recs[(size_t)min((i >> 1) + kChunk + u, q_last) * 64];
-                if (i + 2 * kChunk <= o1) {
 #pragma unroll
-                    for (int u = 0; u < kChunk; ++u) {
-                        one_slot(rec_lo(cur[u]), acc);
-                        one_slot(rec_hi(cur[u]), acc);
-                    }
-                } else {
+                for (int u0 = 0; u0 < kChunk; u0 += kBatch) {
+                    if (i + 2 * u0 >= w1) break;
+                    // (pairs past the wave's end repeat its last pair: reads in bounds, unused)
+                    float va[2 * kBatch][F], vb[2 * kBatch][F], w[2 * kBatch];
 #pragma unroll
-                    for (int u = 0; u < kChunk; ++u)
-                        if (i + 2 * u < o1) {  // widths are even
-                            one_slot(rec_lo(cur[u]), acc);
-                            one_slot(rec_hi(cur[u]), acc);
+                    for (int u = 0; u < kBatch; ++u) {
+#pragma unroll
+                        for (int hf = 0; hf < 2; ++hf) {
+                            const uint2 r = hf ? rec_hi(cur[u0 + u]) : rec_lo(cur[u0 + u]);
+                            const uint32_t xa = r.x & 0xffffu;
+                            const uint32_t xb =
+                                kBHigh ? __builtin_amdgcn_alignbit(1u, r.x, 16u) : r.x >> 16;
+                            w[2 * u + hf] = __uint_as_float(r.y);
+#pragma unroll
+                            for (int f = 0; f < F; ++f) {
+                                va[2 * u + hf][f] = lds_ld(xa + (uint32_t)(f * STRIDE));
+                                vb[2 * u + hf][f] = lds_ld(xb + ((uint32_t)((F + f) * STRIDE) - kBBase));
+                            }
                         }
+                    }
+                    {  // one wait for the 16: the values used first depend on those loaded last
+                        float* a = &va[0][0];
+                        float* b = &vb[0][0];
+                        asm volatile(""
+                                     : "+v"(a[0]), "+v"(b[0]), "+v"(a[1]), "+v"(b[1])
+                                     : "v"(a[2]), "v"(b[2]), "v"(a[3]), "v"(b[3]), "v"(a[4]), "v"(b[4]),
+                                       "v"(a[5]), "v"(b[5]), "v"(a[6]), "v"(b[6]), "v"(a[7]), "v"(b[7]));
+                    }
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        const int at = i + 2 * (u0 + u);  // first slot of this pair
+                        if (u > 0 && at >= w1) break;
+#pragma unroll
+                        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                            for (int f = 0; f < F; ++f)
+                                acc[f] = fmaf(w[2 * u + hf] * vb[2 * u + hf][f], va[2 * u + hf][f], acc[f]);
+                        if (at + 2 == o_end) {  // the slice ends with this pair
+                            const int k = sl - s0;
+                            uint32_t slot;
+                            if constexpr (kSlotsInLds) {
+                                slot = __float_as_uint(lds_ld(slot_tab + (uint32_t)(sl * 64 + lane) * 4u));
+                            } else {
+                                slot = slot_r[0];
+#pragma unroll
+                                for (int q = 1; q < kSlotsKept; ++q)
+                                    if (q == k) slot = slot_r[q];
+                                if (k >= kSlotsKept) slot = (uint32_t)row_slot[sl * 64 + lane];
+                            }
+#pragma unroll
+                            for (int f = 0; f < F; ++f) {
+                                lds_st(kRowSum + ((uint32_t)(f * occ_rows) + slot) * 4u, acc[f]);
+                                acc[f] = 0.f;
+                            }
+                            ++sl;
+                            o_end = slice_end(sl - s0);
+                        }
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u) cur[u] = nxt[u];
             }
-#pragma unroll
-            for (int f = 0; f < F; ++f)
-                lds_st(kRowSum + ((uint32_t)(f * occ_rows) + slot) * 4u, acc[f]);
         }
         __syncthreads();
         // a pdf's row sums lie side by side; a thread adds up those of a pdf with few rows
@@ -2161,7 +2230,10 @@ int occ_plane_frames(int rows, int occ_rows)
 
 size_t occ_plane_lds_bytes(int rows, int occ_rows, int frames)
 {
-    return 2 * (size_t)frames * occ_plane_stride(rows, frames) + (size_t)frames * occ_rows * 4;
+    // planes, row sums, and behind them (large planes only) the table of the rows' places
+    const int stride = occ_plane_stride(rows, frames);
+    return 2 * (size_t)frames * stride + (size_t)frames * occ_rows * 4 +
+           (stride >= 32768 ? (size_t)occ_rows * 4 : 0);
 }
 
 template <typename Real>

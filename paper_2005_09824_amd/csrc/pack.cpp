@@ -608,6 +608,141 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int32_t>
     }
 }
 
+// OCC ordering: deals every arc to a row of its pdf and a slot of that row.
+// pdf_of[r], len[r]: pdf and arc count of row r; ar: where the rows sit; pos_f /
+// pos_b: state -> position in the FWD / BWD numbering (the words the two gathers
+// of an arc read). For every half-slice, slot by slot: rows that must take an
+// arc in this slot (as many arcs left as slots) choose first, then the others;
+// a row takes an arc of its pdf whose two banks are still free in this slot, an
+// optional row rather none than one that conflicts; a forced row takes the arc
+// with the fewest conflicts, and then tries to have the rows it collides with
+// take other arcs (one level of re-choosing). Deterministic.
+void deal_occ_arcs(const ArcList& g, const std::vector<int32_t>& pdf_of,
+                   const std::vector<int32_t>& len, const Arrangement& ar,
+                   const std::vector<int32_t>& pos_f, const std::vector<int32_t>& pos_b,
+                   std::vector<int32_t>* prow, std::vector<int32_t>* nth)
+{
+    const int64_t A = g.num_arcs;
+    int32_t num_pdfs = 0;
+    for (int32_t d : pdf_of) num_pdfs = std::max(num_pdfs, d + 1);
+    for (int64_t a = 0; a < A; ++a) num_pdfs = std::max(num_pdfs, g.pdf[a] + 1);
+    std::vector<std::vector<int32_t>> pool(num_pdfs);  // arcs of a pdf not dealt yet
+    for (int64_t a = 0; a < A; ++a) pool[g.pdf[a]].push_back((int32_t)a);
+    std::vector<uint8_t> taken(A, 0);
+    auto bank_f = [&](int32_t a) { return pos_f[g.src[a]] % kBanks; };
+    auto bank_b = [&](int32_t a) { return pos_b[g.dst[a]] % kBanks; };
+    const int32_t halves = ar.num_slices * 2;
+    std::vector<std::vector<int32_t>> rows_of(halves);
+    for (int32_t r = 0; r < (int32_t)len.size(); ++r) rows_of[ar.pos[r] / kHalf].push_back(r);
+    std::vector<int32_t> need, order, chosen;
+    for (int32_t h = 0; h < halves; ++h) {
+        const std::vector<int32_t>& rows = rows_of[h];
+        if (rows.empty()) continue;
+        const int32_t W = ar.slice_width[h / 2];
+        need.assign(rows.size(), 0);
+        for (size_t i = 0; i < rows.size(); ++i) need[i] = len[rows[i]];
+        // the pools of this half-slice's pdfs without the arcs dealt so far
+        for (int32_t r : rows) {
+            std::vector<int32_t>& q = pool[pdf_of[r]];
+            q.erase(std::remove_if(q.begin(), q.end(), [&](int32_t a) { return taken[a] != 0; }),
+                    q.end());
+        }
+        for (int32_t j = 0; j < W; ++j) {
+            int32_t own_f[kBanks], own_b[kBanks];  // the row that holds a bank in this slot
+            std::fill(own_f, own_f + kBanks, -1);
+            std::fill(own_b, own_b + kBanks, -1);
+            chosen.assign(rows.size(), -1);
+            // a free arc of row i's pdf whose banks nobody holds (-1: none)
+            auto free_arc = [&](int32_t i) {
+                for (int32_t a : pool[pdf_of[rows[i]]])
+                    if (!taken[a] && own_f[bank_f(a)] < 0 && own_b[bank_b(a)] < 0) return a;
+                return (int32_t)-1;
+            };
+            auto take = [&](int32_t i, int32_t a) {
+                chosen[i] = a;
+                taken[a] = 1;
+                if (own_f[bank_f(a)] < 0) own_f[bank_f(a)] = i;
+                if (own_b[bank_b(a)] < 0) own_b[bank_b(a)] = i;
+            };
+            auto drop = [&](int32_t i) {
+                const int32_t a = chosen[i];
+                taken[a] = 0;
+                if (own_f[bank_f(a)] == i) own_f[bank_f(a)] = -1;
+                if (own_b[bank_b(a)] == i) own_b[bank_b(a)] = -1;
+                chosen[i] = -1;
+            };
+            order.resize(rows.size());
+            std::iota(order.begin(), order.end(), 0);
+            const int32_t slots_left = W - j;
+            std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+                const bool fx = need[x] >= slots_left, fy = need[y] >= slots_left;
+                return fx != fy ? fx : need[x] > need[y];
+            });
+            for (int32_t i : order) {
+                if (need[i] <= 0) continue;
+                const bool forced = need[i] >= slots_left;
+                int32_t a = free_arc(i);
+                if (a >= 0) {
+                    take(i, a);
+                    continue;
+                }
+                if (!forced) continue;  // rather an empty slot than a conflict
+                // every free arc of the pdf collides: try each with the rows it collides
+                // with (at most two) re-choosing; keep the first that leaves no conflict
+                bool settled = false;
+                int32_t fallback = -1;
+                for (int32_t cand : pool[pdf_of[rows[i]]]) {
+                    if (taken[cand]) continue;
+                    if (fallback < 0) fallback = cand;
+                    const int32_t l1 = own_f[bank_f(cand)], l2 = own_b[bank_b(cand)];
+                    int32_t blockers[2], nb = 0, old_arc[2];
+                    if (l1 >= 0) blockers[nb++] = l1;
+                    if (l2 >= 0 && l2 != l1) blockers[nb++] = l2;
+                    for (int q = 0; q < nb; ++q) {
+                        old_arc[q] = chosen[blockers[q]];
+                        drop(blockers[q]);
+                    }
+                    bool ok = own_f[bank_f(cand)] < 0 && own_b[bank_b(cand)] < 0;
+                    int32_t placed = 0;
+                    if (ok) {
+                        take(i, cand);
+                        for (; placed < nb; ++placed) {
+                            const int32_t alt = free_arc(blockers[placed]);
+                            if (alt < 0) break;
+                            take(blockers[placed], alt);
+                        }
+                        ok = placed == nb;
+                    }
+                    if (ok) {
+                        settled = true;
+                        break;
+                    }
+                    // back to where it was
+                    for (int32_t q = 0; q < placed; ++q) drop(blockers[q]);
+                    if (chosen[i] >= 0) drop(i);
+                    for (int q = 0; q < nb; ++q) take(blockers[q], old_arc[q]);
+                }
+                if (!settled && fallback >= 0) {
+                    // the arc with the fewest collisions
+                    int32_t best = fallback, best_cost = 3;
+                    for (int32_t cand : pool[pdf_of[rows[i]]]) {
+                        if (taken[cand]) continue;
+                        const int cost = (own_f[bank_f(cand)] >= 0) + (own_b[bank_b(cand)] >= 0);
+                        if (cost < best_cost) { best_cost = cost; best = cand; }
+                    }
+                    take(i, best);
+                }
+            }
+            for (size_t i = 0; i < rows.size(); ++i)
+                if (chosen[i] >= 0) {
+                    (*prow)[chosen[i]] = ar.pos[rows[i]];
+                    (*nth)[chosen[i]] = j;
+                    --need[i];
+                }
+        }
+    }
+}
+
 // Padding slots (w == 0) still gather: point each at a bank its half-wave does
 // not use in that slot (or, failing that, at an address another lane reads
 // anyway), so that padding never adds a bank conflict. fix_y: do the same for
@@ -998,16 +1133,35 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
             by[a] = ab.pos[g.dst[a]];
         }
         for (int32_t sl = 0; sl < ao.num_slices; ++sl) wo[sl] = ao.slice_width[sl];
-        if (tune.order_slots) order_slots(prow, bx, by, ao.num_slices, wo, &nth);
-        for (int64_t a = 0; a < A; ++a)
-            put(&out->ord[2], prow[a], nth[a], (uint32_t)af.pos[g.src[a]],
-                (uint32_t)ab.pos[g.dst[a]], w[a]);
+        const int32_t rf = af.num_slices * kLanes, rb = ab.num_slices * kLanes;
+        auto fill = [&](const std::vector<int32_t>& rows, const std::vector<int32_t>& slots,
+                        Ordering* o) {
+            for (int64_t a = 0; a < A; ++a)
+                put(o, rows[a], slots[a], (uint32_t)af.pos[g.src[a]], (uint32_t)ab.pos[g.dst[a]],
+                    w[a]);
+            if (tune.order_slots) retarget_padding(o, true, false, rf, rb);
+        };
+        if (tune.order_slots && tune.deal_occ) {
+            // two ways to place the arcs; the one whose gathers the bank model prices
+            // lower stays: the slots of each row ordered with the rows as they are, or
+            // rows and slots dealt together (arcs of a pdf may sit in any of its rows)
+            Ordering dealt = out->ord[2];
+            std::vector<int32_t> prow_d(prow), nth_d(nth);
+            order_slots(prow, bx, by, ao.num_slices, wo, &nth);
+            fill(prow, nth, &out->ord[2]);
+            deal_occ_arcs(g, pdf_of, len, ao, af.pos, ab.pos, &prow_d, &nth_d);
+            fill(prow_d, nth_d, &dealt);
+            if (gather_cycles(dealt, true) < gather_cycles(out->ord[2], true))
+                out->ord[2] = std::move(dealt);
+        } else {
+            if (tune.order_slots) order_slots(prow, bx, by, ao.num_slices, wo, &nth);
+            fill(prow, nth, &out->ord[2]);
+        }
     }
     if (tune.order_slots) {
         const int32_t rf = af.num_slices * kLanes, rb = ab.num_slices * kLanes;
         retarget_padding(&out->ord[0], tune.emission_conflicts, closing != 0, rf, num_pdfs);
         retarget_padding(&out->ord[1], tune.emission_conflicts, closing != 0, rb, num_pdfs);
-        retarget_padding(&out->ord[2], true, false, rf, rb);
     }
     out->ord[0].gather_cycles = gather_cycles(out->ord[0], tune.emission_conflicts);
     out->ord[1].gather_cycles = gather_cycles(out->ord[1], tune.emission_conflicts);

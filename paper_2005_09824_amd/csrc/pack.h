@@ -101,6 +101,7 @@ struct PackTuning {
     bool order_slots = true;          // order each row's arcs over its slots
     bool emission_conflicts = true;   // the emission gather can conflict (row not replicated)
     bool hub_slices = true;           // rows with far more arcs than the others get a slice each
+    bool deal_occ = true;             // OCC ordering: arcs dealt to rows and slots jointly
 };
 
 // per_arc_leak: fill the per-arc leak factors (required when init_prob is not

@@ -134,6 +134,29 @@ def test_slot_ordering_lowers_modelled_bank_conflicts(monkeypatch):
     tuned.close(); plain.close()
 
 
+@pytest.mark.parametrize("which", ["den", "hmm"])
+def test_occupancy_arcs_dealt_to_rows_and_slots_keep_every_arc(which, monkeypatch):
+    # the occupancy ordering may place an arc in any row of its pdf: both placements hold every
+    # arc once, in a row of its pdf, and the one that is kept is never the dearer of the two
+    if which == "den":
+        g = workloads.make_workload(2, scale={"B": 2, "Tlo": 5, "Thi": 6})["den"]
+    else:
+        g = workloads.make_workload(6, scale={"B": 2, "Tlo": 5, "Thi": 6})["den"]
+    both = binding.lfmmi_graph_pack(g)
+    monkeypatch.setenv("LFMMI_DEAL", "0")
+    ordered = binding.lfmmi_graph_pack(g)
+    for h in (both, ordered):
+        got, want, _ = _unpack(h, 0, g)
+        assert got[2] == want
+    a = binding.lfmmi_graph_ordering_info(both, 0, 2)
+    b = binding.lfmmi_graph_ordering_info(ordered, 0, 2)
+    assert a["total_slots"] == b["total_slots"] and a["rows"] == b["rows"]
+    assert 4 * a["total_slots"] <= a["gather_cycles"] <= b["gather_cycles"]
+    if which == "den":  # random pdfs on the arcs: the joint placement wins clearly
+        assert a["gather_cycles"] <= 0.9 * b["gather_cycles"], (a, b)
+    both.close(); ordered.close()
+
+
 def test_graph_with_no_arcs_and_isolated_states():
     g = {"num_states": 3, "num_pdfs": 2, "src": np.zeros(0, np.int32), "dst": np.zeros(0, np.int32),
          "pdf": np.zeros(0, np.int32), "logw": np.zeros(0, np.float32),
