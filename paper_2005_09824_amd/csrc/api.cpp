@@ -674,10 +674,12 @@ void fill_params(lfmmi_graph* h, const CallLayout& lay, unsigned char* ws,
     shape.occ_threads = h->occ_waves * kLanes;
     shape.occ_frames = std::max(1, env_int("LFMMI_OCC_FRAMES", 4));
     // the plane-layout occupancy kernel (several frames per arc record) when it fits
-    shape.occ_multi = h->wide ? 0 : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b), h->max_rows_occ);
     {
-        const int forced = env_int("LFMMI_OCC_MULTI", -1);
-        if (forced == 0 || (forced > 0 && forced <= shape.occ_multi)) shape.occ_multi = forced;
+        const int most = env_int("LFMMI_OCC_MULTI", 4);  // 0: the frame-at-a-time kernel
+        shape.occ_multi = h->wide || most <= 0
+                              ? 0
+                              : occ_plane_frames(std::max(h->max_rows_f, h->max_rows_b),
+                                                 h->max_rows_occ, most);
     }
     // groups of frames per workgroup: with one frame per group a workgroup takes four,
     // with two frames of large planes two, which spreads its start-up cost and lets it

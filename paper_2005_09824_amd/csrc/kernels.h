@@ -149,7 +149,7 @@ int rec_hybrid_slots(bool wide, bool has_wb, bool yrep, bool hubs, int map /* 1:
 int rec_grouped_slots(bool wide, bool has_wb, int max_wave_slots, int threads);
 int rec_grouped_max_rows(int threads);
 size_t occ_lds_bytes(int rows_a, int rows_b, int occ_rows, bool wide);
-int occ_plane_frames(int rows, int occ_rows);
+int occ_plane_frames(int rows, int occ_rows, int most);
 size_t occ_plane_lds_bytes(int rows, int occ_rows, int frames);
 
 }  // namespace lfmmi

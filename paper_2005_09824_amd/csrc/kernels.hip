@@ -1874,14 +1874,14 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             // used while the kChunk after them load, across slice ends, so that a slice
             // does not start with an exposed trip to L2. A load past the wave's last pair
             // fetches that pair again, unused (a conditional 16-byte load would be split
-            // into four 4-byte ones). The gathers of kBatch pairs (16 reads) go out
+            // into four 4-byte ones). The gathers of kBatch slots (16 reads) go out
             // together and are waited for once; left to itself the compiler waits for
             // every slot's reads before it issues the next slot's. Where a slice ends,
             // the lane's sums go to its row's place among the row sums. Everything that
             // steers the loop is wave-uniform and sits in scalar registers.
             constexpr int kChunk = 4;
-            constexpr int kBatch = F == 1 ? 4 : (F == 2 ? 2 : 1);  // pairs per batch of gathers
-            static_assert(kBatch * 4 * F == 16 && kChunk % kBatch == 0, "16 reads per batch");
+            constexpr int kBatch = 8 / F;  // slots per batch of gathers
+            static_assert((2 * kChunk) % kBatch == 0, "a chunk is a whole number of batches");
             // (the end of the wave's k-th slice: out of a lane of so_tab, no memory access)
             auto slice_end = [&](const int k) {
                 return k < 64 ? __builtin_amdgcn_readlane(so_tab, __builtin_amdgcn_readfirstlane(k))
@@ -1901,44 +1901,37 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 for (int u = 0; u < kChunk; ++u)
                     nxt[u] = recs[(size_t)min((i >> 1) + kChunk + u, q_last) * 64];
 #pragma unroll
-                for (int u0 = 0; u0 < kChunk; u0 += kBatch) {
-                    if (i + 2 * u0 >= w1) break;
+                for (int v0 = 0; v0 < 2 * kChunk; v0 += kBatch) {  // v: slot of the chunk
+                    if (i + v0 >= w1) break;
                     // (pairs past the wave's end repeat its last pair: reads in bounds, unused)
-                    float va[2 * kBatch][F], vb[2 * kBatch][F], w[2 * kBatch];
+                    float va[kBatch][F], vb[kBatch][F], w[kBatch];
 #pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
+                    for (int v = 0; v < kBatch; ++v) {
+                        const uint4 pr = cur[(v0 + v) >> 1];
+                        const uint2 r = ((v0 + v) & 1) ? rec_hi(pr) : rec_lo(pr);
+                        const uint32_t xa = r.x & 0xffffu;
+                        const uint32_t xb = kBHigh ? __builtin_amdgcn_alignbit(1u, r.x, 16u) : r.x >> 16;
+                        w[v] = __uint_as_float(r.y);
 #pragma unroll
-                        for (int hf = 0; hf < 2; ++hf) {
-                            const uint2 r = hf ? rec_hi(cur[u0 + u]) : rec_lo(cur[u0 + u]);
-                            const uint32_t xa = r.x & 0xffffu;
-                            const uint32_t xb =
-                                kBHigh ? __builtin_amdgcn_alignbit(1u, r.x, 16u) : r.x >> 16;
-                            w[2 * u + hf] = __uint_as_float(r.y);
-#pragma unroll
-                            for (int f = 0; f < F; ++f) {
-                                va[2 * u + hf][f] = lds_ld(xa + (uint32_t)(f * STRIDE));
-                                vb[2 * u + hf][f] = lds_ld(xb + ((uint32_t)((F + f) * STRIDE) - kBBase));
-                            }
+                        for (int f = 0; f < F; ++f) {
+                            va[v][f] = lds_ld(xa + (uint32_t)(f * STRIDE));
+                            vb[v][f] = lds_ld(xb + ((uint32_t)((F + f) * STRIDE) - kBBase));
                         }
                     }
-                    {  // one wait for the 16: the values used first depend on those loaded last
+                    {  // one wait for the batch: the values used first depend on all the others
                         float* a = &va[0][0];
                         float* b = &vb[0][0];
-                        asm volatile(""
-                                     : "+v"(a[0]), "+v"(b[0]), "+v"(a[1]), "+v"(b[1])
-                                     : "v"(a[2]), "v"(b[2]), "v"(a[3]), "v"(b[3]), "v"(a[4]), "v"(b[4]),
-                                       "v"(a[5]), "v"(b[5]), "v"(a[6]), "v"(b[6]), "v"(a[7]), "v"(b[7]));
+#pragma unroll
+                        for (int j = 1; j < kBatch * F; ++j)
+                            asm volatile("" : "+v"(a[0]), "+v"(b[0]) : "v"(a[j]), "v"(b[j]));
                     }
 #pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        const int at = i + 2 * (u0 + u);  // first slot of this pair
-                        if (u > 0 && at >= w1) break;
+                    for (int v = 0; v < kBatch; ++v) {
+                        const int at = i + v0 + v;  // this slot
+                        if (v > 0 && at >= w1) break;
 #pragma unroll
-                        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                            for (int f = 0; f < F; ++f)
-                                acc[f] = fmaf(w[2 * u + hf] * vb[2 * u + hf][f], va[2 * u + hf][f], acc[f]);
-                        if (at + 2 == o_end) {  // the slice ends with this pair
+                        for (int f = 0; f < F; ++f) acc[f] = fmaf(w[v] * vb[v][f], va[v][f], acc[f]);
+                        if (((v0 + v) & 1) && at + 1 == o_end) {  // the slice ends with this pair
                             const int k = sl - s0;
                             uint32_t slot;
                             if constexpr (kSlotsInLds) {
@@ -2214,15 +2207,15 @@ static int occ_plane_stride(int rows, int frames)
 {
     if (frames == 1) return rows * 4 > 32768 ? 49152 : 32768;
     if (frames == 2) return rows * 4 > 16384 ? 32768 : 16384;
-    return 32768 / frames;
+    return 8192;
 }
 
 // Frames per record of the plane-layout occupancy kernel for this many state
 // rows and OCC rows (0: they do not fit its LDS map).
-int occ_plane_frames(int rows, int occ_rows)
+int occ_plane_frames(int rows, int occ_rows, int most)
 {
     for (int f : {4, 2, 1})
-        if (rows * 4 <= (f == 1 ? 49152 : (f == 2 ? 32768 : 8192)) &&
+        if (f <= most && rows * 4 <= (f == 1 ? 49152 : (f == 2 ? 32768 : 8192)) &&
             occ_plane_lds_bytes(rows, occ_rows, f) <= 160 * 1024)
             return f;
     return 0;
