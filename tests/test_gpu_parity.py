@@ -144,6 +144,24 @@ def test_occupancy_kernel_with_one_or_two_frames_per_arc_record(frames, groups, 
     h.close()
 
 
+def test_occupancy_wave_with_more_slices_than_it_keeps_places_for():
+    # 2,500 pdfs on a 1,500-state graph: 40 slices of occupancy rows for 8 waves, five each;
+    # the four-frame kernel keeps the places of a wave's first four slices in registers and
+    # fetches the fifth's when that slice ends
+    rng = np.random.default_rng(5)
+    g = workloads.random_den_graph(rng, 1500, 19, 2500, 0.5, "uniform")
+    lengths = np.array([23, 9, 16], np.int32)
+    x = rng.normal(0, 2, (3, 23, 2500)).astype(np.float32)
+    for b, Tb in enumerate(lengths):
+        x[b, Tb:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    info = binding.lfmmi_graph_ordering_info(h, 0, 2)
+    assert info["waves"] == 8 and info["slices"] >= 5 * 8
+    lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
+    check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "five occupancy slices per wave")
+    h.close()
+
+
 def test_wave_with_more_than_64_streamed_slices(monkeypatch):
     # two waves for 141 slices: each streams about 70 slices a frame, more than the
     # 64 whose ends (and hub flags) a wave keeps in the lanes of one register
