@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # WRITE_SIZE scaled by a plain copy of known size (profiles/hbm_traffic_<workload>.txt)
 # (e2e_num_den: the denominator's recursion, the kernel the roofline object describes)
 REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6, "biphone_10k": 4245.5e6, "long_unequal_5k": 1224.1e6,
-                     "e2e_num_den": 641.8e6, "hmm_den_2k": 345.6e6}
+                     "e2e_num_den": 641.8e6, "hmm_den_2k": 345.6e6, "wsj_den_7398": 2347.2e6}
 
 
 def main():
