@@ -162,6 +162,26 @@ def test_occupancy_wave_with_more_slices_than_it_keeps_places_for():
     h.close()
 
 
+def test_largest_graph_the_library_takes():
+    # 16,384 states, the limit: state vectors of 64 KB each, streamed arcs, the
+    # frame-at-a-time occupancy kernel; one state more is refused when the graph is made
+    rng = np.random.default_rng(99)
+    g = workloads.random_den_graph(rng, 16384, 3, 200, 0.5, "uniform")
+    lengths = np.array([11, 6], np.int32)
+    x = rng.normal(0, 2, (2, 11, 200)).astype(np.float32)
+    x[1, 6:] = np.nan
+    h = binding.lfmmi_graph_create(g)
+    info = binding.lfmmi_graph_ordering_info(h, 0, 0)
+    assert info["rows"] == 16384 and info["register_slots"] == 0
+    lz, gamma = oracle.forward_backward(g, x, lengths, 1e-5)
+    check(*run_gpu(h, x, lengths, 1e-5), lz, gamma, "16384 states")
+    h.close()
+    g2 = workloads.random_den_graph(rng, 16385, 2, 200, 0.5, "uniform")
+    with pytest.raises(binding.LfmmiError) as err:
+        binding.lfmmi_graph_create(g2)
+    assert "16384" in str(err.value)
+
+
 def test_wave_with_more_than_64_streamed_slices(monkeypatch):
     # two waves for 141 slices: each streams about 70 slices a frame, more than the
     # 64 whose ends (and hub flags) a wave keeps in the lanes of one register
