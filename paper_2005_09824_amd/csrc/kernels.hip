@@ -509,6 +509,7 @@ struct RecRegs {
     static_assert(kStageAt % 2 == 0 && (kStageAt == 0 || kStageAt < NSLOT - kTailSlots),
                   "every wave reaches it");
     static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
+    static_assert(NSLOT <= 64, "one bit per resident slot in the 64-bit slice-end and hub masks");
 
     // Packed slots (the hybrid): both addresses of a slot in one register, taken apart
     // again in every step by two instructions; two registers per slot instead of
@@ -1066,6 +1067,7 @@ struct RecGrouped {
     static constexpr int kStageAt = NSLOT - kTailSlots > 4 ? 4 : 0;
     static constexpr uint32_t kZeroX = kRegX1 - kRB;  // byte offset of the zero inside an X buffer
     static_assert(NSLOT % 2 == 0 && kPrefetch % 2 == 0, "slots are handled in pairs");
+    static_assert(NSLOT <= 64, "one bit per resident slot in the 64-bit slice-end mask");
 
     uint32_t xa[NSLOT];  // byte address of the gathered state value inside X0
     float wr[NSLOT];     // arc weight; closing slots: the row's leak-dot weight
