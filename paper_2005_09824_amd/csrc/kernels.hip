@@ -1869,6 +1869,16 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             const int d = tid + (j + 1) * nthreads;
             more_e[j] = d < P ? p.emis[group_at + d] : 0.f;
         }
+        // ... and those of the (pdf, frame) pairs this wave adds up with all its lanes
+        float hv_e[kHeavyKept], hv_c[kHeavyKept];
+#pragma unroll
+        for (int k = 0; k < kHeavyKept; ++k) {
+            const int u = wave + k * nwaves;
+            const int f = u % F;
+            const bool on = u < heavy_n * F && t0 + f <= T;
+            hv_e[k] = on ? p.emis[group_at + (size_t)f * P + hv_d[k]] : 0.f;
+            hv_c[k] = on ? cfac[t0 + f] : 0.f;
+        }
 
         if (s0 < s1) {
             // The wave's slices as one flat sequence of record pairs (slices are an even
@@ -2021,6 +2031,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             const int t = t0 + f;
             if (t > T) continue;  // zeroed above
             int d = 0, r0 = 0, r1 = 0;
+            float e = 0.f, c = 0.f;
             if (k < kHeavyKept) {
 #pragma unroll
                 for (int q = 0; q < kHeavyKept; ++q)
@@ -2028,11 +2039,15 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                         d = hv_d[q];
                         r0 = hv_r0[q];
                         r1 = hv_r1[q];
+                        e = hv_e[q];
+                        c = hv_c[q];
                     }
             } else {
                 d = heavy[h];
                 r0 = pdf_first[d];
                 r1 = pdf_first[d + 1];
+                e = p.emis[group_at + (size_t)f * P + d];
+                c = cfac[t];
             }
             float sum = 0.f;
             for (int r = r0 + lane; r < r1; r += 64)
@@ -2040,8 +2055,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             sum = wave_sum_uniform(sum);
             if (lane == 0) {
                 float* g = p.grad + group_at + (size_t)f * P + d;
-                const float c = cfac[t];
-                const float v = c == 0.f ? 0.f : p.grad_scale * c * p.emis[group_at + (size_t)f * P + d] * sum;
+                const float v = c == 0.f ? 0.f : p.grad_scale * c * e * sum;
                 *g = p.accumulate ? *g + v : v;
             }
         }

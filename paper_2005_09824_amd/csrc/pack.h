@@ -19,7 +19,7 @@
 namespace lfmmi {
 
 constexpr int kLanes = 64;
-constexpr int kHeavyPdfRows = 64;  // OCC: more rows than this and a wave adds them up
+constexpr int kHeavyPdfRows = 24;  // OCC: more rows than this and a wave adds them up
 constexpr int kMaxWaves = 16;
 constexpr int kMaxIndex = 16384;  // x / y index * 4 must fit 16 bits
 
