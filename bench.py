@@ -33,6 +33,41 @@ REC_TRAFFIC_BYTES = {"wsj_mono_2k": 362.4e6, "biphone_10k": 4245.5e6, "long_uneq
                      "e2e_num_den": 641.8e6, "hmm_den_2k": 345.6e6, "wsj_den_7398": 2347.2e6}
 
 
+def phase_timers(config, torch, binding, workloads):
+    """Clocks per phase of k_occ_planes (thread 0 of every workgroup, s_memtime), from the
+    counters a library built with -DLFMMI_PHASE_TIMERS keeps."""
+    import ctypes
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    if not hasattr(lib, "lfmmi_phase_timers_read"):
+        print("bench.py: the library was not built with -DLFMMI_PHASE_TIMERS", file=sys.stderr)
+        return 2
+    os.environ["LFMMI_BUCKETS"] = "1"
+    wl = workloads.make_workload(config)
+    x = torch.from_numpy(wl["logits"]).cuda()
+    B, T, P = x.shape
+    h = binding.lfmmi_graph_create(wl["den"])
+    objf = torch.empty(B, device="cuda")
+    grad = torch.empty((B, T, P), device="cuda")
+    status = torch.zeros(B, dtype=torch.int32, device="cuda")
+    out = (ctypes.c_ulonglong * 16)()
+    for k in range(4):  # the last call is the one that is read
+        if k == 3 and lib.lfmmi_phase_timers_read(out, 1) != 0:
+            return 1
+        binding.lfmmi_forward_backward(h, x, wl["lengths"], wl["leak"], 1.0, False, objf, grad, status)
+    if lib.lfmmi_phase_timers_read(out, 1) != 0:
+        return 1
+    names = ["start of the workgroup", "scales of the group", "barrier", "staging", "barrier",
+             "gathers", "barrier", "sums, pdfs with few rows", "sums, pdfs with many rows"]
+    v = list(out)
+    total = float(sum(v[:9]))
+    print("%s: %d workgroups, %d frame groups; clocks of thread 0 per frame group" %
+          (wl["name"], v[14], v[15]))
+    for i, n in enumerate(names):
+        print("  %-28s %9.0f  %5.1f %%" % (n, v[i] / max(v[15], 1), 100.0 * v[i] / max(total, 1.0)))
+    h.close()
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +80,10 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run plain device-to-device copies of BYTES (to calibrate the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--phase-timers", action="store_true",
+                    help="one call with the whole batch as one launch on a library built with "
+                         "-DLFMMI_PHASE_TIMERS: where a frame group of the occupancy kernel "
+                         "spends its clocks; prints a table and exits")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; sequences are independent, so "
@@ -69,6 +108,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes": n * 4, "copies": 4}))
         return 0
+    if args.phase_timers:
+        return phase_timers(args.config, torch, binding, workloads)
     wl = workloads.make_workload(args.config)
     lengths, leak = wl["lengths"], wl["leak"]
     frames = int(lengths.sum())

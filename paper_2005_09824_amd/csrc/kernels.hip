@@ -1650,9 +1650,30 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 // adds the row sums of pdf d in frame f and writes that gradient entry: the F
 // gradient rows of a group are contiguous, so the write is coalesced.
 // ---------------------------------------------------------------------------
+// Phase timers (builds with -DLFMMI_PHASE_TIMERS only; the library as shipped carries
+// none of this): thread 0 of every workgroup adds the clocks between two marks to a
+// counter per phase, which lfmmi_phase_timers_read() copies out.
+#ifdef LFMMI_PHASE_TIMERS
+__device__ unsigned long long g_phase_clocks[16];
+#define LFMMI_MARK_BEGIN unsigned long long mark_last_ = __builtin_amdgcn_s_memtime();
+#define LFMMI_MARK(i)                                                              \
+    {                                                                              \
+        const unsigned long long mark_now_ = __builtin_amdgcn_s_memtime();         \
+        if (threadIdx.x == 0) atomicAdd(&g_phase_clocks[i], mark_now_ - mark_last_); \
+        mark_last_ = mark_now_;                                                    \
+    }
+#define LFMMI_COUNT(i) \
+    if (threadIdx.x == 0) atomicAdd(&g_phase_clocks[i], 1ull);
+#else
+#define LFMMI_MARK_BEGIN
+#define LFMMI_MARK(i)
+#define LFMMI_COUNT(i)
+#endif
+
 template <int F, int STRIDE>
 __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_wg)
 {
+    LFMMI_MARK_BEGIN
     // Plane offsets ride in the 16-bit immediate of the ds instruction. Where the XB
     // planes lie beyond 64 KB (two frames of 32 KB planes), the record's XB offset is
     // taken out of its upper half together with a 1 above it (64 KB + offset, one
@@ -1778,6 +1799,8 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
     const int t_end = min(t_begin + groups_per_wg * F - 1, p.T);
     if constexpr (kAhead)
         if (ahead && t_begin <= min(t_end, T)) fetch_rows(t_begin);
+    LFMMI_MARK(0)  // start of the workgroup: descriptors, tables
+    LFMMI_COUNT(14)
     for (int t0 = t_begin; t0 <= t_end; t0 += F) {
         if (t0 > T) {  // nothing but padding rows from here on
             if (!p.accumulate)
@@ -1803,7 +1826,9 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             invb[f] = ok ? 1.f / nb : 0.f;
             cb[f] = eps * sb * invb[f];
         }
+        LFMMI_MARK(1)  // the group's scales
         __syncthreads();  // the previous group's gathers and row-sum reads are done
+        LFMMI_MARK(2)
         // staging: two rows per thread and side in flight, all loads (alpha and beta)
         // issued before any is used
         const int rows_max = ahead ? 0 : rows_most;
@@ -1853,7 +1878,9 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 }
             }
         }
+        LFMMI_MARK(3)  // staging
         __syncthreads();
+        LFMMI_MARK(4)
         if constexpr (kAhead)
             if (ahead && t0 + F <= min(t_end, T)) fetch_rows(t0 + F);
 
@@ -1969,7 +1996,10 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 for (int u = 0; u < kChunk; ++u) cur[u] = nxt[u];
             }
         }
+        LFMMI_MARK(5)  // gathers
         __syncthreads();
+        LFMMI_MARK(6)
+        LFMMI_COUNT(15)
         // a pdf's row sums lie side by side; a thread adds up those of a pdf with few rows
         auto few_rows = [&](const int f, const int r0, const int r1) {
             const uint32_t at = kRowSum + (uint32_t)(f * occ_rows + r0) * 4u;
@@ -2025,6 +2055,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
             const float v = c == 0.f ? 0.f : p.grad_scale * c * e * sum;
             *g = p.accumulate ? *g + v : v;
         }
+        LFMMI_MARK(7)  // sums of the pdfs with few rows
         // pdfs with many rows: one wave per pdf and frame, lanes striding over the rows
         for (int u = wave, k = 0; u < heavy_n * F; u += nwaves, ++k) {
             const int h = u / F, f = u - h * F;
@@ -2059,6 +2090,7 @@ __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_
                 *g = p.accumulate ? *g + v : v;
             }
         }
+        LFMMI_MARK(8)  // sums of the pdfs with many rows
     }
 }
 
@@ -2433,3 +2465,21 @@ hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
 }
 
 }  // namespace lfmmi
+
+#ifdef LFMMI_PHASE_TIMERS
+// out[0..8]: clocks per phase of k_occ_planes summed over the workgroups since the
+// last reset; out[14]: workgroups, out[15]: frame groups. Synchronises the device.
+extern "C" int lfmmi_phase_timers_read(unsigned long long out[16], int reset)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return 1;
+    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(lfmmi::g_phase_clocks), sizeof(unsigned long long) * 16) !=
+        hipSuccess)
+        return 2;
+    if (reset) {
+        const unsigned long long zero[16] = {};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(lfmmi::g_phase_clocks), zero, sizeof zero) != hipSuccess)
+            return 3;
+    }
+    return 0;
+}
+#endif
