@@ -608,6 +608,10 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int32_t>
     }
 }
 
+// (graphs with fewer arcs keep the ordered slots: the per-utterance graphs of a batch
+// are packed at every call of the trainer, and have little to gain)
+constexpr int64_t kDealMinArcs = 4096;
+
 // OCC ordering: deals every arc to a row of its pdf and a slot of that row.
 // pdf_of[r], len[r]: pdf and arc count of row r; ar: where the rows sit; pos_f /
 // pos_b: state -> position in the FWD / BWD numbering (the words the two gathers
@@ -1141,7 +1145,7 @@ std::string pack_graph(const ArcList& g, int32_t num_pdfs, int rec_waves, int oc
                     w[a]);
             if (tune.order_slots) retarget_padding(o, true, false, rf, rb);
         };
-        if (tune.order_slots && tune.deal_occ) {
+        if (tune.order_slots && tune.deal_occ && A >= kDealMinArcs) {
             // two ways to place the arcs; the one whose gathers the bank model prices
             // lower stays: the slots of each row ordered with the rows as they are, or
             // rows and slots dealt together (arcs of a pdf may sit in any of its rows)
