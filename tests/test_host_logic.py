@@ -390,3 +390,14 @@ def test_packer_finds_graphs_whose_pdf_is_a_function_of_the_entered_state(monkey
     h = binding.lfmmi_graph_pack_batch(mixed)
     assert binding.lfmmi_graph_info(h)["emission_by_state"] == 0
     h.close()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU is the whole target: the command says so and exits before it touches a device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
