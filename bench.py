@@ -49,7 +49,7 @@ def phase_timers(config, torch, binding, workloads):
     objf = torch.empty(B, device="cuda")
     grad = torch.empty((B, T, P), device="cuda")
     status = torch.zeros(B, dtype=torch.int32, device="cuda")
-    out = (ctypes.c_ulonglong * 16)()
+    out = (ctypes.c_ulonglong * 81)()
     for k in range(4):  # the last call is the one that is read
         if k == 3 and lib.lfmmi_phase_timers_read(out, 1) != 0:
             return 1
@@ -64,6 +64,21 @@ def phase_timers(config, torch, binding, workloads):
           (wl["name"], v[14], v[15]))
     for i, n in enumerate(names):
         print("  %-28s %9.0f  %5.1f %%" % (n, v[i] / max(v[15], 1), 100.0 * v[i] / max(total, 1.0)))
+    steps = v[80]
+    if steps:
+        info = binding.lfmmi_graph_ordering_info
+        slots = [[0] * 16, [0] * 16]
+        for o in (0, 1):
+            d = binding.lfmmi_graph_ordering_copy(h, 0, o)
+            for w in range(d["waves"]):
+                slots[o][w] = int(d["slice_off"][d["wave_first"][w + 1]] - d["slice_off"][d["wave_first"][w]])
+        print("k_rec, arcs in registers: clocks per step and wave (mean over both directions; "
+              "%d steps); slots of the wave in the alpha / beta ordering" % steps)
+        print("  wave   head  slots   tail   wait at the barrier   total   slots alpha/beta")
+        for w in range(16):
+            c = [v[16 + 4 * w + q] / steps for q in range(4)]
+            print("  %4d %6.0f %6.0f %6.0f %6.0f %21.0f   %d/%d" %
+                  (w, c[0], c[1], c[2], c[3], sum(c), slots[0][w], slots[1][w]))
     h.close()
     return 0
 

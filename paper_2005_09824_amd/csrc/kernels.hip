@@ -466,6 +466,46 @@ __device__ __forceinline__ Real lds_ldr(uint32_t addr)
         return *reinterpret_cast<const lds_float_t*>(static_cast<uintptr_t>(addr));
 }
 
+// Phase timers (builds with -DLFMMI_PHASE_TIMERS only; the library as shipped carries
+// none of this). k_occ_planes: thread 0 of every workgroup adds the clocks between two
+// marks to a counter per phase. Register-resident k_rec: every wave keeps the clocks of
+// the four phases of a step in scalar registers and adds them to the counters of its
+// wave number when its sequence is done. lfmmi_phase_timers_read() copies them out.
+#ifdef LFMMI_PHASE_TIMERS
+__device__ unsigned long long g_phase_clocks[16];
+__device__ unsigned long long g_rec_clocks[16 * 4 + 1];  // [wave][phase], steps
+#define LFMMI_REC_TIMERS unsigned long long rec_clk[4] = {0, 0, 0, 0}, rec_last = 0;
+#define LFMMI_REC_BEGIN rec_last = __builtin_amdgcn_s_memtime();
+#define LFMMI_REC_MARK(i)                                                  \
+    {                                                                      \
+        const unsigned long long mark_now_ = __builtin_amdgcn_s_memtime(); \
+        rec_clk[i] += mark_now_ - rec_last;                                \
+        rec_last = mark_now_;                                              \
+    }
+#define LFMMI_REC_END(wave, lane, steps)                                              \
+    if ((lane) == 0 && (wave) < 16) {                                                 \
+        for (int q_ = 0; q_ < 4; ++q_) atomicAdd(&g_rec_clocks[(wave) * 4 + q_], rec_clk[q_]); \
+        if ((wave) == 0) atomicAdd(&g_rec_clocks[64], (unsigned long long)(steps));   \
+    }
+#define LFMMI_MARK_BEGIN unsigned long long mark_last_ = __builtin_amdgcn_s_memtime();
+#define LFMMI_MARK(i)                                                              \
+    {                                                                              \
+        const unsigned long long mark_now_ = __builtin_amdgcn_s_memtime();         \
+        if (threadIdx.x == 0) atomicAdd(&g_phase_clocks[i], mark_now_ - mark_last_); \
+        mark_last_ = mark_now_;                                                    \
+    }
+#define LFMMI_COUNT(i) \
+    if (threadIdx.x == 0) atomicAdd(&g_phase_clocks[i], 1ull);
+#else
+#define LFMMI_REC_TIMERS
+#define LFMMI_REC_BEGIN
+#define LFMMI_REC_MARK(i)
+#define LFMMI_REC_END(wave, lane, steps)
+#define LFMMI_MARK_BEGIN
+#define LFMMI_MARK(i)
+#define LFMMI_COUNT(i)
+#endif
+
 // Emission staging passes of the variant for workgroups of up to NT threads.
 __host__ __device__ constexpr int stage_passes(bool yrep, int nt)
 {
@@ -532,6 +572,7 @@ struct RecRegs {
     // slice; one past the wave's last slot
     int so_tab, stream_end;
 
+    LFMMI_REC_TIMERS
     // per-step pointers, moved by one frame after every step
     const float* e2;  // emission row loaded during this step (used two steps on)
     Real* trow;       // trellis row written by this step
@@ -594,6 +635,7 @@ struct RecRegs {
                                          const uint64_t hub_bits, const int32_t* hub,
                                          const uint4* recs_uniform)
     {
+        LFMMI_REC_BEGIN
         // PAR = k & 1: read X/Y buffer (PAR ? 0 : 1), write buffer (PAR ? 1 : 0)
         constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
         // Y addresses in ya[] are absolute addresses inside Y0; Y1 is 32 KB further
@@ -638,6 +680,7 @@ struct RecRegs {
         }
         const Real c = eps * Sd * inv;
         const Real cb = HAS_WB ? c : c * bconst;
+        LFMMI_REC_MARK(0)  // head: last step's partial sums into this step's scalars
 
         Real acc1 = 0, acc2 = 0, n = 0, s = 0;
         uint64_t left = mask;
@@ -828,6 +871,7 @@ struct RecRegs {
                 }
             }
         }
+        LFMMI_REC_MARK(1)  // the slots
         __builtin_amdgcn_s_setprio(3);  // the serial end of this step and start of the next
         if constexpr (HAS_WB) {
             // both wave sums in one reduction: lane 31 ends up with n, lane 63 with s
@@ -841,7 +885,9 @@ struct RecRegs {
         trow += tstep;
         sN += sstep;
         sS += sstep;
+        LFMMI_REC_MARK(2)  // tail: wave sum, partial sum to LDS
         __syncthreads();
+        LFMMI_REC_MARK(3)  // wait for the other waves
     }
 
     __device__ __forceinline__ void run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
@@ -998,6 +1044,7 @@ struct RecRegs {
         }
         if (k <= T) step<1>(k, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
                     sl_stream, s1, first + nsl, so, hub_bits, hub, rec_pairs(p, od, 0));
+        LFMMI_REC_END(wave, lane, T)
 
         // ---- last scalars and the closing dot product
         {
@@ -1650,26 +1697,6 @@ __global__ void __launch_bounds__(1024) k_occ(FbParams p, int frames_per_wg)
 // adds the row sums of pdf d in frame f and writes that gradient entry: the F
 // gradient rows of a group are contiguous, so the write is coalesced.
 // ---------------------------------------------------------------------------
-// Phase timers (builds with -DLFMMI_PHASE_TIMERS only; the library as shipped carries
-// none of this): thread 0 of every workgroup adds the clocks between two marks to a
-// counter per phase, which lfmmi_phase_timers_read() copies out.
-#ifdef LFMMI_PHASE_TIMERS
-__device__ unsigned long long g_phase_clocks[16];
-#define LFMMI_MARK_BEGIN unsigned long long mark_last_ = __builtin_amdgcn_s_memtime();
-#define LFMMI_MARK(i)                                                              \
-    {                                                                              \
-        const unsigned long long mark_now_ = __builtin_amdgcn_s_memtime();         \
-        if (threadIdx.x == 0) atomicAdd(&g_phase_clocks[i], mark_now_ - mark_last_); \
-        mark_last_ = mark_now_;                                                    \
-    }
-#define LFMMI_COUNT(i) \
-    if (threadIdx.x == 0) atomicAdd(&g_phase_clocks[i], 1ull);
-#else
-#define LFMMI_MARK_BEGIN
-#define LFMMI_MARK(i)
-#define LFMMI_COUNT(i)
-#endif
-
 template <int F, int STRIDE>
 __global__ void __launch_bounds__(1024) k_occ_planes(FbParams p, int groups_per_wg)
 {
@@ -2468,16 +2495,22 @@ hipError_t launch_forward_backward(const FbParams& p, const LaunchShape& shape,
 
 #ifdef LFMMI_PHASE_TIMERS
 // out[0..8]: clocks per phase of k_occ_planes summed over the workgroups since the
-// last reset; out[14]: workgroups, out[15]: frame groups. Synchronises the device.
-extern "C" int lfmmi_phase_timers_read(unsigned long long out[16], int reset)
+// last reset; out[14]: workgroups, out[15]: frame groups. out[16 + 4 w + q]: clocks of
+// phase q of a step in wave w of the register-resident k_rec, out[80]: steps (both
+// directions of every sequence). Synchronises the device.
+extern "C" int lfmmi_phase_timers_read(unsigned long long out[81], int reset)
 {
     if (hipDeviceSynchronize() != hipSuccess) return 1;
     if (hipMemcpyFromSymbol(out, HIP_SYMBOL(lfmmi::g_phase_clocks), sizeof(unsigned long long) * 16) !=
-        hipSuccess)
+            hipSuccess ||
+        hipMemcpyFromSymbol(out + 16, HIP_SYMBOL(lfmmi::g_rec_clocks), sizeof(unsigned long long) * 65) !=
+            hipSuccess)
         return 2;
     if (reset) {
-        const unsigned long long zero[16] = {};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(lfmmi::g_phase_clocks), zero, sizeof zero) != hipSuccess)
+        const unsigned long long zero[65] = {};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(lfmmi::g_phase_clocks), zero, sizeof(unsigned long long) * 16) !=
+                hipSuccess ||
+            hipMemcpyToSymbol(HIP_SYMBOL(lfmmi::g_rec_clocks), zero, sizeof zero) != hipSuccess)
             return 3;
     }
     return 0;
