@@ -557,9 +557,10 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int32_t>
                 cand.erase(cand.begin() + best);
             }
         }
-        // hill climbing on the sum of squared bank loads: move an arc of a row to
-        // another slot of that row (swapping with what is there); the (slot, bank)
-        // cells a move can touch are summed before and after it
+        // hill climbing on the modelled cycles of the two slots of a move (squared bank
+        // loads break ties: on their own they spread conflicts over many slots, each of
+        // which then costs a cycle, where the cycles want them in few): move an arc of a
+        // row to another slot of that row (swapping with what is there)
         auto squares = [&](int32_t i, int32_t other, int32_t j1, int32_t j2) {
             int32_t cells[8];
             int nc = 0;
@@ -584,7 +585,21 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int32_t>
             }
             return sum;
         };
-        const int64_t tries = 40LL * n;
+        // what the two slots of a move cost: per gather the most loaded bank (the cycles of
+        // the half-wave's read); squared loads break ties
+        auto slots_cost = [&](int32_t i, int32_t other, int32_t j1, int32_t j2) {
+            int64_t c = 0;
+            for (const int32_t j : {j1, j2}) {
+                int32_t mx_ = 0, my_ = 0;
+                for (int k = 0; k < kBanks; ++k) {
+                    mx_ = std::max(mx_, lx[(size_t)j * kBanks + k]);
+                    my_ = std::max(my_, ly[(size_t)j * kBanks + k]);
+                }
+                c += mx_ + my_;
+            }
+            return c * 1000000 + squares(i, other, j1, j2);
+        };
+        const int64_t tries = 80LL * n;
         for (int64_t it = 0; it < tries; ++it) {
             const int32_t i = (int32_t)rng.below((uint32_t)n);
             const int32_t r = pos_row[arcs[i]] % kHalf;
@@ -592,12 +607,12 @@ void order_slots(const std::vector<int32_t>& pos_row, const std::vector<int32_t>
             const int32_t j2 = (int32_t)rng.below((uint32_t)W);
             if (j1 == j2) continue;
             const int32_t other = table[(size_t)r * W + j2];
-            const int64_t before = squares(i, other, j1, j2);
+            const int64_t before = slots_cost(i, other, j1, j2);
             place(r, j1, i, -1);
             if (other >= 0) place(r, j2, other, -1);
             place(r, j2, i, 1);
             if (other >= 0) place(r, j1, other, 1);
-            if (squares(i, other, j1, j2) > before) {  // worse: back
+            if (slots_cost(i, other, j1, j2) > before) {  // worse: back
                 place(r, j2, i, -1);
                 if (other >= 0) place(r, j1, other, -1);
                 place(r, j1, i, 1);
