@@ -432,6 +432,48 @@ def test_config5_full_size_all_sequences():
     den.close(); num.close()
 
 
+def test_a_call_with_its_four_buckets_replays_from_a_hip_graph():
+    # after one eager call (workspace allocated, descriptors staged) a call enqueues kernels,
+    # event records and event waits only: captured on a side stream, with the buckets' streams
+    # joining the capture through the fork event, it replays with the same bits, also with
+    # eager calls and synchronisations between the replays
+    torch = _torch()
+    wl = workloads.make_workload(2, scale={"S": 600, "B": 12, "Tlo": 20, "Thi": 90})
+    h = binding.lfmmi_graph_create(wl["den"])
+    x = torch.from_numpy(wl["logits"]).cuda()
+    B, T, P = x.shape
+    objf = torch.empty(B, device="cuda")
+    grad = torch.empty((B, T, P), device="cuda")
+    status = torch.zeros(B, dtype=torch.int32, device="cuda")
+
+    def call():
+        binding.lfmmi_forward_backward(h, x, wl["lengths"], wl["leak"], 1.0, False, objf, grad, status)
+
+    call()
+    torch.cuda.synchronize()
+    want_o, want_g = objf.clone(), grad.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side, capture_error_mode="relaxed"):
+            call()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        objf.zero_()
+        grad.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(objf, want_o) and torch.equal(grad, want_g)
+        call()                      # eager work between the replays
+        torch.cuda.synchronize()
+    assert int(status.abs().max()) == 0
+    del graph
+    h.close()
+
+
 def test_autograd_wrapper_gives_the_objective_and_its_gradient():
     torch = _torch()
     from paper_2005_09824_amd import chain
