@@ -132,6 +132,11 @@ void lfmmi_graph_destroy(lfmmi_graph *graph);
  *            streams sit on hardware queues of their own; HIP gives a process four
  *            by default, GPU_MAX_HW_QUEUES, and streams that share one run their
  *            kernels one after the other. LFMMI_BUCKETS=1..4 sets the bucket count.)
+ *            A call with the same B, T and lengths as the handle's last one, and
+ *            a workspace that is large enough already, copies nothing from the
+ *            host and allocates nothing: it enqueues kernels, event records and
+ *            event waits only, and may be captured into a HIP graph (relaxed
+ *            capture mode, because of the library's own streams).
  * B == 0 or T == 0 with all lengths 0 are valid. Calls on one handle must be
  * ordered on one stream (they share the handle's workspace). The device the
  * graph was uploaded to must be the current one (LFMMI_ERR_INVALID_ARG if not).
