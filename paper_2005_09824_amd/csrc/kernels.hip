@@ -355,8 +355,11 @@ template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ double dpp_add(double v)
 {
     const long long bits = __double_as_longlong(v);
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, CTRL, ROW_MASK, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xf, false);
+    // (with every row written the old value is dead: bound_ctrl lets the compiler drop the
+    // two moves that would zero it first)
+    constexpr bool kAll = ROW_MASK == 0xf;
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, CTRL, ROW_MASK, 0xf, kAll);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xf, kAll);
     return v + __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
@@ -682,7 +685,10 @@ struct RecRegs {
         const Real cb = HAS_WB ? c : c * bconst;
         LFMMI_REC_MARK(0)  // head: last step's partial sums into this step's scalars
 
-        Real acc1 = 0, acc2 = 0, n = 0, s = 0;
+        // (the leak's accumulator stays fp32 also beside fp64 state values: a few products
+        // of fp32 numbers, which only ever meet the leak coefficient)
+        Real acc1 = 0, n = 0, s = 0;
+        float acc2 = 0;
         uint64_t left = mask;
         int next_close = left ? __builtin_ctzll(left) : 64;
         uint32_t row4 = row4_first;  // byte offset of this lane's row in a state vector
@@ -747,9 +753,9 @@ struct RecRegs {
                 acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i + 1 : 0], e1, acc2) : acc2 + t1;
             } else {  // products of the arc weight and the emission stay fp32
                 acc1 += (Real)t0 * x0;
-                acc2 += HAS_WB ? (Real)(wbr[HAS_WB ? i : 0] * e0) : (Real)t0;
+                acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i : 0], e0, acc2) : acc2 + t0;
                 acc1 += (Real)t1 * x1;
-                acc2 += HAS_WB ? (Real)(wbr[HAS_WB ? i + 1 : 0] * e1) : (Real)t1;
+                acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i + 1 : 0], e1, acc2) : acc2 + t1;
             }
             if (__builtin_expect(i + 1 == next_close, 0)) {  // wave-uniform: a slice ends
                 const bool hub_slice = HUBS && ((hubmask >> (i + 1)) & 1);
@@ -757,7 +763,7 @@ struct RecRegs {
                     acc1 = wave_sum_uniform(acc1);
                     acc2 = wave_sum_uniform(acc2);
                 }
-                Real v = inv * acc1 + cb * acc2;
+                Real v = inv * acc1 + cb * (Real)acc2;
                 if (hub_slice && lane != 0) v = 0;
                 lds_st(xn + row4, v);
                 *reinterpret_cast<Real*>(tr + row4) = v;
@@ -778,7 +784,7 @@ struct RecRegs {
             // is waited for. Loads past the wave's last pair repeat it (in bounds,
             // never used). Everything that steers the loop is wave-uniform.
             int i = first_streamed;  // even
-            Real a1 = acc1, a2 = acc2;
+            Real a1 = acc1, a2 = (Real)acc2;
             if (i < stream_end) {
                 // pair q of this lane: a wave-uniform base in scalar registers plus a
                 // 32-bit byte offset (one vector add per load, no 64-bit arithmetic)
