@@ -896,6 +896,90 @@ struct RecRegs {
         LFMMI_REC_MARK(3)  // wait for the other waves
     }
 
+    // A step for a wave that owns at most one slice of at most kLeanSlots slots (the
+    // per-utterance numerator graphs: a few hundred states, two or three arcs into each):
+    // the same protocol as step() - LDS map, partial sums, one barrier - and the same
+    // arithmetic in the same order, so the waves of a workgroup may take either (which one
+    // depends on the wave's own slice only); but straight-line: all gathers at once, one close, no
+    // slice masks, slot counts or priorities. Such steps are bound by the instructions a
+    // wave issues, not by LDS. a_row: the row's leak-dot weight (the closing slot's w).
+    static constexpr int kLeanSlots = 4;
+    template <int PAR>
+    __device__ __forceinline__ void step_lean(const int k, const int T, const int tid, const int lane,
+                                              const Real eps, const Real aconst, const Real bconst,
+                                              const bool owns, const float a_row,
+                                              const uint32_t row4_first, const uint32_t part_at)
+    {
+        LFMMI_REC_BEGIN
+        constexpr uint32_t xc = PAR ? 0u : kRegX1, xn = PAR ? kRegX1 : 0u;
+        constexpr uint32_t yc = PAR ? 0u : (kRegY1 - kRegY0), yn = PAR ? kRegY1 : kRegY0;
+        constexpr uint32_t pc = kRegPart + (PAR ? 0u : 32u * kRB), pn = kRegPart + (PAR ? 32u * kRB : 0u);
+        Real pv = lds_ldr<Real>(pc + (lane & (HAS_WB ? 31 : 15)) * kRB);
+        Real xv[kLeanSlots];
+        float ev[kLeanSlots];
+#pragma unroll
+        for (int i = 0; i < kLeanSlots; ++i) {
+            xv[i] = lds_ldr<Real>(xc + x_at(i));
+            ev[i] = lds_ld(yc + y_at(i));
+        }
+        asm volatile("" ::: "memory");  // nothing else moves ahead of these reads
+        pv = row16_allsum(pv);
+        const Real N = lane_value(pv, 0);
+        const Real Sd = HAS_WB ? lane_value(pv, 16) : aconst * N;
+        Real inv = 0;
+        if (N > 0) {
+            if constexpr (sizeof(Real) == 4) {
+                inv = __builtin_amdgcn_rcpf(N);
+                inv = fmaf(fmaf(-N, inv, 1.f), inv, inv);
+            } else {
+                inv = __builtin_amdgcn_rcp((double)N);
+                inv = fma(fma(-N, inv, (Real)1), inv, inv);
+                inv = fma(fma(-N, inv, (Real)1), inv, inv);
+            }
+        }
+        const Real c = eps * Sd * inv;
+        const Real cb = HAS_WB ? c : c * bconst;
+        LFMMI_REC_MARK(0)
+        store_y(yn);
+        load_y();
+        if (tid == 0) {
+            *sN = N;
+            *sS = Sd;
+        }
+        Real acc1 = 0;
+        float acc2 = 0;
+#pragma unroll
+        for (int i = 0; i < kLeanSlots; ++i) {
+            const float t = wr[i] * ev[i];
+            if constexpr (sizeof(Real) == 4) acc1 = fmaf(t, xv[i], acc1);
+            else acc1 += (Real)t * xv[i];
+            acc2 = HAS_WB ? fmaf(wbr[HAS_WB ? i : 0], ev[i], acc2) : acc2 + t;
+        }
+        Real n = 0, s = 0;
+        if (owns) {
+            const Real v = inv * acc1 + cb * (Real)acc2;
+            lds_st(xn + row4_first, v);
+            *reinterpret_cast<Real*>(reinterpret_cast<char*>(trow) + row4_first) = v;
+            n = v;
+            if (HAS_WB) s = (Real)a_row * v;
+        }
+        LFMMI_REC_MARK(1)
+        if constexpr (HAS_WB) {
+            const Real ns = half_wave_sums(n, s);
+            if ((lane & 31) == 31) lds_st(pn + part_at, ns);
+        } else {
+            const Real ns = wave_sum_lane63(n);
+            if (lane == 63) lds_st(pn + part_at, ns);
+        }
+        if (k + 2 < T) e2 += estep;
+        trow += tstep;
+        sN += sstep;
+        sS += sstep;
+        LFMMI_REC_MARK(2)
+        __syncthreads();
+        LFMMI_REC_MARK(3)
+    }
+
     __device__ __forceinline__ void run(const FbParams& p, const SeqDesc& sd, const OrdDesc& od,
                                         const int b, const int dir, unsigned char* lds)
     {
@@ -1042,6 +1126,20 @@ struct RecRegs {
         // where this lane's end-of-step sum goes: n of wave w at value w, s at 16 + w
         const uint32_t part_at = ((uint32_t)wave + (HAS_WB && lane >= 32 ? 16u : 0u)) * kRB;
         int k = 1;
+        if constexpr (!HYBRID && !HUBS && NSLOT <= 8 && NSLOT >= kLeanSlots) {
+            if (s1 - s0 <= 1 && nsl <= kLeanSlots) {  // wave-uniform
+                const bool owns = s1 > s0;
+                float a_row = 0.f;  // the closing slot is the slice's last
+                if (HAS_WB && owns) a_row = nsl == 2 ? wr[1] : wr[kLeanSlots - 1];
+                for (; k + 1 <= T; k += 2) {
+                    step_lean<1>(k, T, tid, lane, eps, aconst, bconst, owns, a_row, row4_first, part_at);
+                    step_lean<0>(k + 1, T, tid, lane, eps, aconst, bconst, owns, a_row, row4_first, part_at);
+                }
+                if (k <= T)
+                    step_lean<1>(k, T, tid, lane, eps, aconst, bconst, owns, a_row, row4_first, part_at);
+                k = T + 1;
+            }
+        }
         for (; k + 1 <= T; k += 2) {
             step<1>(k, T, tid, lane, eps, aconst, bconst, mask, hubmask, row4_first, part_at, nsl,
                     sl_stream, s1, first + nsl, so, hub_bits, hub, rec_pairs(p, od, 0));
